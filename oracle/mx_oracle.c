@@ -1,0 +1,395 @@
+/*
+ * mx_oracle.c -- CPU oracle for the MXFP4 quantized linear layer of TetraJet
+ * (arxiv 2502.20853).  TEST INFRASTRUCTURE ONLY: see mx_oracle.h.
+ *
+ * Every step is written the way the paper states it, one element at a time.
+ * Precision: the scaled value y = x / S is formed in FP32 (exact except when it
+ * underflows below 2^-126, where IEEE gradual underflow applies); every
+ * comparison that picks a code is then evaluated exactly in FP64 on that FP32
+ * value.  The EMA update is FP32.  Matrix products are FP64.
+ *
+ * Build: gcc -O2 -std=c11 -fopenmp -ffp-contract=off -fPIC -shared mx_oracle.c -lm
+ */
+#include "mx_oracle.h"
+
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* ---------------------------------------------------------------- E2M1 ---- */
+
+/* Sec. 3.1: E2M1 has 2 exponent bits and 1 mantissa bit, Q_p = 6.  With
+ * exponent bias 1 the eight magnitudes are: subnormal 0, 0.5; then
+ * (1 + m/2) * 2^(e-1) for e = 1, 2, 3. */
+static const double E2M1_MAG[8] = {0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0};
+
+double orc_e2m1_value(int code)
+{
+    double m = E2M1_MAG[code & 7];
+    return (code & 8) ? -m : m;
+}
+
+/* index (0..7) of an E2M1 magnitude */
+static int mag_index(double m)
+{
+    for (int t = 0; t < 8; ++t)
+        if (E2M1_MAG[t] == m) return t;
+    return 7;
+}
+
+/* Two consecutive E2M1 magnitudes with m1 <= a <= m2 (Sec. 3.2).  If a is at
+ * or beyond the largest magnitude the bracket collapses to m1 = m2 = 6. */
+static void bracket(double a, double* m1, double* m2)
+{
+    int i = 0;
+    for (int t = 0; t < 8; ++t)
+        if (E2M1_MAG[t] <= a) i = t;
+    *m1 = E2M1_MAG[i];
+    *m2 = (i < 7) ? E2M1_MAG[i + 1] : E2M1_MAG[7];
+}
+
+/* -------------------------------------------------------------- Philox ---- */
+
+static void mulhilo32(uint32_t a, uint32_t b, uint32_t* hi, uint32_t* lo)
+{
+    uint64_t p = (uint64_t)a * (uint64_t)b;
+    *hi = (uint32_t)(p >> 32);
+    *lo = (uint32_t)p;
+}
+
+void orc_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    const uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;   /* round multipliers   */
+    const uint32_t W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;   /* key schedule (Weyl) */
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        uint32_t hi0, lo0, hi1, lo1;
+        mulhilo32(M0, c0, &hi0, &lo0);
+        mulhilo32(M1, c2, &hi1, &lo1);
+        uint32_t n0 = hi1 ^ c1 ^ k0;
+        uint32_t n1 = lo1;
+        uint32_t n2 = hi0 ^ c3 ^ k1;
+        uint32_t n3 = lo0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += W0; k1 += W1;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+uint32_t orc_sr_bits(uint64_t seed, uint32_t tensor_id, uint64_t e)
+{
+    uint64_t blk = e >> 3;
+    uint32_t ctr[4] = {(uint32_t)blk, (uint32_t)(blk >> 32), tensor_id, 0u};
+    uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    uint32_t w[4];
+    orc_philox4x32_10(ctr, key, w);
+    unsigned j = (unsigned)(e & 7u);
+    return (w[j >> 1] >> (16u * (j & 1u))) & 0xFFFFu;
+}
+
+/* ------------------------------------------------------- shared exponent -- */
+
+int orc_shared_exponent(float M, int scale_mode)
+{
+    double Mt = (M > 0.0f) ? (double)M : 1e-8;   /* epsilon for the all-zero group */
+    int guess;
+    (void)frexp(Mt, &guess);                     /* only a starting point */
+    int s;
+    if (scale_mode == ORC_SCALE_TRUNCFREE) {
+        /* s = ceil(log2(2*Mt/(Qp-Qn))) = ceil(log2(Mt/6)): the smallest
+         * integer s with Mt <= 6 * 2^s.  ldexp and the comparison are exact. */
+        s = guess;
+        while (ldexp(6.0, s) < Mt) ++s;
+        while (ldexp(6.0, s - 1) >= Mt) --s;
+    } else {
+        /* floor(log2 Mt): the largest integer e with 2^e <= Mt; s = e - E_max. */
+        int e = guess;
+        while (ldexp(1.0, e) > Mt) --e;
+        while (ldexp(1.0, e + 1) <= Mt) ++e;
+        s = e - 2;
+    }
+    if (s > 127) s = 127;
+    if (s < -127) s = -127;
+    return s;
+}
+
+/* x / S with S = 2^s, formed in FP32 (one IEEE rounding, only on underflow). */
+static float scale_to_group(float x, int s, int scale_mode)
+{
+    float y = ldexpf(x, -s);
+    if (scale_mode == ORC_SCALE_FLOOR) {
+        /* Eq. 2's scale can leave |y| > Q_p: "exceeding values will be truncated" */
+        if (y > 6.0f) y = 6.0f;
+        if (y < -6.0f) y = -6.0f;
+    }
+    return y;
+}
+
+/* -------------------------------------------------------------- rounding -- */
+
+int orc_round_rtn(float y)
+{
+    int sign = signbit(y) ? 8 : 0;
+    double yd = (double)y, m1, m2, q1, q2;
+    bracket(fabs(yd), &m1, &m2);
+    if (!sign) { q1 = m1;  q2 = m2;  }           /* q1 < q2 in signed terms */
+    else       { q1 = -m2; q2 = -m1; }
+    double pick = (fabs(yd - q1) < fabs(yd - q2)) ? q1 : q2;
+    return sign | mag_index(fabs(pick));
+}
+
+int orc_round_sr(float y, uint32_t r16)
+{
+    /* round_S: xi ~ U(-D/2, D/2), D = q2 - q1; q1 iff y + xi < (q1+q2)/2, so
+     * P(q2) = (y - q1)/D and P(q1) = (q2 - y)/D.  On the magnitude a = |y| both
+     * signs read: the larger magnitude m2 is taken with probability
+     * p = (a - m1)/(m2 - m1).  The uniform variate is r16/65536. */
+    int sign = signbit(y) ? 8 : 0;
+    double a = fabs((double)y), m1, m2;
+    bracket(a, &m1, &m2);
+    double p = (m2 > m1) ? (a - m1) / (m2 - m1) : 0.0;
+    int up = ((double)r16 < 65536.0 * p);
+    return sign | mag_index(up ? m2 : m1);
+}
+
+int orc_round_ema(float y, float z)
+{
+    int sign = signbit(y) ? 8 : 0;
+    double yd = (double)y, zd = (double)z, m1, m2, q1, q2;
+    bracket(fabs(yd), &m1, &m2);
+    if (m1 == fabs(yd)) return sign | mag_index(m1);   /* y is an E2M1 value */
+    if (!sign) { q1 = m1;  q2 = m2;  }
+    else       { q1 = -m2; q2 = -m1; }
+    double pick = (fabs(zd - q1) < fabs(zd - q2)) ? q1 : q2;
+    return sign | mag_index(fabs(pick));
+}
+
+/* ------------------------------------------------------------ quantizers -- */
+
+static float group_amax(const float* x, int64_t stride)
+{
+    float M = 0.0f;
+    for (int i = 0; i < 32; ++i) {
+        float a = fabsf(x[i * stride]);
+        if (a > M) M = a;
+    }
+    return M;
+}
+
+static void put_code(uint8_t* codes, int64_t idx, int code)
+{
+    uint8_t* b = &codes[idx >> 1];
+    if (idx & 1) *b = (uint8_t)((*b & 0x0F) | (code << 4));
+    else         *b = (uint8_t)((*b & 0xF0) | code);
+}
+
+static int get_code(const uint8_t* codes, int64_t idx)
+{
+    uint8_t b = codes[idx >> 1];
+    return (idx & 1) ? (b >> 4) : (b & 0x0F);
+}
+
+void orc_quantize(const float* src, int64_t rows, int64_t cols, int64_t ld,
+                  uint8_t* codes, uint8_t* scales,
+                  int round, int scale_mode,
+                  uint64_t seed, uint32_t tensor_id, uint64_t index_base)
+{
+    int64_t groups = cols / 32;
+    #pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        for (int64_t g = 0; g < groups; ++g) {
+            const float* x = src + r * ld + 32 * g;
+            float M = group_amax(x, 1);
+            int s = orc_shared_exponent(M, scale_mode);
+            scales[r * groups + g] = (uint8_t)(s + 127);
+            for (int i = 0; i < 32; ++i) {
+                int64_t c = 32 * g + i;
+                float y = scale_to_group(x[i], s, scale_mode);
+                int code;
+                if (round == ORC_ROUND_SR) {
+                    uint64_t e = index_base + (uint64_t)r * (uint64_t)cols + (uint64_t)c;
+                    code = orc_round_sr(y, orc_sr_bits(seed, tensor_id, e));
+                } else {
+                    code = orc_round_rtn(y);
+                }
+                put_code(codes + r * (cols / 2), c, code);
+            }
+        }
+    }
+}
+
+void orc_dequantize(const uint8_t* codes, const uint8_t* scales,
+                    int64_t rows, int64_t cols, double* out)
+{
+    int64_t groups = cols / 32;
+    #pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t c = 0; c < cols; ++c) {
+            int s = (int)scales[r * groups + c / 32] - 127;
+            out[r * cols + c] = ldexp(orc_e2m1_value(get_code(codes + r * (cols / 2), c)), s);
+        }
+}
+
+void orc_quantize_transposed(const float* src, int64_t rows, int64_t cols, int64_t ld,
+                  uint8_t* codes_t, uint8_t* scales_t,
+                  int round_t, uint32_t tensor_id_t, int pre_quant,
+                  uint8_t* codes_row, uint8_t* scales_row,
+                  int round_row, uint32_t tensor_id_row,
+                  const uint8_t* row_codes_in, const uint8_t* row_scales_in,
+                  int scale_mode, uint64_t seed, uint64_t index_base)
+{
+    /* 1. the 1x32 quantizer (forward operand), if asked for or needed */
+    uint8_t* tmp_codes = NULL;
+    uint8_t* tmp_scales = NULL;
+    const uint8_t* rc = row_codes_in;
+    const uint8_t* rs = row_scales_in;
+    int need_row = (codes_row != NULL) || (pre_quant && rc == NULL);
+    if (need_row) {
+        uint8_t* oc = codes_row;
+        uint8_t* os = scales_row;
+        if (oc == NULL) {
+            oc = tmp_codes = (uint8_t*)malloc((size_t)(rows * (cols / 2)));
+            os = tmp_scales = (uint8_t*)malloc((size_t)(rows * (cols / 32)));
+        }
+        if (rc != NULL) {            /* caller supplied the row result: pass it on */
+            memcpy(oc, rc, (size_t)(rows * (cols / 2)));
+            memcpy(os, rs, (size_t)(rows * (cols / 32)));
+        } else {
+            orc_quantize(src, rows, cols, ld, oc, os, round_row, scale_mode,
+                         seed, tensor_id_row, index_base);
+            rc = oc; rs = os;
+        }
+    }
+
+    /* 2. the matrix the 32x1 quantizer sees: src, or dequant(Q_row(src)) */
+    float* V = (float*)malloc((size_t)(rows * cols) * sizeof(float));
+    if (pre_quant) {
+        double* dq = (double*)malloc((size_t)(rows * cols) * sizeof(double));
+        orc_dequantize(rc, rs, rows, cols, dq);
+        for (int64_t t = 0; t < rows * cols; ++t) V[t] = (float)dq[t];   /* exact */
+        free(dq);
+    } else {
+        for (int64_t i = 0; i < rows; ++i)
+            for (int64_t c = 0; c < cols; ++c) V[i * cols + c] = src[i * ld + c];
+    }
+
+    /* 3. 32x1 groups: 32 consecutive rows of one column; result stored transposed */
+    int64_t groups = rows / 32;
+    #pragma omp parallel for schedule(static)
+    for (int64_t c = 0; c < cols; ++c) {
+        for (int64_t g = 0; g < groups; ++g) {
+            const float* x = V + (32 * g) * cols + c;
+            float M = group_amax(x, cols);
+            int s = orc_shared_exponent(M, scale_mode);
+            scales_t[c * groups + g] = (uint8_t)(s + 127);
+            for (int t = 0; t < 32; ++t) {
+                int64_t i = 32 * g + t;
+                float y = scale_to_group(x[t * cols], s, scale_mode);
+                int code;
+                if (round_t == ORC_ROUND_SR) {
+                    uint64_t e = index_base + (uint64_t)i * (uint64_t)cols + (uint64_t)c;
+                    code = orc_round_sr(y, orc_sr_bits(seed, tensor_id_t, e));
+                } else {
+                    code = orc_round_rtn(y);
+                }
+                put_code(codes_t + c * (rows / 2), i, code);
+            }
+        }
+    }
+    free(V);
+    free(tmp_codes);
+    free(tmp_scales);
+}
+
+void orc_ema_weight_quant(const float* w, float* w_ema, float beta, int update_ema,
+                  int64_t rows, int64_t cols, int64_t ld,
+                  uint8_t* codes, uint8_t* scales, int scale_mode)
+{
+    int64_t groups = cols / 32;
+    #pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        for (int64_t g = 0; g < groups; ++g) {
+            const float* x = w + r * ld + 32 * g;
+            float* ema = w_ema + r * ld + 32 * g;
+            /* Eq. 8: W_EMA <- beta * W_EMA + (1 - beta) * W, in FP32 */
+            for (int i = 0; i < 32; ++i) {
+                if (update_ema == 1) {
+                    float one_minus_beta = 1.0f - beta;
+                    float t = one_minus_beta * x[i];
+                    ema[i] = fmaf(beta, ema[i], t);
+                } else if (update_ema == 2) {
+                    ema[i] = x[i];
+                }
+            }
+            /* Algorithm 1: the scale comes from the weight block itself */
+            float M = group_amax(x, 1);
+            int s = orc_shared_exponent(M, scale_mode);
+            scales[r * groups + g] = (uint8_t)(s + 127);
+            for (int i = 0; i < 32; ++i) {
+                float y = scale_to_group(x[i], s, scale_mode);
+                float z = ldexpf(ema[i], -s);
+                put_code(codes + r * (cols / 2), 32 * g + i, orc_round_ema(y, z));
+            }
+        }
+    }
+}
+
+/* ------------------------------------------------------------------ GEMM -- */
+
+void orc_gemm_f64(const uint8_t* a_codes, const uint8_t* a_scales,
+                  const uint8_t* b_codes, const uint8_t* b_scales,
+                  int64_t m, int64_t n, int64_t k, double* c)
+{
+    double* A = (double*)malloc((size_t)(m * k) * sizeof(double));
+    double* B = (double*)malloc((size_t)(n * k) * sizeof(double));
+    orc_dequantize(a_codes, a_scales, m, k, A);
+    orc_dequantize(b_codes, b_scales, n, k, B);
+    #pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < m; ++i)
+        for (int64_t j = 0; j < n; ++j) {
+            double acc = 0.0;
+            for (int64_t t = 0; t < k; ++t) acc += A[i * k + t] * B[j * k + t];
+            c[i * n + j] = acc;
+        }
+    free(A);
+    free(B);
+}
+
+void orc_gemm_f64_sampled(const uint8_t* a_codes, const uint8_t* a_scales,
+                  const uint8_t* b_codes, const uint8_t* b_scales,
+                  int64_t m, int64_t n, int64_t k,
+                  const int64_t* ii, const int64_t* jj, int64_t nsamp,
+                  double* out, double* abs_out)
+{
+    (void)m; (void)n;
+    int64_t groups = k / 32;
+    #pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < nsamp; ++t) {
+        const uint8_t* ac = a_codes + ii[t] * (k / 2);
+        const uint8_t* bc = b_codes + jj[t] * (k / 2);
+        const uint8_t* as = a_scales + ii[t] * groups;
+        const uint8_t* bs = b_scales + jj[t] * groups;
+        double acc = 0.0, aacc = 0.0;
+        for (int64_t d = 0; d < k; ++d) {
+            double a = ldexp(orc_e2m1_value(get_code(ac, d)), (int)as[d / 32] - 127);
+            double b = ldexp(orc_e2m1_value(get_code(bc, d)), (int)bs[d / 32] - 127);
+            acc += a * b;
+            aacc += fabs(a * b);
+        }
+        out[t] = acc;
+        if (abs_out) abs_out[t] = aacc;
+    }
+}
+
+int orc_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

@@ -1,0 +1,134 @@
+/*
+ * mx_oracle.h -- CPU oracle for the MXFP4 quantized linear layer of TetraJet
+ * (arxiv 2502.20853).
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT PRODUCT CODE.  It is a plain, slow,
+ * step-by-step implementation of what the paper defines, written so that a
+ * reader can check it against the paper by eye.  Only the tests, the smoke
+ * check and the benchmark's "cpu_baseline" leg may call it.  It shares no
+ * code, table or constant generator with the HIP path.
+ *
+ * Parity status: every function below is pinned by tests that do not run the
+ * function's own formula a second time (worked values printed in the paper,
+ * closed forms, invariants, brute force).  The one exception is the Philox
+ * stream, whose constants the paper does not give: it is pinned against the
+ * published Philox4x32-10 known-answer vectors and a second big-integer
+ * implementation in the tests.
+ *
+ * Notation follows the paper: a group is 32 consecutive elements along the
+ * contraction dimension, S = 2^s its shared scale, P_i the E2M1 element,
+ * Q_p = 6, Q_n = -6, M the group's largest absolute value.
+ *
+ * Packed layout used everywhere (Sec. 3.1 "stored as ({P_i}, S)"; nibble order
+ * is this build's choice): for a row-major [rows x cols] matrix quantized
+ * along its columns,
+ *     codes [r][j] = code(r, 2j) | code(r, 2j+1) << 4      (cols/2 bytes per row)
+ *     scales[r][g] = s + 127   for group g = cols [32g, 32g+32)  (cols/32 bytes)
+ * An E2M1 code is sign<<3 | exponent<<1 | mantissa; magnitudes of codes 0..7
+ * are 0, 0.5, 1, 1.5, 2, 3, 4, 6.
+ */
+#ifndef MX_ORACLE_H
+#define MX_ORACLE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { ORC_ROUND_RTN = 0, ORC_ROUND_SR = 1 };
+enum { ORC_SCALE_TRUNCFREE = 0, ORC_SCALE_FLOOR = 1 };
+
+/* Value of one E2M1 code (0..15).  Sec. 3.1: E2M1 with Q_p = 6. */
+double orc_e2m1_value(int code);
+
+/* Philox4x32 with 10 rounds (Salmon et al., SC'11).  ctr and out are 4 words,
+ * key is 2 words. */
+void orc_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);
+
+/* The 16 random bits that decide the stochastic rounding of the element with
+ * global index e of tensor tensor_id under seed.  One Philox call, with
+ * counter (e>>3 low, e>>3 high, tensor_id, 0) and key (seed low, seed high),
+ * serves 8 consecutive elements: element e uses 16-bit field (e & 7), fields
+ * numbered from the low half of word 0. */
+uint32_t orc_sr_bits(uint64_t seed, uint32_t tensor_id, uint64_t e);
+
+/* Shared exponent s of a group whose largest absolute value is M.
+ * TRUNCFREE: s = ceil(log2(2*Mt/(Q_p-Q_n))) (Sec. 3.2, truncation-free scaling);
+ * FLOOR:     s = floor(log2 Mt) - E_max, E_max = 2 (Eq. 2);
+ * Mt = M if M > 0 else 1e-8; the result is clamped to |s| <= 127 (Sec. 3.1). */
+int orc_shared_exponent(float M, int scale_mode);
+
+/* round_D of Sec. 3.2 applied to the scaled value y (|y| <= 6): returns the
+ * E2M1 code; the sign bit of the code is the sign bit of y. */
+int orc_round_rtn(float y);
+
+/* round_S of Sec. 3.2 with the 16 random bits r16 (0..65535): with a = |y|,
+ * m1 <= a <= m2 the bracketing magnitudes and p = (a-m1)/(m2-m1), the larger
+ * magnitude is taken iff r16 < 65536*p. */
+int orc_round_sr(float y, uint32_t r16);
+
+/* Q-EMA decision (Algorithm 1) for one element: y = w/S proposes the bracket
+ * (q1, q2), z = w_ema/S picks the nearer (q1 iff strictly nearer).  If y is
+ * itself an E2M1 value the result is y. */
+int orc_round_ema(float y, float z);
+
+/* Quantize src[rows x cols] (row stride ld elements) in 1x32 groups along the
+ * columns.  Element (r, c) has global index index_base + r*cols + c. */
+void orc_quantize(const float* src, int64_t rows, int64_t cols, int64_t ld,
+                  uint8_t* codes, uint8_t* scales,
+                  int round, int scale_mode,
+                  uint64_t seed, uint32_t tensor_id, uint64_t index_base);
+
+/* Quantize src[rows x cols] in 32x1 groups (32 consecutive rows of one
+ * column) and store the result transposed: codes_t[cols x rows/2],
+ * scales_t[cols x rows/32].
+ * pre_quant = 1: the quantizer's input is dequant(Q_row(src)) (double
+ *   quantization, Sec. 3.3), where Q_row is the 1x32 quantizer with rounding
+ *   round_row / tensor_id_row, or the given (row_codes_in, row_scales_in) when
+ *   those are non-NULL.
+ * codes_row/scales_row, when non-NULL, receive the 1x32 result as well.
+ * Element (i, c) keeps its source index index_base + i*cols + c in both
+ * quantizers. */
+void orc_quantize_transposed(const float* src, int64_t rows, int64_t cols, int64_t ld,
+                  uint8_t* codes_t, uint8_t* scales_t,
+                  int round_t, uint32_t tensor_id_t, int pre_quant,
+                  uint8_t* codes_row, uint8_t* scales_row,
+                  int round_row, uint32_t tensor_id_row,
+                  const uint8_t* row_codes_in, const uint8_t* row_scales_in,
+                  int scale_mode, uint64_t seed, uint64_t index_base);
+
+/* Q-EMA (Eq. 8 and Algorithm 1).  update_ema: 0 leave w_ema, 1 set
+ * w_ema = beta*w_ema + (1-beta)*w first, 2 set w_ema = w first.  Then quantize
+ * w in 1x32 groups with the scale of w and the rounding of orc_round_ema. */
+void orc_ema_weight_quant(const float* w, float* w_ema, float beta, int update_ema,
+                  int64_t rows, int64_t cols, int64_t ld,
+                  uint8_t* codes, uint8_t* scales, int scale_mode);
+
+/* X_i = P_i * 2^s (Sec. 3.1), exact in double. */
+void orc_dequantize(const uint8_t* codes, const uint8_t* scales,
+                  int64_t rows, int64_t cols, double* out);
+
+/* C[m x n] = A[m x k] * B[n x k]^T on the dequantized operands, FP64
+ * (Sec. 3.3: the three products all take this form once the second operand is
+ * stored along its contraction dimension). */
+void orc_gemm_f64(const uint8_t* a_codes, const uint8_t* a_scales,
+                  const uint8_t* b_codes, const uint8_t* b_scales,
+                  int64_t m, int64_t n, int64_t k, double* c);
+
+/* Same product, only at the nsamp entries (ii[t], jj[t]); also returns
+ * sum_k |A||B| per entry in abs_out (may be NULL). */
+void orc_gemm_f64_sampled(const uint8_t* a_codes, const uint8_t* a_scales,
+                  const uint8_t* b_codes, const uint8_t* b_scales,
+                  int64_t m, int64_t n, int64_t k,
+                  const int64_t* ii, const int64_t* jj, int64_t nsamp,
+                  double* out, double* abs_out);
+
+/* Threads the parallel loops use. */
+int orc_num_threads(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

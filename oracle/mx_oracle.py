@@ -1,0 +1,222 @@
+"""ctypes loader for the CPU oracle (mx_oracle.c).
+
+TEST INFRASTRUCTURE ONLY.  Nothing in the product package may import this
+module; only tests, the smoke check and the benchmark's cpu_baseline leg do.
+All arrays are numpy; FP32 in, uint8 codes/scales and FP64 products out.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "mx_oracle.c")
+_LIB = os.path.join(_HERE, "libmx_oracle.so")
+
+ROUND_RTN, ROUND_SR = 0, 1
+SCALE_TRUNCFREE, SCALE_FLOOR = 0, 1
+
+
+def build(force=False):
+    """Compile mx_oracle.c with gcc into libmx_oracle.so next to it."""
+    if (not force and os.path.exists(_LIB)
+            and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC)
+            and os.path.getmtime(_LIB) >= os.path.getmtime(os.path.join(_HERE, "mx_oracle.h"))):
+        return _LIB
+    cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-ffp-contract=off", "-fPIC", "-shared",
+           "-Wall", "-Wextra", _SRC, "-o", _LIB, "-lm"]
+    subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+_u8p = ctypes.POINTER(ctypes.c_uint8)
+_f32p = ctypes.POINTER(ctypes.c_float)
+_f64p = ctypes.POINTER(ctypes.c_double)
+_i64p = ctypes.POINTER(ctypes.c_int64)
+_u32p = ctypes.POINTER(ctypes.c_uint32)
+_i64, _u64, _u32, _int = ctypes.c_int64, ctypes.c_uint64, ctypes.c_uint32, ctypes.c_int
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = ctypes.CDLL(build())
+        L.orc_e2m1_value.restype = ctypes.c_double
+        L.orc_e2m1_value.argtypes = [_int]
+        L.orc_philox4x32_10.restype = None
+        L.orc_philox4x32_10.argtypes = [_u32p, _u32p, _u32p]
+        L.orc_sr_bits.restype = _u32
+        L.orc_sr_bits.argtypes = [_u64, _u32, _u64]
+        L.orc_shared_exponent.restype = _int
+        L.orc_shared_exponent.argtypes = [ctypes.c_float, _int]
+        L.orc_round_rtn.restype = _int
+        L.orc_round_rtn.argtypes = [ctypes.c_float]
+        L.orc_round_sr.restype = _int
+        L.orc_round_sr.argtypes = [ctypes.c_float, _u32]
+        L.orc_round_ema.restype = _int
+        L.orc_round_ema.argtypes = [ctypes.c_float, ctypes.c_float]
+        L.orc_quantize.restype = None
+        L.orc_quantize.argtypes = [_f32p, _i64, _i64, _i64, _u8p, _u8p, _int, _int, _u64, _u32, _u64]
+        L.orc_quantize_transposed.restype = None
+        L.orc_quantize_transposed.argtypes = [_f32p, _i64, _i64, _i64, _u8p, _u8p, _int, _u32, _int,
+                                              _u8p, _u8p, _int, _u32, _u8p, _u8p, _int, _u64, _u64]
+        L.orc_ema_weight_quant.restype = None
+        L.orc_ema_weight_quant.argtypes = [_f32p, _f32p, ctypes.c_float, _int, _i64, _i64, _i64,
+                                           _u8p, _u8p, _int]
+        L.orc_dequantize.restype = None
+        L.orc_dequantize.argtypes = [_u8p, _u8p, _i64, _i64, _f64p]
+        L.orc_gemm_f64.restype = None
+        L.orc_gemm_f64.argtypes = [_u8p, _u8p, _u8p, _u8p, _i64, _i64, _i64, _f64p]
+        L.orc_gemm_f64_sampled.restype = None
+        L.orc_gemm_f64_sampled.argtypes = [_u8p, _u8p, _u8p, _u8p, _i64, _i64, _i64,
+                                           _i64p, _i64p, _i64, _f64p, _f64p]
+        L.orc_num_threads.restype = _int
+        L.orc_num_threads.argtypes = []
+        _lib = L
+    return _lib
+
+
+def _p(a, typ):
+    return a.ctypes.data_as(typ) if a is not None else typ()
+
+
+def _f32(a):
+    a = np.asarray(a)
+    assert a.dtype == np.float32 and a.ndim == 2 and a.strides[1] == 4
+    return a
+
+
+def _u8(a):
+    a = np.ascontiguousarray(a)
+    assert a.dtype == np.uint8
+    return a
+
+
+def e2m1_value(code):
+    return lib().orc_e2m1_value(int(code))
+
+
+def philox4x32_10(ctr, key):
+    c = (ctypes.c_uint32 * 4)(*[int(x) & 0xFFFFFFFF for x in ctr])
+    k = (ctypes.c_uint32 * 2)(*[int(x) & 0xFFFFFFFF for x in key])
+    o = (ctypes.c_uint32 * 4)()
+    lib().orc_philox4x32_10(c, k, o)
+    return [int(x) for x in o]
+
+
+def sr_bits(seed, tensor_id, e):
+    return int(lib().orc_sr_bits(int(seed), int(tensor_id), int(e)))
+
+
+def shared_exponent(M, scale_mode=SCALE_TRUNCFREE):
+    return int(lib().orc_shared_exponent(float(M), int(scale_mode)))
+
+
+def round_rtn(y):
+    return int(lib().orc_round_rtn(float(y)))
+
+
+def round_sr(y, r16):
+    return int(lib().orc_round_sr(float(y), int(r16)))
+
+
+def round_ema(y, z):
+    return int(lib().orc_round_ema(float(y), float(z)))
+
+
+def quantize(src, round=ROUND_RTN, scale_mode=SCALE_TRUNCFREE, seed=0, tensor_id=0, index_base=0):
+    """1x32 groups along the columns -> (codes[rows, cols/2], scales[rows, cols/32])."""
+    src = _f32(src)
+    rows, cols = src.shape
+    assert cols % 32 == 0
+    ld = src.strides[0] // 4
+    codes = np.zeros((rows, cols // 2), np.uint8)
+    scales = np.zeros((rows, cols // 32), np.uint8)
+    lib().orc_quantize(_p(src, _f32p), rows, cols, ld, _p(codes, _u8p), _p(scales, _u8p),
+                       int(round), int(scale_mode), int(seed), int(tensor_id), int(index_base))
+    return codes, scales
+
+
+def quantize_transposed(src, round_t=ROUND_SR, tensor_id_t=0, pre_quant=1, want_row=True,
+                        round_row=ROUND_RTN, tensor_id_row=0, row_in=None,
+                        scale_mode=SCALE_TRUNCFREE, seed=0, index_base=0):
+    """32x1 groups down the rows, stored transposed.
+
+    Returns (codes_t[cols, rows/2], scales_t[cols, rows/32], codes_row, scales_row);
+    the last two are None unless want_row.
+    """
+    src = _f32(src)
+    rows, cols = src.shape
+    assert rows % 32 == 0
+    ld = src.strides[0] // 4
+    codes_t = np.zeros((cols, rows // 2), np.uint8)
+    scales_t = np.zeros((cols, rows // 32), np.uint8)
+    codes_row = scales_row = None
+    if want_row:
+        codes_row = np.zeros((rows, cols // 2), np.uint8)
+        scales_row = np.zeros((rows, cols // 32), np.uint8)
+    rc_in = rs_in = None
+    if row_in is not None:
+        rc_in, rs_in = _u8(row_in[0]), _u8(row_in[1])
+    lib().orc_quantize_transposed(_p(src, _f32p), rows, cols, ld, _p(codes_t, _u8p), _p(scales_t, _u8p),
+                                  int(round_t), int(tensor_id_t), int(pre_quant),
+                                  _p(codes_row, _u8p), _p(scales_row, _u8p),
+                                  int(round_row), int(tensor_id_row),
+                                  _p(rc_in, _u8p), _p(rs_in, _u8p),
+                                  int(scale_mode), int(seed), int(index_base))
+    return codes_t, scales_t, codes_row, scales_row
+
+
+def ema_weight_quant(w, w_ema, beta=0.998, update_ema=1, scale_mode=SCALE_TRUNCFREE):
+    """Q-EMA.  w_ema (float32, same shape as w) is updated in place."""
+    w = _f32(w)
+    assert w_ema.dtype == np.float32 and w_ema.shape == w.shape and w_ema.strides == w.strides
+    rows, cols = w.shape
+    ld = w.strides[0] // 4
+    codes = np.zeros((rows, cols // 2), np.uint8)
+    scales = np.zeros((rows, cols // 32), np.uint8)
+    lib().orc_ema_weight_quant(_p(w, _f32p), _p(w_ema, _f32p), float(beta), int(update_ema),
+                               rows, cols, ld, _p(codes, _u8p), _p(scales, _u8p), int(scale_mode))
+    return codes, scales
+
+
+def dequantize(codes, scales):
+    codes, scales = _u8(codes), _u8(scales)
+    rows, cols = codes.shape[0], codes.shape[1] * 2
+    out = np.zeros((rows, cols), np.float64)
+    lib().orc_dequantize(_p(codes, _u8p), _p(scales, _u8p), rows, cols, _p(out, _f64p))
+    return out
+
+
+def gemm_f64(a_codes, a_scales, b_codes, b_scales):
+    """C[m, n] = A[m, k] . B[n, k]^T on dequantized operands, FP64."""
+    a_codes, a_scales, b_codes, b_scales = map(_u8, (a_codes, a_scales, b_codes, b_scales))
+    m, k = a_codes.shape[0], a_codes.shape[1] * 2
+    n = b_codes.shape[0]
+    assert b_codes.shape[1] * 2 == k
+    c = np.zeros((m, n), np.float64)
+    lib().orc_gemm_f64(_p(a_codes, _u8p), _p(a_scales, _u8p), _p(b_codes, _u8p), _p(b_scales, _u8p),
+                       m, n, k, _p(c, _f64p))
+    return c
+
+
+def gemm_f64_sampled(a_codes, a_scales, b_codes, b_scales, ii, jj):
+    """Entries (ii[t], jj[t]) of the same product, plus sum_k |a||b| for each."""
+    a_codes, a_scales, b_codes, b_scales = map(_u8, (a_codes, a_scales, b_codes, b_scales))
+    m, k = a_codes.shape[0], a_codes.shape[1] * 2
+    n = b_codes.shape[0]
+    ii = np.ascontiguousarray(ii, np.int64)
+    jj = np.ascontiguousarray(jj, np.int64)
+    out = np.zeros(ii.shape[0], np.float64)
+    aout = np.zeros(ii.shape[0], np.float64)
+    lib().orc_gemm_f64_sampled(_p(a_codes, _u8p), _p(a_scales, _u8p), _p(b_codes, _u8p), _p(b_scales, _u8p),
+                               m, n, k, _p(ii, _i64p), _p(jj, _i64p), ii.shape[0],
+                               _p(out, _f64p), _p(aout, _f64p))
+    return out, aout
+
+
+def num_threads():
+    return int(lib().orc_num_threads())

@@ -1,0 +1,515 @@
+"""Pins for the CPU oracle: every check here compares the oracle with something
+that is not the oracle's own formula -- values the paper prints, closed forms,
+invariants, brute force, special cases that reduce to numpy routines."""
+import json
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+PAPER = json.load(open(os.path.join(GOLD, "paper_worked_values.json")))
+GRID = [0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0]
+SIGNED_GRID = sorted(set([-g for g in GRID] + GRID))
+
+
+def f32(x):
+    return float(np.float32(x))
+
+
+# ------------------------------------------------------------------ E2M1 ----
+
+def test_e2m1_table_from_bit_fields(orc):
+    # Sec. 3.1: 1 sign, 2 exponent, 1 mantissa bit; bias 1; Q_p = 6
+    for code in range(16):
+        s, e, m = code >> 3, (code >> 1) & 3, code & 1
+        mag = m * 0.5 if e == 0 else (1 + m / 2) * 2.0 ** (e - 1)
+        assert orc.e2m1_value(code) == (-mag if s else mag)
+    vals = [orc.e2m1_value(c) for c in range(16)]
+    assert max(vals) == PAPER["format"]["Qp"] and min(vals) == PAPER["format"]["Qn"]
+    # largest binade starts at 2^E_max
+    assert orc.e2m1_value(6) == 2.0 ** PAPER["emax"]["E_max"]
+
+
+def test_threshold_example_adjacent_values(orc):
+    # Sec. 4.1: -0.75 is the midpoint of the adjacent FP4 values -1 and -0.5
+    t = PAPER["threshold_example"]
+    vals = sorted(set(orc.e2m1_value(c) for c in range(16)))
+    i = vals.index(t["q1"])
+    assert vals[i + 1] == t["q2"] and (t["q1"] + t["q2"]) / 2 == t["thrd"]
+    # just either side of the threshold; the threshold itself goes to q2 (strict <)
+    assert orc.e2m1_value(orc.round_rtn(-0.7501)) == -1.0
+    assert orc.e2m1_value(orc.round_rtn(-0.7499)) == -0.5
+    assert orc.e2m1_value(orc.round_rtn(-0.75)) == -0.5
+
+
+# --------------------------------------------------------- shared exponent --
+
+def test_scale_worked_examples(orc):
+    fl, tf = PAPER["floor_scale_example"], PAPER["truncfree_scale_example"]
+    assert 2.0 ** orc.shared_exponent(fl["M"], orc.SCALE_FLOOR) == fl["S"]
+    assert 2.0 ** orc.shared_exponent(tf["M"], orc.SCALE_TRUNCFREE) == tf["S"]
+    # the whole quantizer on that group: 31 is stored as 6*4 under Eq. 2 and as 4*8 truncation-free
+    x = np.zeros((1, 32), np.float32)
+    x[0, 5] = 31.0
+    x[0, 6] = -31.0
+    c, s = orc.quantize(x, scale_mode=orc.SCALE_FLOOR)
+    d = orc.dequantize(c, s)
+    assert d[0, 5] == fl["stored_value_of_M"] * fl["S"] and d[0, 6] == -d[0, 5]
+    c, s = orc.quantize(x, scale_mode=orc.SCALE_TRUNCFREE)
+    d = orc.dequantize(c, s)
+    assert s[0, 0] == 127 + 3 and d[0, 5] == 32.0 and d[0, 6] == -32.0  # 3.875 -> 4
+
+
+def _exact_ceil_log2(fr):
+    """ceil(log2(fr)) for a positive Fraction, by integer arithmetic only."""
+    n, d = fr.numerator, fr.denominator
+    s = n.bit_length() - d.bit_length()          # 2^(s-1) < fr < 2^(s+1)
+    while Fraction(2) ** s < fr:
+        s += 1
+    while Fraction(2) ** (s - 1) >= fr:
+        s -= 1
+    return s
+
+
+def _exact_floor_log2(fr):
+    return -_exact_ceil_log2(1 / fr)
+
+
+def test_shared_exponent_vs_exact_rational_and_bit_form(orc):
+    rng = np.random.default_rng(1)
+    bits = rng.integers(0x00800000, 0x7F000000, size=4000, dtype=np.uint32)
+    # add values on and next to the 1.5 * 2^e boundary and exact powers of two
+    special = []
+    for e in range(-120, 120, 7):
+        for m in (0x000000, 0x000001, 0x3FFFFF, 0x400000, 0x400001, 0x7FFFFF):
+            special.append(((e + 127) << 23) | m)
+    bits = np.concatenate([bits, np.array(special, np.uint32)])
+    vals = bits.view(np.float32)
+    for u, v in zip(bits.tolist(), vals.tolist()):
+        fr = Fraction(v)
+        tf = _exact_ceil_log2(fr / 6)
+        fl = _exact_floor_log2(fr) - 2
+        assert orc.shared_exponent(v, orc.SCALE_TRUNCFREE) == max(-127, min(127, tf))
+        assert orc.shared_exponent(v, orc.SCALE_FLOOR) == max(-127, min(127, fl))
+        # closed form on the FP32 fields: 6 = 1.5 * 2^2
+        e, m = (u >> 23) - 127, u & 0x7FFFFF
+        assert tf == e - 2 + (1 if m > 0x400000 else 0)
+        assert fl == e - 2
+
+
+def test_shared_exponent_edges(orc):
+    # all-zero group: epsilon = 1e-8 -> ceil(log2(1e-8/6)) = floor(log2 1e-8) - 2 = -29
+    eps = PAPER["zero_group_epsilon"]["epsilon"]
+    assert math.ceil(math.log2(eps / 6)) == -29 and math.floor(math.log2(eps)) - 2 == -29
+    assert orc.shared_exponent(0.0, orc.SCALE_TRUNCFREE) == -29
+    assert orc.shared_exponent(0.0, orc.SCALE_FLOOR) == -29
+    # |s| <= 127 (Sec. 3.1): smallest subnormal would need s = -151
+    tiny = float(np.float32(1e-45))
+    assert orc.shared_exponent(tiny, orc.SCALE_TRUNCFREE) == -127
+    assert orc.shared_exponent(tiny, orc.SCALE_FLOOR) == -127
+    big = float(np.finfo(np.float32).max)
+    assert orc.shared_exponent(big, orc.SCALE_TRUNCFREE) == 126
+    assert orc.shared_exponent(big, orc.SCALE_FLOOR) == 125
+    # exactly 6 * 2^k sits at the top of the range, 2^k at the bottom of Eq. 2's
+    assert orc.shared_exponent(6.0, orc.SCALE_TRUNCFREE) == 0
+    assert orc.shared_exponent(f32(6.0000005), orc.SCALE_TRUNCFREE) == 1
+    assert orc.shared_exponent(4.0, orc.SCALE_FLOOR) == 0
+    assert orc.shared_exponent(f32(3.9999998), orc.SCALE_FLOOR) == -1
+
+
+def test_range_invariants_per_group(orc):
+    rng = np.random.default_rng(2)
+    x = (rng.standard_normal((64, 256)) * np.exp(rng.uniform(-20, 20, (64, 1)))).astype(np.float32)
+    M = np.abs(x.reshape(64, 8, 32)).max(-1).astype(np.float64)
+    _, s = orc.quantize(x, scale_mode=orc.SCALE_TRUNCFREE)
+    r = M / 2.0 ** (s.astype(np.int64) - 127)
+    assert np.all(r <= 6.0) and np.all(r > 3.0)       # Q_n <= M/S <= Q_p, and the ceiling is tight
+    _, s = orc.quantize(x, scale_mode=orc.SCALE_FLOOR)
+    r = M / 2.0 ** (s.astype(np.int64) - 127)
+    assert np.all(r >= 4.0) and np.all(r < 8.0)       # [2^Emax, 2^(Emax+1))
+
+
+# -------------------------------------------------------------- round_D -----
+
+def test_rtn_tie_vectors(orc):
+    # strict "<" in round_D sends midpoints to q2, the upper neighbour
+    ties = {0.25: 0.5, 0.75: 1.0, 1.25: 1.5, 1.75: 2.0, 2.5: 3.0, 3.5: 4.0, 5.0: 6.0,
+            -0.25: 0.0, -0.75: -0.5, -1.25: -1.0, -1.75: -1.5, -2.5: -2.0, -3.5: -3.0, -5.0: -4.0}
+    for y, q in ties.items():
+        assert orc.e2m1_value(orc.round_rtn(y)) == q, y
+    for g in SIGNED_GRID:                              # grid points are fixed points
+        assert orc.e2m1_value(orc.round_rtn(g)) == g
+    assert orc.round_rtn(-0.0) == 8 and orc.round_rtn(0.0) == 0
+    assert orc.round_rtn(-0.1) == 8                    # sign bit follows the input
+
+
+def test_rtn_brute_force_all_bf16(orc):
+    # every bf16 value in [-6, 6]: nearest of the 15 values, ties to the larger value
+    u = np.arange(65536, dtype=np.uint32) << 16
+    y = u.view(np.float32)
+    y = y[np.isfinite(y) & (np.abs(y) <= 6.0)]
+    grid = np.array(SIGNED_GRID)
+    for v in y.tolist():
+        d = np.abs(grid - v)
+        best = grid[np.flatnonzero(d == d.min()).max()]
+        code = orc.round_rtn(v)
+        assert orc.e2m1_value(code) == best, v
+        assert (code >> 3) == (1 if math.copysign(1.0, v) < 0 else 0)
+
+
+# -------------------------------------------------------------- round_S -----
+
+def test_sr_exhaustive_counts(orc):
+    # over all 65536 draws the larger magnitude is taken exactly ceil(65536 p) times
+    for y in (0.1, 0.25, 0.3, 1.2, 1.999, 2.75, 4.5, 5.999, -0.3, -2.2, -5.0, 1e-6, 3.0, -6.0, 0.0):
+        y = f32(y)
+        a = abs(y)
+        m1 = max(g for g in GRID if g <= a)
+        m2 = min([g for g in GRID if g > m1] or [m1])
+        p = Fraction(a) - Fraction(m1)
+        p = p / Fraction(m2 - m1) if m2 > m1 else Fraction(0)
+        ups = 0
+        for r in range(65536):
+            v = orc.e2m1_value(orc.round_sr(y, r))
+            assert abs(v) in (m1, m2) and (v == 0 or (v < 0) == (y < 0))
+            ups += abs(v) == m2 and m2 > m1
+        assert ups == math.ceil(65536 * p), y
+    assert orc.round_sr(-0.0, 0) == 8
+
+
+def test_sr_extreme_draws(orc):
+    assert orc.e2m1_value(orc.round_sr(f32(1e-30), 0)) == 0.5      # r = 0 rounds up iff p > 0
+    assert orc.e2m1_value(orc.round_sr(2.0, 0)) == 2.0              # p = 0 never moves
+    assert orc.e2m1_value(orc.round_sr(f32(2.99999), 65535)) == 3.0  # p > 65535/65536
+    assert orc.e2m1_value(orc.round_sr(f32(2.9999), 65535)) == 2.0
+
+
+def test_sr_unbiased_with_philox_stream(orc):
+    # E[round_S(y)] = y (Sec. 3.2), driven by the real random stream
+    n = 200000
+    for y in (0.37, 1.1, 2.6, -4.9, -0.05):
+        y = f32(y)
+        acc = 0.0
+        for e in range(n):
+            acc += orc.e2m1_value(orc.round_sr(y, orc.sr_bits(123, 7, e)))
+        a = abs(y)
+        m1 = max(g for g in GRID if g <= a)
+        m2 = min(g for g in GRID if g > m1)
+        p = (a - m1) / (m2 - m1)
+        tol = 5 * math.sqrt(p * (1 - p) / n) * (m2 - m1) + (m2 - m1) / 65536
+        assert abs(acc / n - y) <= tol, (y, acc / n)
+
+
+# --------------------------------------------------------------- Philox -----
+
+def _philox_py(ctr, key):
+    M0, M1, W0, W1 = 0xD2511F53, 0xCD9E8D57, 0x9E3779B9, 0xBB67AE85
+    c = list(ctr)
+    k = list(key)
+    mask = 0xFFFFFFFF
+    for _ in range(10):
+        p0, p1 = M0 * c[0], M1 * c[2]
+        c = [(p1 >> 32) ^ c[1] ^ k[0], p1 & mask, (p0 >> 32) ^ c[3] ^ k[1], p0 & mask]
+        k = [(k[0] + W0) & mask, (k[1] + W1) & mask]
+    return c
+
+
+def test_philox_known_answers(orc):
+    kat = json.load(open(os.path.join(GOLD, "philox4x32_10_kat.json")))
+    for v in kat["vectors"]:
+        ctr = [int(x, 16) for x in v["ctr"]]
+        key = [int(x, 16) for x in v["key"]]
+        out = [int(x, 16) for x in v["out"]]
+        assert orc.philox4x32_10(ctr, key) == out
+        assert _philox_py(ctr, key) == out
+
+
+def test_philox_vs_bigint_and_fields(orc):
+    rng = np.random.default_rng(3)
+    for _ in range(2000):
+        ctr = [int(x) for x in rng.integers(0, 2**32, 4)]
+        key = [int(x) for x in rng.integers(0, 2**32, 2)]
+        assert orc.philox4x32_10(ctr, key) == _philox_py(ctr, key)
+    # element e -> call e>>3, 16-bit field e&7, counting from the low half of word 0
+    seed, tid = 0x1234567890ABCDEF, 42
+    for e in (0, 1, 7, 8, 9, 12345, 2**35 + 5, 2**40 + 3):
+        w = _philox_py([(e >> 3) & 0xFFFFFFFF, (e >> 3) >> 32, tid, 0], [seed & 0xFFFFFFFF, seed >> 32])
+        j = e & 7
+        assert orc.sr_bits(seed, tid, e) == (w[j >> 1] >> (16 * (j & 1))) & 0xFFFF
+    # different tensor ids and seeds give different streams
+    a = [orc.sr_bits(1, 1, e) for e in range(64)]
+    assert a != [orc.sr_bits(1, 2, e) for e in range(64)]
+    assert a != [orc.sr_bits(2, 1, e) for e in range(64)]
+
+
+def test_philox_fields_uniform(orc):
+    n = 1 << 16
+    r = np.array([orc.sr_bits(5, 9, e) for e in range(n)])
+    assert r.min() >= 0 and r.max() <= 65535
+    hist = np.bincount(r >> 8, minlength=256)          # 256 bins, expect n/256 each
+    chi2 = ((hist - n / 256) ** 2 / (n / 256)).sum()
+    assert chi2 < 350                                  # 255 dof: mean 255, sd ~22.6
+    assert abs(r.mean() - 32767.5) < 5 * 65536 / math.sqrt(12 * n)
+
+
+# ------------------------------------------------------------ quantizers ----
+
+def test_pack_layout_by_construction(orc):
+    # a group that is already on the grid with max 6 -> s = 0 and codes known by hand
+    mags = [0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0]
+    row = np.array(mags + [-m for m in mags] + mags + [-m for m in mags], np.float32)
+    x = np.stack([row, row * 4.0, row[::-1] * 0.125])
+    codes, scales = orc.quantize(x)
+    assert scales.tolist() == [[127], [129], [124]]
+    want0 = list(range(8)) + list(range(8, 16)) + list(range(8)) + list(range(8, 16))
+    want = [want0, want0, want0[::-1]]
+    for r in range(3):
+        got = []
+        for b in codes[r].tolist():
+            got += [b & 15, b >> 4]                     # low nibble = even element
+        assert got == want[r]
+    assert np.array_equal(orc.dequantize(codes, scales), x.astype(np.float64))
+
+
+def test_quantize_error_bound_and_scale_equivariance(orc):
+    rng = np.random.default_rng(4)
+    x = (rng.standard_normal((16, 128)) * np.exp(rng.uniform(-8, 8, (16, 128)))).astype(np.float32)
+    for mode in (orc.SCALE_TRUNCFREE, orc.SCALE_FLOOR):
+        codes, scales = orc.quantize(x, scale_mode=mode)
+        S = np.repeat(2.0 ** (scales.astype(np.int64) - 127), 32, axis=1)
+        y = x.astype(np.float64) / S
+        if mode == orc.SCALE_FLOOR:
+            assert np.abs(y).max() > 6.0               # Eq. 2 does overflow the range ...
+            y = np.clip(y, -6, 6)                      # ... and truncates
+        q = orc.dequantize(codes, scales) / S
+        # nearest grid value: the error is at most half the local spacing
+        spacing = np.where(np.abs(y) < 2, 0.5, np.where(np.abs(y) < 4, 1.0, 2.0))
+        assert np.all(np.abs(q - y) <= spacing / 2)
+        # multiplying by 2^7 moves every scale byte by 7 and no code
+        c2, s2 = orc.quantize(x * np.float32(128.0), scale_mode=mode)
+        assert np.array_equal(c2, codes) and np.array_equal(s2.astype(int), scales.astype(int) + 7)
+        # SR result is one of the two neighbours of y
+        c3, s3 = orc.quantize(x, round=orc.ROUND_SR, scale_mode=mode, seed=11, tensor_id=3)
+        q3 = orc.dequantize(c3, s3) / S
+        assert np.array_equal(s3, scales) and np.all(np.abs(q3 - y) < spacing + 1e-12)
+
+
+def test_quantize_zero_group_and_ld(orc):
+    x = np.zeros((2, 64), np.float32)
+    x[1, 40] = -3.0
+    codes, scales = orc.quantize(x)
+    assert scales.tolist() == [[98, 98], [98, 127 - 1]]   # -29; 3/6 -> s = -1
+    assert not codes[0].any() and orc.dequantize(codes, scales)[1, 40] == -3.0
+    # a strided view gives the same bytes as its contiguous copy
+    big = np.random.default_rng(5).standard_normal((8, 96)).astype(np.float32)
+    v = big[:, 32:]
+    a = orc.quantize(v, round=orc.ROUND_SR, seed=3, tensor_id=1)
+    b = orc.quantize(np.ascontiguousarray(v), round=orc.ROUND_SR, seed=3, tensor_id=1)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+def test_quantize_sr_decisions_follow_element_index(orc):
+    # compose the whole quantizer from its pinned parts on a small matrix
+    rng = np.random.default_rng(6)
+    x = rng.standard_normal((4, 64)).astype(np.float32)
+    seed, tid, base = 99, 5, 8 * 1000
+    codes, scales = orc.quantize(x, round=orc.ROUND_SR, seed=seed, tensor_id=tid, index_base=base)
+    for r in range(4):
+        for c in range(64):
+            s = int(scales[r, c // 32]) - 127
+            y = f32(np.ldexp(x[r, c], -s))
+            want = orc.round_sr(y, orc.sr_bits(seed, tid, base + r * 64 + c))
+            got = (codes[r, c // 2] >> (4 * (c & 1))) & 15
+            assert got == want
+
+
+def test_transposed_reduces_to_row_quantizer_of_transpose(orc):
+    rng = np.random.default_rng(7)
+    x = (rng.standard_normal((64, 96)) * 3).astype(np.float32)
+    ct, st, _, _ = orc.quantize_transposed(x, round_t=orc.ROUND_RTN, pre_quant=0, want_row=False)
+    c, s = orc.quantize(np.ascontiguousarray(x.T))
+    assert ct.shape == (96, 32) and st.shape == (96, 2)
+    assert np.array_equal(ct, c) and np.array_equal(st, s)
+
+
+def test_transposed_sr_uses_source_index(orc):
+    rng = np.random.default_rng(8)
+    x = rng.standard_normal((32, 40)).astype(np.float32)
+    seed, tid, base = 7, 6, 64
+    ct, st, _, _ = orc.quantize_transposed(x, round_t=orc.ROUND_SR, tensor_id_t=tid, pre_quant=0,
+                                           want_row=False, seed=seed, index_base=base)
+    for c in range(40):
+        s = int(st[c, 0]) - 127
+        for i in range(32):
+            y = f32(np.ldexp(x[i, c], -s))
+            want = orc.round_sr(y, orc.sr_bits(seed, tid, base + i * 40 + c))
+            assert (ct[c, i // 2] >> (4 * (i & 1))) & 15 == want
+
+
+def test_double_quantization_is_composition(orc):
+    rng = np.random.default_rng(9)
+    x = (rng.standard_normal((64, 64)) * 2).astype(np.float32)
+    x[:, 3] *= 20
+    ct, st, cr, sr = orc.quantize_transposed(x, round_t=orc.ROUND_SR, tensor_id_t=6, pre_quant=1,
+                                             round_row=orc.ROUND_RTN, tensor_id_row=1, seed=5)
+    c1, s1 = orc.quantize(x)
+    assert np.array_equal(cr, c1) and np.array_equal(sr, s1)
+    xq = orc.dequantize(c1, s1).astype(np.float32)
+    ct2, st2, _, _ = orc.quantize_transposed(xq, round_t=orc.ROUND_SR, tensor_id_t=6, pre_quant=0,
+                                             want_row=False, seed=5)
+    assert np.array_equal(ct, ct2) and np.array_equal(st, st2)
+    # handing the row result in gives the same bytes
+    ct3, st3, _, _ = orc.quantize_transposed(x, round_t=orc.ROUND_SR, tensor_id_t=6, pre_quant=1,
+                                             want_row=False, row_in=(c1, s1), seed=5)
+    assert np.array_equal(ct, ct3) and np.array_equal(st, st3)
+    # without double quantization the result differs (Microscaling's design, Eqs. 6-7)
+    ct4, _, _, _ = orc.quantize_transposed(x, round_t=orc.ROUND_SR, tensor_id_t=6, pre_quant=0,
+                                           want_row=False, seed=5)
+    assert not np.array_equal(ct, ct4)
+
+
+# ----------------------------------------------------------------- Q-EMA ----
+
+def test_qema_equals_rtn_when_ema_is_weight(orc):
+    rng = np.random.default_rng(10)
+    w = (rng.standard_normal((32, 128)) * 0.02).astype(np.float32)
+    ema = np.zeros_like(w)
+    c, s = orc.ema_weight_quant(w, ema, update_ema=2)
+    c0, s0 = orc.quantize(w)
+    assert np.array_equal(ema, w) and np.array_equal(c, c0) and np.array_equal(s, s0)
+    ema = rng.standard_normal(w.shape).astype(np.float32)
+    c, s = orc.ema_weight_quant(w, ema, beta=0.0, update_ema=1)   # beta = 0: ema <- w
+    assert np.array_equal(ema, w) and np.array_equal(c, c0)
+
+
+def test_qema_micro_example_and_bracket(orc):
+    # around the -0.75 threshold of Sec. 4.1: latent -0.74 alone rounds to -0.5,
+    # an EMA latent of -0.80 pulls it to -1
+    assert orc.e2m1_value(orc.round_rtn(f32(-0.74))) == -0.5
+    assert orc.e2m1_value(orc.round_ema(f32(-0.74), f32(-0.80))) == -1.0
+    assert orc.e2m1_value(orc.round_ema(f32(-0.74), f32(-0.70))) == -0.5
+    assert orc.e2m1_value(orc.round_ema(f32(-0.74), f32(-0.75))) == -0.5   # tie -> q2
+    assert orc.e2m1_value(orc.round_ema(f32(0.74), f32(0.75))) == 1.0      # tie -> q2
+    # EMA outside the bracket picks the nearer end; never leaves the bracket of w/S
+    assert orc.e2m1_value(orc.round_ema(f32(2.2), f32(-5.0))) == 2.0
+    assert orc.e2m1_value(orc.round_ema(f32(2.2), f32(5.0))) == 3.0
+    assert orc.round_ema(f32(-0.3), f32(4.0)) == 8                         # -0
+    # a latent weight that is already an E2M1 value stays
+    for g in SIGNED_GRID:
+        assert orc.e2m1_value(orc.round_ema(g, 100.0)) == g
+        assert orc.e2m1_value(orc.round_ema(g, -100.0)) == g
+    rng = np.random.default_rng(11)
+    w = (rng.standard_normal((16, 64)) * 0.02).astype(np.float32)
+    ema = (w + rng.standard_normal(w.shape).astype(np.float32) * 0.004).astype(np.float32)
+    c, s = orc.ema_weight_quant(w, ema.copy(), update_ema=0)
+    c0, s0 = orc.quantize(w)
+    assert np.array_equal(s, s0)
+    S = np.repeat(2.0 ** (s.astype(np.int64) - 127), 32, axis=1)
+    y = w / S
+    q = orc.dequantize(c, s) / S
+    lo = np.array([max(g for g in SIGNED_GRID if g <= v) for v in y.ravel()]).reshape(y.shape)
+    hi = np.array([min(g for g in SIGNED_GRID if g >= v) for v in y.ravel()]).reshape(y.shape)
+    assert np.all((q == lo) | (q == hi))
+    z = ema / S
+    pick_hi = np.abs(z - lo) >= np.abs(z - hi)
+    assert np.array_equal(q, np.where(pick_hi, hi, lo))
+    assert not np.array_equal(c, c0)                   # and it does differ from plain RTN
+
+
+def test_ema_update_closed_form(orc):
+    # constant weight: ema_t = w + beta^t (ema_0 - w)
+    beta = PAPER["ema_beta"]["beta"]
+    w = np.full((1, 32), 0.5, np.float32)
+    ema = np.full((1, 32), -1.0, np.float32)
+    for _ in range(50):
+        orc.ema_weight_quant(w, ema, beta=beta, update_ema=1)
+    want = 0.5 + f32(beta) ** 50 * (-1.5)
+    assert np.allclose(ema, want, rtol=0, atol=2e-6)
+    e0 = ema.copy()
+    orc.ema_weight_quant(w, ema, beta=beta, update_ema=0)
+    assert np.array_equal(ema, e0)
+
+
+# ------------------------------------------------------------------ GEMM ----
+
+def test_gemm_vs_numpy_and_structure(orc):
+    rng = np.random.default_rng(12)
+    A = rng.standard_normal((5, 96)).astype(np.float32) * 3
+    B = rng.standard_normal((7, 96)).astype(np.float32) * 0.02
+    ac, as_ = orc.quantize(A)
+    bc, bs = orc.quantize(B)
+    C = orc.gemm_f64(ac, as_, bc, bs)
+    ref = orc.dequantize(ac, as_) @ orc.dequantize(bc, bs).T
+    assert C.shape == (5, 7) and np.allclose(C, ref, rtol=1e-13, atol=0)
+    # adding 1 to every scale byte of A doubles C exactly
+    C2 = orc.gemm_f64(ac, as_ + 1, bc, bs)
+    assert np.array_equal(C2, 2 * C)
+    ii = np.array([0, 4, 2, 3])
+    jj = np.array([6, 0, 5, 3])
+    v, av = orc.gemm_f64_sampled(ac, as_, bc, bs, ii, jj)
+    assert np.array_equal(v, C[ii, jj])
+    aref = np.abs(orc.dequantize(ac, as_)) @ np.abs(orc.dequantize(bc, bs)).T
+    assert np.allclose(av, aref[ii, jj], rtol=1e-13)
+
+
+def test_gemm_one_hot_by_hand(orc):
+    # A row i has a single 3 at k = 10*i+1, B row j a single -2 at k = 10*j+1, scales 2^1 and 2^-2
+    m, n, k = 3, 4, 64
+    ac = np.zeros((m, k // 2), np.uint8)
+    bc = np.zeros((n, k // 2), np.uint8)
+    for i in range(m):
+        ac[i, (10 * i + 1) // 2] = 5 << 4                # code 5 = 3.0 in the high nibble (odd k)
+    for j in range(n):
+        bc[j, (10 * j + 1) // 2] = 12 << 4               # code 12 = -2.0
+    as_ = np.full((m, 2), 128, np.uint8)
+    bs = np.full((n, 2), 125, np.uint8)
+    C = orc.gemm_f64(ac, as_, bc, bs)
+    want = np.zeros((m, n))
+    for i in range(min(m, n)):
+        want[i, i] = (3 * 2) * (-2 * 0.25)
+    assert np.array_equal(C, want)
+
+
+def test_layer_gradients_unbiased(orc):
+    # Sec. 3.4: E[Q3(dY) Q4(Q2(W))] = dY Q2(W) and E[Q5(dY^T) Q6(Q1(X))] = dY^T Q1(X)
+    rng = np.random.default_rng(13)
+    N = D = C = 32
+    X = rng.standard_normal((N, D)).astype(np.float32)
+    W = (rng.standard_normal((C, D)) * 0.02).astype(np.float32)
+    dY = (rng.standard_t(3, (N, C)) * 1e-3).astype(np.float32)
+    xq = orc.dequantize(*orc.quantize(X))
+    wq = orc.dequantize(*orc.quantize(W))
+    dX_ref = dY.astype(np.float64) @ wq
+    dW_ref = dY.astype(np.float64).T @ xq
+    trials = 300
+    dX = np.zeros((N, D))
+    dW = np.zeros((C, D))
+    sqX = np.zeros((N, D))
+    sqW = np.zeros((C, D))
+    for t in range(trials):
+        seed = 1000 + t
+        dyT_c, dyT_s, dy_c, dy_s = orc.quantize_transposed(
+            dY, round_t=orc.ROUND_SR, tensor_id_t=5, pre_quant=0, round_row=orc.ROUND_SR,
+            tensor_id_row=3, seed=seed)
+        wT_c, wT_s, _, _ = orc.quantize_transposed(W, round_t=orc.ROUND_SR, tensor_id_t=4, pre_quant=1,
+                                                   want_row=False, seed=seed)
+        xT_c, xT_s, _, _ = orc.quantize_transposed(X, round_t=orc.ROUND_SR, tensor_id_t=6, pre_quant=1,
+                                                   want_row=False, seed=seed)
+        a = orc.gemm_f64(dy_c, dy_s, wT_c, wT_s)        # dX = Q3(dY) . Q4(...)   [N x D], K = C
+        b = orc.gemm_f64(dyT_c, dyT_s, xT_c, xT_s)      # dW = Q5(dY^T) . Q6(...) [C x D], K = N
+        dX += a
+        dW += b
+        sqX += a * a
+        sqW += b * b
+    for mean, sq, ref in ((dX / trials, sqX / trials, dX_ref), (dW / trials, sqW / trials, dW_ref)):
+        sd = np.sqrt(np.maximum(sq - mean * mean, 0) / trials)
+        zscore = np.abs(mean - ref) / (sd + 1e-12 * np.abs(ref).max())
+        assert zscore.max() < 6.0 and np.mean(zscore < 3.0) > 0.98
+    # the deterministic Microscaling flow (Eqs. 6-7) is visibly biased on the same data
+    dyq = orc.dequantize(*orc.quantize(dY))
+    wT_c, wT_s, _, _ = orc.quantize_transposed(W, round_t=orc.ROUND_RTN, pre_quant=0, want_row=False)
+    bias = np.abs(dyq @ orc.dequantize(wT_c, wT_s).T - dX_ref).mean()
+    assert bias > 3 * np.abs(dX / trials - dX_ref).mean()
