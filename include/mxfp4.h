@@ -1,0 +1,168 @@
+/*
+ * mxfp4.h -- C ABI of the MI355X (gfx950) implementation of the MXFP4 quantized
+ * linear layer of TetraJet (arxiv 2502.20853): the six quantizers and three
+ * matrix products of Eqs. 3-5 (Sec. 3.3) and the EMA weight quantizer
+ * (Sec. 5, Algorithm 1).
+ *
+ * Conventions
+ *  - Every data pointer is a DEVICE pointer owned by the caller.  The library
+ *    never allocates, frees or synchronises; all work is enqueued on the HIP
+ *    stream passed as `stream` (a hipStream_t cast to void*, NULL = default
+ *    stream).  Outputs are valid once that stream has reached the call.
+ *  - Every function returns MX_OK or a negative MX_ERR_* code.  Arguments are
+ *    validated on the host before anything is launched, so a call that returns
+ *    an error other than MX_ERR_HIP has touched no memory.  MX_ERR_HIP means
+ *    the HIP runtime refused a launch; mx_last_hip_error() gives its code.
+ *  - Matrices are row-major; `ld` is the row stride in elements.
+ *  - Packed MXFP4 layout (Sec. 3.1: a group of 32 elements shares S = 2^s, each
+ *    element is an E2M1 value P_i, stored as ({P_i}, S)).  For a [rows x cols]
+ *    matrix grouped 1x32 along its columns:
+ *        codes [r][j] = code(r, 2j) | code(r, 2j+1) << 4     rows x cols/2  bytes
+ *        scales[r][g] = s + 127 for columns [32g, 32g+32)    rows x cols/32 bytes
+ *    both dense (no padding).  An E2M1 code is sign<<3 | exponent<<1 | mantissa
+ *    (magnitudes 0, .5, 1, 1.5, 2, 3, 4, 6); its sign bit is the sign bit of
+ *    the source element, also when the magnitude rounds to zero.  |s| <= 127,
+ *    so a scale byte of 255 is never produced.
+ *  - Inputs must be finite.  NaN/Inf give unspecified codes but never an
+ *    out-of-bounds access.  With pre_quant, |x| must stay below 2^126 so that
+ *    the dequantized intermediate is finite in FP32.
+ *  - Stochastic rounding draws 16 bits per element from Philox4x32-10 with key
+ *    (seed low, seed high) and counter (e>>3 low, e>>3 high, tensor_id, 0),
+ *    e = index_base + row*cols + col being the element's index in the SOURCE
+ *    tensor as passed (before any transposition); element e takes the 16-bit
+ *    field (e & 7), counted from the low half of output word 0.  The larger
+ *    magnitude of the bracketing E2M1 pair is taken iff field < 65536 * p,
+ *    p = (|y| - m1) / (m2 - m1)  (round_S of Sec. 3.2).  index_base must be a
+ *    multiple of 8 when stochastic rounding is used.
+ */
+#ifndef MXFP4_H
+#define MXFP4_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    MX_OK = 0,
+    MX_ERR_NULL = -1,       /* a required pointer is NULL, or an optional pair is half set */
+    MX_ERR_SHAPE = -2,      /* non-positive size, contraction/group dimension not a multiple of 32, ld < cols, size out of range */
+    MX_ERR_DTYPE = -3,      /* unknown dtype code */
+    MX_ERR_MODE = -4,       /* unknown rounding / scale / update mode, beta outside [0,1) */
+    MX_ERR_ALIGN = -5,      /* pointer, ld or index_base violates the stated alignment */
+    MX_ERR_WORKSPACE = -6,  /* workspace missing or smaller than mx_linear_workspace_bytes() */
+    MX_ERR_HIP = -7         /* HIP launch failure, see mx_last_hip_error() */
+};
+
+enum { MX_DTYPE_F32 = 0, MX_DTYPE_BF16 = 1 };
+enum { MX_ROUND_RTN = 0, MX_ROUND_SR = 1 };          /* round_D / round_S of Sec. 3.2 */
+enum { MX_SCALE_TRUNCFREE = 0, MX_SCALE_FLOOR = 1 }; /* truncation-free scaling of Sec. 3.2 / Eq. 2 */
+enum { MX_GEMM_FWD = 0, MX_GEMM_BWD_DX = 1, MX_GEMM_BWD_DW = 2 };
+
+/*
+ * Quantizers Q(1), Q(3) of Eqs. 3-4 (and Q(2) on W[C x D]): 1x32 groups along
+ * the columns of src[rows x cols].  Sec. 3.1 Eq. 1, Sec. 3.2.
+ *   src      device, dtype F32 or BF16, 16-byte aligned, ld % 8 == 0 (BF16) or ld % 4 == 0 (F32)
+ *   codes    device out, rows*cols/2 bytes, 4-byte aligned
+ *   scales   device out, rows*cols/32 bytes
+ *   cols % 32 == 0, ld >= cols; rows*cols < 2^35.
+ */
+int mx_quantize(const void* src, int dtype, int64_t rows, int64_t cols, int64_t ld,
+                uint8_t* codes, uint8_t* scales,
+                int round, int scale_mode,
+                uint64_t seed, uint32_t tensor_id, uint64_t index_base,
+                void* stream);
+
+/*
+ * Quantizers Q(2)/Q(4), Q(5), Q(6) of Eqs. 3-5: 32x1 groups (32 consecutive
+ * rows of one column of src[rows x cols]), result stored transposed so that it
+ * is contiguous along the contraction dimension of the product that consumes
+ * it ("Block Format", Sec. 3.3):
+ *        codes_t[cols x rows/2], scales_t[cols x rows/32]
+ *   pre_quant   0: quantize src itself;
+ *               1: quantize dequant(Q_row(src)) -- the "double quantization" of
+ *                  Sec. 3.3, Q(6)(Q(1)(X)) and Q(4)(Q(2)(W)).  Q_row is the 1x32
+ *                  quantizer with (round_row, tensor_id_row).
+ *   codes_row, scales_row   optional (both NULL or both set): also store the
+ *               1x32 result Q_row(src), computed in the same pass.
+ *   row_codes_in, row_scales_in   optional (both NULL or both set), only with
+ *               pre_quant = 1: take Q_row(src) as given (e.g. the output of
+ *               mx_ema_weight_quant) instead of computing it; src is then
+ *               unused and may be NULL, and codes_row/scales_row must be NULL.
+ *   rows % 32 == 0, cols % 32 == 0, ld >= cols; alignment as mx_quantize;
+ *   codes_t 4-byte aligned; rows*cols < 2^35.
+ */
+int mx_quantize_transposed(const void* src, int dtype, int64_t rows, int64_t cols, int64_t ld,
+                uint8_t* codes_t, uint8_t* scales_t,
+                int round_t, uint32_t tensor_id_t,
+                int pre_quant,
+                uint8_t* codes_row, uint8_t* scales_row,
+                int round_row, uint32_t tensor_id_row,
+                const uint8_t* row_codes_in, const uint8_t* row_scales_in,
+                int scale_mode, uint64_t seed, uint64_t index_base,
+                void* stream);
+
+/*
+ * The three products (Sec. 3.3, Eqs. 3-5), FP32 accumulation on the
+ * block-scaled FP4 matrix cores.  X[N x D], W[C x D], Y[N x C].  Every operand
+ * is packed along the product's contraction dimension, which must be a
+ * multiple of 32; the other two dimensions are arbitrary (>= 1).
+ * Operand code pointers must be 16-byte aligned and the contraction dimension
+ * a multiple of 32; out dtype F32 or BF16 (round to nearest even), ld >= row
+ * length.  workspace: device, 256-byte aligned, at least
+ * mx_linear_workspace_bytes(which, N, C, D) bytes (may be NULL when that is 0).
+ *
+ *   mx_linear_fwd     Y  = Q1(X) . Q2(W)^T        (Eq. 3)  xq[N x D/2] xs[N x D/32], wq[C x D/2] ws[C x D/32]
+ *   mx_linear_bwd_dx  dX = Q3(dY) . Q4(...)       (Eq. 4)  dyq[N x C/2] dys[N x C/32], wtq[D x C/2] wts[D x C/32]
+ *   mx_linear_bwd_dw  dW = Q5(dY^T) . Q6(...)     (Eq. 5)  dytq[C x N/2] dyts[C x N/32], xtq[D x N/2] xts[D x N/32]
+ */
+int mx_linear_fwd(const uint8_t* xq, const uint8_t* xs, const uint8_t* wq, const uint8_t* ws,
+                  int64_t N, int64_t C, int64_t D,
+                  void* y, int y_dtype, int64_t ldy,
+                  void* workspace, size_t workspace_bytes, void* stream);
+int mx_linear_bwd_dx(const uint8_t* dyq, const uint8_t* dys, const uint8_t* wtq, const uint8_t* wts,
+                  int64_t N, int64_t C, int64_t D,
+                  void* dx, int dx_dtype, int64_t lddx,
+                  void* workspace, size_t workspace_bytes, void* stream);
+int mx_linear_bwd_dw(const uint8_t* dytq, const uint8_t* dyts, const uint8_t* xtq, const uint8_t* xts,
+                  int64_t N, int64_t C, int64_t D,
+                  void* dw, int dw_dtype, int64_t lddw,
+                  void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Q-EMA (Sec. 5 Eq. 8, Algorithm 1): 1x32 quantizer of the weight w[rows x cols]
+ * whose scale comes from w and whose choice between the two E2M1 neighbours of
+ * w/S is the one nearer to w_ema/S (q1 iff strictly nearer).  A w/S that is
+ * itself an E2M1 value is kept.
+ *   w        device, F32 or BF16, row stride ld
+ *   w_ema    device, FP32, in/out, same shape and the same row stride ld
+ *   update_ema  0: use w_ema as is; 1: w_ema <- beta*w_ema + (1-beta)*w (FP32,
+ *               (1-beta)*w rounded, then one fused multiply-add), then quantize;
+ *               2: w_ema <- w, then quantize
+ *   0 <= beta < 1.  Shapes and alignment as mx_quantize; w_ema 16-byte aligned.
+ */
+int mx_ema_weight_quant(const void* w, int dtype, float* w_ema, float beta, int update_ema,
+                  int64_t rows, int64_t cols, int64_t ld,
+                  uint8_t* codes, uint8_t* scales, int scale_mode, void* stream);
+
+/* ---- helpers (not part of the path) ---- */
+
+/* Bytes of workspace the product `which` (MX_GEMM_*) needs for these sizes. */
+size_t mx_linear_workspace_bytes(int which, int64_t N, int64_t C, int64_t D);
+
+/* out[rows x cols] (FP32, dense) = P * 2^s.  Test aid. */
+int mx_dequantize(const uint8_t* codes, const uint8_t* scales, int64_t rows, int64_t cols,
+                  float* out, void* stream);
+
+/* Raw hipError_t of the last launch that made a call return MX_ERR_HIP (0 if none). */
+int mx_last_hip_error(void);
+
+/* Static version string. */
+const char* mx_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,10 @@
+"""MI355X (gfx950) implementation of the MXFP4 quantized linear layer of TetraJet
+(arxiv 2502.20853): HIP kernels behind a C ABI (include/mxfp4.h) and a thin
+binding with the same names."""
+from .binding import (  # noqa: F401
+    DTYPE_BF16, DTYPE_F32, GEMM_BWD_DW, GEMM_BWD_DX, GEMM_FWD, ROUND_RTN, ROUND_SR,
+    SCALE_FLOOR, SCALE_TRUNCFREE, MxError,
+    mx_dequantize, mx_ema_weight_quant, mx_linear_bwd_dw, mx_linear_bwd_dx, mx_linear_fwd,
+    mx_linear_workspace_bytes, mx_quantize, mx_quantize_transposed, mx_version,
+)
+from .layer import MxLinearStep  # noqa: F401

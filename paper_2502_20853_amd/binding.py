@@ -1,0 +1,212 @@
+"""Thin Python binding of the C ABI in include/mxfp4.h.
+
+Argument marshalling only: torch supplies device memory and the current HIP
+stream; every step of the path runs in the library's kernels.  The functions
+have the same names as the C entry points.  A missing or unloadable library is
+an error -- there is no fallback path.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmxfp4_hip.so")
+
+MX_OK = 0
+MX_ERR_NULL, MX_ERR_SHAPE, MX_ERR_DTYPE, MX_ERR_MODE = -1, -2, -3, -4
+MX_ERR_ALIGN, MX_ERR_WORKSPACE, MX_ERR_HIP = -5, -6, -7
+_ERR_NAMES = {-1: "MX_ERR_NULL", -2: "MX_ERR_SHAPE", -3: "MX_ERR_DTYPE", -4: "MX_ERR_MODE",
+              -5: "MX_ERR_ALIGN", -6: "MX_ERR_WORKSPACE", -7: "MX_ERR_HIP"}
+
+DTYPE_F32, DTYPE_BF16 = 0, 1
+ROUND_RTN, ROUND_SR = 0, 1
+SCALE_TRUNCFREE, SCALE_FLOOR = 0, 1
+GEMM_FWD, GEMM_BWD_DX, GEMM_BWD_DW = 0, 1, 2
+
+EXPORTS = ["mx_quantize", "mx_quantize_transposed", "mx_linear_fwd", "mx_linear_bwd_dx",
+           "mx_linear_bwd_dw", "mx_ema_weight_quant", "mx_linear_workspace_bytes",
+           "mx_dequantize", "mx_last_hip_error", "mx_version"]
+
+
+class MxError(RuntimeError):
+    def __init__(self, fn, code, hip=0):
+        self.code = code
+        msg = "%s failed: %s (%d)" % (fn, _ERR_NAMES.get(code, "?"), code)
+        if code == MX_ERR_HIP:
+            msg += ", hipError_t %d" % hip
+        super().__init__(msg)
+
+
+_lib = None
+
+
+def lib():
+    """Load the HIP library (built by paper_2502_20853_amd.build); raises if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("HIP library %s is not built: run `python -m paper_2502_20853_amd.build` "
+                           "(or __graft_entry__.build())" % LIB_PATH)
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i64, u64, u32, ci, sz, f32 = (ctypes.c_void_p, ctypes.c_int64, ctypes.c_uint64, ctypes.c_uint32,
+                                      ctypes.c_int, ctypes.c_size_t, ctypes.c_float)
+    L.mx_quantize.restype = ci
+    L.mx_quantize.argtypes = [vp, ci, i64, i64, i64, vp, vp, ci, ci, u64, u32, u64, vp]
+    L.mx_quantize_transposed.restype = ci
+    L.mx_quantize_transposed.argtypes = [vp, ci, i64, i64, i64, vp, vp, ci, u32, ci, vp, vp, ci, u32,
+                                         vp, vp, ci, u64, u64, vp]
+    for name in ("mx_linear_fwd", "mx_linear_bwd_dx", "mx_linear_bwd_dw"):
+        fn = getattr(L, name)
+        fn.restype = ci
+        fn.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, ci, i64, vp, sz, vp]
+    L.mx_ema_weight_quant.restype = ci
+    L.mx_ema_weight_quant.argtypes = [vp, ci, vp, f32, ci, i64, i64, i64, vp, vp, ci, vp]
+    L.mx_linear_workspace_bytes.restype = sz
+    L.mx_linear_workspace_bytes.argtypes = [ci, i64, i64, i64]
+    L.mx_dequantize.restype = ci
+    L.mx_dequantize.argtypes = [vp, vp, i64, i64, vp, vp]
+    L.mx_last_hip_error.restype = ci
+    L.mx_last_hip_error.argtypes = []
+    L.mx_version.restype = ctypes.c_char_p
+    L.mx_version.argtypes = []
+    _lib = L
+    return L
+
+
+def _check(fn, rc):
+    if rc != MX_OK:
+        raise MxError(fn, rc, lib().mx_last_hip_error() if rc == MX_ERR_HIP else 0)
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else ctypes.c_void_p(0)
+
+
+def _src_dtype(t):
+    if t.dtype == torch.float32:
+        return DTYPE_F32
+    if t.dtype == torch.bfloat16:
+        return DTYPE_BF16
+    raise TypeError("source must be float32 or bfloat16, got %s" % t.dtype)
+
+
+def _matrix(t):
+    if t.dim() != 2 or t.stride(1) != 1:
+        raise ValueError("expected a 2-D tensor with unit column stride")
+    return t.shape[0], t.shape[1], t.stride(0)
+
+
+def _u8(shape, device):
+    return torch.empty(shape, dtype=torch.uint8, device=device)
+
+
+def mx_version():
+    return lib().mx_version().decode()
+
+
+def mx_quantize(src, round=ROUND_RTN, scale_mode=SCALE_TRUNCFREE, seed=0, tensor_id=0, index_base=0,
+                out=None, stream=None):
+    """1x32 groups along the columns.  Returns (codes[rows, cols/2], scales[rows, cols/32])."""
+    rows, cols, ld = _matrix(src)
+    codes, scales = out if out is not None else (_u8((rows, cols // 2), src.device), _u8((rows, cols // 32), src.device))
+    rc = lib().mx_quantize(_ptr(src), _src_dtype(src), rows, cols, ld, _ptr(codes), _ptr(scales),
+                           round, scale_mode, seed, tensor_id, index_base, _stream(stream))
+    _check("mx_quantize", rc)
+    return codes, scales
+
+
+def mx_quantize_transposed(src, round_t=ROUND_SR, tensor_id_t=0, pre_quant=1, want_row=True,
+                           round_row=ROUND_RTN, tensor_id_row=0, row_in=None,
+                           scale_mode=SCALE_TRUNCFREE, seed=0, index_base=0, out=None, stream=None,
+                           shape=None):
+    """32x1 groups stored transposed, optionally fused with the 1x32 quantizer.
+
+    Returns (codes_t[cols, rows/2], scales_t[cols, rows/32], codes_row, scales_row);
+    the last two are None unless want_row.  With row_in=(codes, scales) the given
+    row result is re-quantized and src may be None (pass shape=(rows, cols)).
+    """
+    if src is not None:
+        rows, cols, ld = _matrix(src)
+        dtype, device = _src_dtype(src), src.device
+    else:
+        rows, cols = shape
+        ld, dtype, device = cols, DTYPE_F32, row_in[0].device
+    if out is not None:
+        codes_t, scales_t, codes_row, scales_row = out
+    else:
+        codes_t, scales_t = _u8((cols, rows // 2), device), _u8((cols, rows // 32), device)
+        codes_row = scales_row = None
+        if want_row:
+            codes_row, scales_row = _u8((rows, cols // 2), device), _u8((rows, cols // 32), device)
+    rc_in, rs_in = row_in if row_in is not None else (None, None)
+    rc = lib().mx_quantize_transposed(_ptr(src), dtype, rows, cols, ld, _ptr(codes_t), _ptr(scales_t),
+                                      round_t, tensor_id_t, pre_quant, _ptr(codes_row), _ptr(scales_row),
+                                      round_row, tensor_id_row, _ptr(rc_in), _ptr(rs_in),
+                                      scale_mode, seed, index_base, _stream(stream))
+    _check("mx_quantize_transposed", rc)
+    return codes_t, scales_t, codes_row, scales_row
+
+
+def mx_linear_workspace_bytes(which, N, C, D):
+    return int(lib().mx_linear_workspace_bytes(which, N, C, D))
+
+
+def _linear(name, which, a, a_s, b, b_s, N, C, D, out_shape, out, out_dtype, workspace, stream):
+    device = a.device
+    if out is None:
+        out = torch.empty(out_shape, dtype=out_dtype, device=device)
+    need = mx_linear_workspace_bytes(which, N, C, D)
+    if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
+        workspace = torch.empty(need, dtype=torch.uint8, device=device)
+    wbytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    rc = getattr(lib(), name)(_ptr(a), _ptr(a_s), _ptr(b), _ptr(b_s), N, C, D,
+                              _ptr(out), _src_dtype(out), out.stride(0), _ptr(workspace), wbytes,
+                              _stream(stream))
+    _check(name, rc)
+    return out
+
+
+def mx_linear_fwd(xq, xs, wq, ws, out=None, out_dtype=torch.float32, workspace=None, stream=None):
+    """Y[N, C] = Q1(X) . Q2(W)^T from packed operands xq[N, D/2], wq[C, D/2]."""
+    N, D, C = xq.shape[0], xq.shape[1] * 2, wq.shape[0]
+    return _linear("mx_linear_fwd", GEMM_FWD, xq, xs, wq, ws, N, C, D, (N, C), out, out_dtype, workspace, stream)
+
+
+def mx_linear_bwd_dx(dyq, dys, wtq, wts, out=None, out_dtype=torch.float32, workspace=None, stream=None):
+    """dX[N, D] from dyq[N, C/2] and the transposed-quantized weight wtq[D, C/2]."""
+    N, C, D = dyq.shape[0], dyq.shape[1] * 2, wtq.shape[0]
+    return _linear("mx_linear_bwd_dx", GEMM_BWD_DX, dyq, dys, wtq, wts, N, C, D, (N, D), out, out_dtype, workspace, stream)
+
+
+def mx_linear_bwd_dw(dytq, dyts, xtq, xts, out=None, out_dtype=torch.float32, workspace=None, stream=None):
+    """dW[C, D] from dytq[C, N/2] and xtq[D, N/2]."""
+    C, N, D = dytq.shape[0], dytq.shape[1] * 2, xtq.shape[0]
+    return _linear("mx_linear_bwd_dw", GEMM_BWD_DW, dytq, dyts, xtq, xts, N, C, D, (C, D), out, out_dtype, workspace, stream)
+
+
+def mx_ema_weight_quant(w, w_ema, beta=0.998, update_ema=1, scale_mode=SCALE_TRUNCFREE, out=None, stream=None):
+    """Q-EMA; w_ema (float32, same shape and strides as w) is updated in place."""
+    rows, cols, ld = _matrix(w)
+    if w_ema.dtype != torch.float32 or w_ema.shape != w.shape or w_ema.stride() != w.stride():
+        raise ValueError("w_ema must be float32 with the shape and strides of w")
+    codes, scales = out if out is not None else (_u8((rows, cols // 2), w.device), _u8((rows, cols // 32), w.device))
+    rc = lib().mx_ema_weight_quant(_ptr(w), _src_dtype(w), _ptr(w_ema), beta, update_ema, rows, cols, ld,
+                                   _ptr(codes), _ptr(scales), scale_mode, _stream(stream))
+    _check("mx_ema_weight_quant", rc)
+    return codes, scales
+
+
+def mx_dequantize(codes, scales, stream=None):
+    rows, cols = codes.shape[0], codes.shape[1] * 2
+    out = torch.empty((rows, cols), dtype=torch.float32, device=codes.device)
+    rc = lib().mx_dequantize(_ptr(codes), _ptr(scales), rows, cols, _ptr(out), _stream(stream))
+    _check("mx_dequantize", rc)
+    return out

@@ -1,0 +1,197 @@
+// C ABI of the library (declared in include/mxfp4.h): argument validation on
+// the host, then launches.  No allocation, no synchronisation.
+#include "../../include/mxfp4.h"
+#include "mx_launch.hpp"
+
+#include <atomic>
+
+namespace {
+
+std::atomic<int> g_last_hip_error{0};
+
+int hip_status(hipError_t e)
+{
+    if (e == hipSuccess) return MX_OK;
+    g_last_hip_error.store((int)e);
+    return MX_ERR_HIP;
+}
+
+bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+constexpr int64_t MAX_ELEMS = (int64_t)0xFFFF0000LL * 8;   // 8-element chunks are indexed with 32 bits
+
+// shared checks of the 1x32 quantizer entry points
+int check_rows_call(const void* src, int dtype, int64_t rows, int64_t cols, int64_t ld,
+                    const uint8_t* codes, const uint8_t* scales, int scale_mode)
+{
+    if (!src || !codes || !scales) return MX_ERR_NULL;
+    if (dtype != MX_DTYPE_F32 && dtype != MX_DTYPE_BF16) return MX_ERR_DTYPE;
+    if (scale_mode != MX_SCALE_TRUNCFREE && scale_mode != MX_SCALE_FLOOR) return MX_ERR_MODE;
+    if (rows <= 0 || cols <= 0 || (cols % 32) != 0 || ld < cols) return MX_ERR_SHAPE;
+    if (rows > MAX_ELEMS / cols) return MX_ERR_SHAPE;
+    if (!aligned(src, 16) || !aligned(codes, 4)) return MX_ERR_ALIGN;
+    if (ld % (dtype == MX_DTYPE_BF16 ? 8 : 4) != 0) return MX_ERR_ALIGN;
+    return MX_OK;
+}
+
+int check_gemm_call(const uint8_t* aq, const uint8_t* as, const uint8_t* bq, const uint8_t* bs,
+                    int64_t m, int64_t n, int64_t k, const void* out, int out_dtype, int64_t ldo)
+{
+    if (!aq || !as || !bq || !bs || !out) return MX_ERR_NULL;
+    if (out_dtype != MX_DTYPE_F32 && out_dtype != MX_DTYPE_BF16) return MX_ERR_DTYPE;
+    if (m <= 0 || n <= 0 || k <= 0 || (k % 32) != 0 || ldo < n) return MX_ERR_SHAPE;
+    if (m > 0x7FFFFFFFLL || n > 0x7FFFFFFFLL || k > 0x7FFFFFFFLL) return MX_ERR_SHAPE;
+    if (((m + 255) / 256) * ((n + 255) / 256) > 0x7FFFFFFFLL) return MX_ERR_SHAPE;
+    if (!aligned(aq, 16) || !aligned(bq, 16) || !aligned(as, 4) || !aligned(bs, 4)) return MX_ERR_ALIGN;
+    if (!aligned(out, out_dtype == MX_DTYPE_BF16 ? 8 : 16)) return MX_ERR_ALIGN;
+    return MX_OK;
+}
+
+int run_gemm(const uint8_t* aq, const uint8_t* as, const uint8_t* bq, const uint8_t* bs,
+             int64_t m, int64_t n, int64_t k, void* out, int out_dtype, int64_t ldo,
+             void* workspace, size_t workspace_bytes, void* stream)
+{
+    int rc = check_gemm_call(aq, as, bq, bs, m, n, k, out, out_dtype, ldo);
+    if (rc != MX_OK) return rc;
+    int split = mxl::gemm_split_k(m, n, k);
+    size_t need = split > 1 ? (size_t)split * (size_t)m * (size_t)n * sizeof(float) : 0;
+    if (need > 0) {
+        if (!workspace || workspace_bytes < need) return MX_ERR_WORKSPACE;
+        if (!aligned(workspace, 256)) return MX_ERR_ALIGN;
+    }
+    mxl::GemmParams p{};
+    p.a_codes = aq; p.a_scales = as; p.b_codes = bq; p.b_scales = bs;
+    p.m = m; p.n = n; p.k = k;
+    p.c = out; p.c_bf16 = out_dtype == MX_DTYPE_BF16; p.ldc = ldo;
+    p.workspace = workspace; p.split_k = split;
+    return hip_status(mxl::launch_gemm(p, static_cast<hipStream_t>(stream)));
+}
+
+}  // namespace
+
+extern "C" {
+
+int mx_quantize(const void* src, int dtype, int64_t rows, int64_t cols, int64_t ld,
+                uint8_t* codes, uint8_t* scales, int round, int scale_mode,
+                uint64_t seed, uint32_t tensor_id, uint64_t index_base, void* stream)
+{
+    int rc = check_rows_call(src, dtype, rows, cols, ld, codes, scales, scale_mode);
+    if (rc != MX_OK) return rc;
+    if (round != MX_ROUND_RTN && round != MX_ROUND_SR) return MX_ERR_MODE;
+    if (round == MX_ROUND_SR && (index_base & 7u) != 0) return MX_ERR_ALIGN;
+    mxl::QuantRowsParams p{};
+    p.src = src; p.bf16 = dtype == MX_DTYPE_BF16; p.rows = rows; p.cols = cols; p.ld = ld;
+    p.codes = codes; p.scales = scales; p.sr = round == MX_ROUND_SR;
+    p.floor_mode = scale_mode == MX_SCALE_FLOOR;
+    p.seed = seed; p.tensor_id = tensor_id; p.index_base = index_base;
+    return hip_status(mxl::launch_quantize_rows(p, static_cast<hipStream_t>(stream)));
+}
+
+int mx_quantize_transposed(const void* src, int dtype, int64_t rows, int64_t cols, int64_t ld,
+                uint8_t* codes_t, uint8_t* scales_t, int round_t, uint32_t tensor_id_t,
+                int pre_quant, uint8_t* codes_row, uint8_t* scales_row,
+                int round_row, uint32_t tensor_id_row,
+                const uint8_t* row_codes_in, const uint8_t* row_scales_in,
+                int scale_mode, uint64_t seed, uint64_t index_base, void* stream)
+{
+    if (!codes_t || !scales_t) return MX_ERR_NULL;
+    if ((codes_row == nullptr) != (scales_row == nullptr)) return MX_ERR_NULL;
+    if ((row_codes_in == nullptr) != (row_scales_in == nullptr)) return MX_ERR_NULL;
+    const bool given = row_codes_in != nullptr;
+    if (!given && !src) return MX_ERR_NULL;
+    if (pre_quant != 0 && pre_quant != 1) return MX_ERR_MODE;
+    if (given && (pre_quant != 1 || codes_row != nullptr)) return MX_ERR_MODE;
+    if (round_t != MX_ROUND_RTN && round_t != MX_ROUND_SR) return MX_ERR_MODE;
+    if (round_row != MX_ROUND_RTN && round_row != MX_ROUND_SR) return MX_ERR_MODE;
+    if (scale_mode != MX_SCALE_TRUNCFREE && scale_mode != MX_SCALE_FLOOR) return MX_ERR_MODE;
+    if (!given && dtype != MX_DTYPE_F32 && dtype != MX_DTYPE_BF16) return MX_ERR_DTYPE;
+    if (rows <= 0 || cols <= 0 || (rows % 32) != 0 || (cols % 32) != 0) return MX_ERR_SHAPE;
+    if (!given && ld < cols) return MX_ERR_SHAPE;
+    if (rows > MAX_ELEMS / cols || rows > 65535LL * 256) return MX_ERR_SHAPE;
+    if (!aligned(codes_t, 4)) return MX_ERR_ALIGN;
+    if (codes_row && !aligned(codes_row, 4)) return MX_ERR_ALIGN;
+    if (given && !aligned(row_codes_in, 4)) return MX_ERR_ALIGN;
+    if (!given) {
+        if (!aligned(src, 16)) return MX_ERR_ALIGN;
+        if (ld % (dtype == MX_DTYPE_BF16 ? 8 : 4) != 0) return MX_ERR_ALIGN;
+    }
+    const bool any_sr = round_t == MX_ROUND_SR || (!given && round_row == MX_ROUND_SR && (pre_quant || codes_row));
+    if (any_sr && (index_base & 7u) != 0) return MX_ERR_ALIGN;
+    mxl::QuantTileParams p{};
+    p.src = src; p.bf16 = dtype == MX_DTYPE_BF16; p.rows = rows; p.cols = cols; p.ld = ld;
+    p.codes_t = codes_t; p.scales_t = scales_t; p.sr_t = round_t == MX_ROUND_SR; p.tensor_id_t = tensor_id_t;
+    p.pre_quant = pre_quant == 1; p.codes_row = codes_row; p.scales_row = scales_row;
+    p.sr_row = round_row == MX_ROUND_SR; p.tensor_id_row = tensor_id_row;
+    p.row_codes_in = row_codes_in; p.row_scales_in = row_scales_in;
+    p.floor_mode = scale_mode == MX_SCALE_FLOOR; p.seed = seed; p.index_base = index_base;
+    return hip_status(mxl::launch_quantize_tile(p, static_cast<hipStream_t>(stream)));
+}
+
+int mx_linear_fwd(const uint8_t* xq, const uint8_t* xs, const uint8_t* wq, const uint8_t* ws,
+                  int64_t N, int64_t C, int64_t D, void* y, int y_dtype, int64_t ldy,
+                  void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (N <= 0 || C <= 0 || D <= 0) return (!xq || !xs || !wq || !ws || !y) ? MX_ERR_NULL : MX_ERR_SHAPE;
+    return run_gemm(xq, xs, wq, ws, N, C, D, y, y_dtype, ldy, workspace, workspace_bytes, stream);
+}
+
+int mx_linear_bwd_dx(const uint8_t* dyq, const uint8_t* dys, const uint8_t* wtq, const uint8_t* wts,
+                  int64_t N, int64_t C, int64_t D, void* dx, int dx_dtype, int64_t lddx,
+                  void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (N <= 0 || C <= 0 || D <= 0) return (!dyq || !dys || !wtq || !wts || !dx) ? MX_ERR_NULL : MX_ERR_SHAPE;
+    return run_gemm(dyq, dys, wtq, wts, N, D, C, dx, dx_dtype, lddx, workspace, workspace_bytes, stream);
+}
+
+int mx_linear_bwd_dw(const uint8_t* dytq, const uint8_t* dyts, const uint8_t* xtq, const uint8_t* xts,
+                  int64_t N, int64_t C, int64_t D, void* dw, int dw_dtype, int64_t lddw,
+                  void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (N <= 0 || C <= 0 || D <= 0) return (!dytq || !dyts || !xtq || !xts || !dw) ? MX_ERR_NULL : MX_ERR_SHAPE;
+    return run_gemm(dytq, dyts, xtq, xts, C, D, N, dw, dw_dtype, lddw, workspace, workspace_bytes, stream);
+}
+
+int mx_ema_weight_quant(const void* w, int dtype, float* w_ema, float beta, int update_ema,
+                  int64_t rows, int64_t cols, int64_t ld,
+                  uint8_t* codes, uint8_t* scales, int scale_mode, void* stream)
+{
+    int rc = check_rows_call(w, dtype, rows, cols, ld, codes, scales, scale_mode);
+    if (rc != MX_OK) return rc;
+    if (!w_ema) return MX_ERR_NULL;
+    if (update_ema < 0 || update_ema > 2) return MX_ERR_MODE;
+    if (!(beta >= 0.0f && beta < 1.0f)) return MX_ERR_MODE;
+    if (!aligned(w_ema, 16) || (ld % 4) != 0) return MX_ERR_ALIGN;
+    mxl::QuantRowsParams p{};
+    p.src = w; p.bf16 = dtype == MX_DTYPE_BF16; p.rows = rows; p.cols = cols; p.ld = ld;
+    p.codes = codes; p.scales = scales; p.sr = false; p.floor_mode = scale_mode == MX_SCALE_FLOOR;
+    return hip_status(mxl::launch_ema_quantize(p, w_ema, beta, update_ema, static_cast<hipStream_t>(stream)));
+}
+
+size_t mx_linear_workspace_bytes(int which, int64_t N, int64_t C, int64_t D)
+{
+    if (N <= 0 || C <= 0 || D <= 0) return 0;
+    int64_t m, n, k;
+    switch (which) {
+        case MX_GEMM_FWD:    m = N; n = C; k = D; break;
+        case MX_GEMM_BWD_DX: m = N; n = D; k = C; break;
+        case MX_GEMM_BWD_DW: m = C; n = D; k = N; break;
+        default: return 0;
+    }
+    int split = mxl::gemm_split_k(m, n, k);
+    return split > 1 ? (size_t)split * (size_t)m * (size_t)n * sizeof(float) : 0;
+}
+
+int mx_dequantize(const uint8_t* codes, const uint8_t* scales, int64_t rows, int64_t cols,
+                  float* out, void* stream)
+{
+    if (!codes || !scales || !out) return MX_ERR_NULL;
+    if (rows <= 0 || cols <= 0 || (cols % 32) != 0) return MX_ERR_SHAPE;
+    if (rows > MAX_ELEMS / cols) return MX_ERR_SHAPE;
+    return hip_status(mxl::launch_dequantize(codes, scales, rows, cols, out, static_cast<hipStream_t>(stream)));
+}
+
+int mx_last_hip_error(void) { return g_last_hip_error.load(); }
+
+const char* mx_version(void) { return "mxfp4-gfx950 0.1"; }
+
+}  // extern "C"

@@ -1,0 +1,67 @@
+// Host-side launch interface between the C ABI (mx_api.hip) and the kernels.
+// All arguments have been validated by the caller.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace mxl {
+
+struct QuantRowsParams {
+    const void* src;
+    bool bf16;
+    int64_t rows, cols, ld;
+    uint8_t* codes;
+    uint8_t* scales;
+    bool sr;
+    bool floor_mode;
+    uint64_t seed;
+    uint32_t tensor_id;
+    uint64_t index_base;
+};
+
+struct QuantTileParams {
+    const void* src;
+    bool bf16;
+    int64_t rows, cols, ld;
+    uint8_t* codes_t;
+    uint8_t* scales_t;
+    bool sr_t;
+    uint32_t tensor_id_t;
+    bool pre_quant;
+    uint8_t* codes_row;
+    uint8_t* scales_row;
+    bool sr_row;
+    uint32_t tensor_id_row;
+    const uint8_t* row_codes_in;
+    const uint8_t* row_scales_in;
+    bool floor_mode;
+    uint64_t seed;
+    uint64_t index_base;
+};
+
+// C[m x n] = A[m x k] . B[n x k]^T, operands packed MXFP4 along k.
+struct GemmParams {
+    const uint8_t* a_codes;
+    const uint8_t* a_scales;
+    const uint8_t* b_codes;
+    const uint8_t* b_scales;
+    int64_t m, n, k;
+    void* c;
+    bool c_bf16;
+    int64_t ldc;
+    void* workspace;
+    int split_k;     // >= 1; > 1 needs workspace of split_k * m * n floats
+};
+
+hipError_t launch_quantize_rows(const QuantRowsParams& p, hipStream_t st);
+hipError_t launch_ema_quantize(const QuantRowsParams& p, float* ema, float beta, int update_ema, hipStream_t st);
+hipError_t launch_quantize_tile(const QuantTileParams& p, hipStream_t st);
+hipError_t launch_dequantize(const uint8_t* codes, const uint8_t* scales, int64_t rows, int64_t cols,
+                             float* out, hipStream_t st);
+
+// Number of K-splits the product will use for these sizes (1 = none).
+int gemm_split_k(int64_t m, int64_t n, int64_t k);
+hipError_t launch_gemm(const GemmParams& p, hipStream_t st);
+
+}  // namespace mxl

@@ -1,0 +1,367 @@
+// MXFP4 quantizer kernels for gfx950: streaming, HBM-bound, no matrix cores.
+//
+//  quantize_rows_kernel   1x32 groups along the columns (Q1, Q2, Q3 of Eqs. 3-4)
+//  quantize_tile_kernel   32x1 groups stored transposed (Q4, Q5, Q6 of Eqs. 4-5),
+//                         optionally fused with the 1x32 quantizer of the same
+//                         source (one read of the tensor) and with double
+//                         quantization (Sec. 3.3)
+//  ema_quantize_kernel    Q-EMA (Eq. 8, Algorithm 1)
+//  dequantize_kernel      test aid
+//
+// Work split: one lane owns 8 consecutive elements of a row (one 16-byte bf16
+// load, one Philox call for its 8 rounding decisions, one 4-byte store of 8
+// codes); 4 neighbouring lanes form a 1x32 group and reduce |x| with DPP.
+#include "mx_device.hpp"
+#include "mx_launch.hpp"
+
+using namespace mxd;
+
+namespace {
+
+constexpr int ROWS_UNROLL = 4;       // 8-element chunks per lane in quantize_rows_kernel
+constexpr int ROWS_THREADS = 256;
+
+struct RowsArgs {
+    const void* src;
+    uint8_t* codes;
+    uint8_t* scales;
+    float* ema;            // Q-EMA only
+    int64_t ld;            // elements
+    uint32_t cpr;          // 8-element chunks per row (cols / 8)
+    uint32_t total;        // rows * cpr
+    int contiguous;        // ld == cols
+    int floor_mode;
+    uint32_t k0, k1, tensor_id;
+    uint64_t base_blk;     // index_base >> 3
+    float beta;
+    int update_ema;
+};
+
+// Encode 8 scaled elements and pack them low nibble first.
+template <bool SR>
+__device__ __forceinline__ uint32_t encode8(const F8& x, float inv, bool floor_mode, const U4& rnd)
+{
+    uint32_t packed = 0;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        float y = x.v[t] * inv;     // exact (gradual underflow only below 2^-126)
+        uint32_t c = SR ? round_sr(y, sr_field(rnd, t), floor_mode) : round_rtn(y, floor_mode);
+        packed |= c << (4 * t);
+    }
+    return packed;
+}
+
+template <typename SrcT, bool SR>
+__global__ __launch_bounds__(ROWS_THREADS) void quantize_rows_kernel(RowsArgs a)
+{
+    const SrcT* src = static_cast<const SrcT*>(a.src);
+    const uint32_t q0 = blockIdx.x * (ROWS_THREADS * ROWS_UNROLL) + threadIdx.x;
+    F8 x[ROWS_UNROLL];
+    bool ok[ROWS_UNROLL];
+#pragma unroll
+    for (int u = 0; u < ROWS_UNROLL; ++u) {
+        uint32_t q = q0 + u * ROWS_THREADS;
+        ok[u] = q < a.total && q >= q0;
+        if (ok[u]) {
+            int64_t off;
+            if (a.contiguous) {
+                off = (int64_t)q * 8;
+            } else {
+                uint32_t r = q / a.cpr;
+                off = (int64_t)r * a.ld + (int64_t)(q - r * a.cpr) * 8;
+            }
+            x[u] = load8(src + off);
+        } else {
+            x[u] = zero8();
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < ROWS_UNROLL; ++u) {
+        uint32_t q = q0 + u * ROWS_THREADS;
+        uint32_t m = quad_max(amax_bits8(x[u]));
+        uint32_t byte = scale_byte(m, a.floor_mode);
+        U4 rnd;
+        if (SR) rnd = sr_block(a.base_blk + q, a.tensor_id, a.k0, a.k1);
+        uint32_t packed = encode8<SR>(x[u], inv_scale(byte), a.floor_mode, rnd);
+        if (ok[u]) {
+            reinterpret_cast<uint32_t*>(a.codes)[q] = packed;
+            if ((threadIdx.x & 3) == 0) a.scales[q >> 2] = (uint8_t)byte;
+        }
+    }
+}
+
+template <typename SrcT>
+__global__ __launch_bounds__(ROWS_THREADS) void ema_quantize_kernel(RowsArgs a)
+{
+    const SrcT* src = static_cast<const SrcT*>(a.src);
+    const uint32_t q = blockIdx.x * ROWS_THREADS + threadIdx.x;
+    const bool ok = q < a.total;
+    F8 w = zero8(), e = zero8();
+    int64_t off = 0;
+    if (ok) {
+        if (a.contiguous) {
+            off = (int64_t)q * 8;
+        } else {
+            uint32_t r = q / a.cpr;
+            off = (int64_t)r * a.ld + (int64_t)(q - r * a.cpr) * 8;
+        }
+        w = load8(src + off);
+        if (a.update_ema != 2) e = load8(a.ema + off);
+    }
+    if (a.update_ema == 1) {
+        const float omb = __fsub_rn(1.0f, a.beta);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) e.v[t] = __fmaf_rn(a.beta, e.v[t], __fmul_rn(omb, w.v[t]));
+    } else if (a.update_ema == 2) {
+        e = w;
+    }
+    uint32_t m = quad_max(amax_bits8(w));
+    uint32_t byte = scale_byte(m, a.floor_mode);
+    float inv = inv_scale(byte);
+    uint32_t packed = 0;
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+        packed |= round_ema(w.v[t] * inv, e.v[t] * inv, a.floor_mode) << (4 * t);
+    if (ok) {
+        if (a.update_ema != 0) {
+            float4* p = reinterpret_cast<float4*>(a.ema + off);
+            p[0] = make_float4(e.v[0], e.v[1], e.v[2], e.v[3]);
+            p[1] = make_float4(e.v[4], e.v[5], e.v[6], e.v[7]);
+        }
+        reinterpret_cast<uint32_t*>(a.codes)[q] = packed;
+        if ((threadIdx.x & 3) == 0) a.scales[q >> 2] = (uint8_t)byte;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Transposed / fused quantizer.
+//
+// A workgroup of 8 waves owns a 256 x 256 macro tile of the source; wave w owns
+// rows [32w, 32w+32) of it and walks over four 32 x 64 tiles.  Inside a tile,
+// lane l holds rows 4*(l/8)+j (j = 0..3) x columns 8*(l%8)+t (t = 0..7):
+//   - each load instruction reads 8 full rows of 64 elements,
+//   - a 1x32 row group is 4 neighbouring lanes (DPP quad reduction),
+//   - a 32x1 column group is 4 registers x 8 lanes (l/8 = 0..7) of one column.
+// All stores of one macro tile come from one workgroup close in time, so the
+// 32-byte (row codes) and 2-byte (transposed codes) pieces merge into full
+// 128-byte lines in that XCD's L2 before they are written back.
+// ---------------------------------------------------------------------------
+constexpr int TILE_THREADS = 512;
+
+struct TileArgs {
+    const void* src;
+    const uint8_t* row_codes_in;
+    const uint8_t* row_scales_in;
+    uint8_t* codes_t;
+    uint8_t* scales_t;
+    uint8_t* codes_row;
+    uint8_t* scales_row;
+    int64_t ld;
+    uint32_t rows, cols;
+    int pre_quant;
+    int floor_mode;
+    uint32_t k0, k1, tensor_id_t, tensor_id_row;
+    uint64_t index_base;
+};
+
+__device__ __forceinline__ uint32_t xor_lane_max(uint32_t v, int mask)
+{
+    uint32_t o = (uint32_t)__shfl_xor((int)v, mask, 64);
+    return v > o ? v : o;
+}
+
+// SRC: 0 = FP32 source, 1 = bf16 source, 2 = packed row result given
+template <int SRC, bool ROW_SR, bool T_SR>
+__global__ __launch_bounds__(TILE_THREADS) void quantize_tile_kernel(TileArgs a)
+{
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const uint32_t rt = blockIdx.y * 8 + wave;            // 32-row tile index
+    if (rt * 32 >= a.rows) return;                        // whole wave leaves; no block barrier is used
+    const int cc = lane & 7, rg = lane >> 3;
+    const uint32_t row0 = rt * 32 + 4 * rg;
+    const bool want_row = a.codes_row != nullptr;
+    const bool floor_mode = a.floor_mode != 0;
+    const uint32_t half_rows = a.rows >> 1, grp_rows = a.rows >> 5;
+    const uint32_t half_cols = a.cols >> 1, grp_cols = a.cols >> 5;
+
+    for (int ci = 0; ci < 4; ++ci) {
+        const uint32_t col0 = blockIdx.x * 256 + ci * 64;
+        if (col0 >= a.cols) break;                        // uniform over the wave
+        const uint32_t c = col0 + cc * 8;
+        const bool ok = c < a.cols;
+        F8 x[4];
+        // ---- load -----------------------------------------------------------
+        if (SRC == 2) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                x[j] = zero8();
+                if (ok) {
+                    uint32_t r = row0 + j;
+                    uint32_t pk = *reinterpret_cast<const uint32_t*>(a.row_codes_in + (size_t)r * half_cols + (c >> 1));
+                    float sc = fwd_scale(a.row_scales_in[(size_t)r * grp_cols + (c >> 5)]);
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) x[j].v[t] = dequant((pk >> (4 * t)) & 15u, sc);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                x[j] = zero8();
+                if (ok) {
+                    int64_t off = (int64_t)(row0 + j) * a.ld + c;
+                    if (SRC == 1) x[j] = load8(static_cast<const uint16_t*>(a.src) + off);
+                    else          x[j] = load8(static_cast<const float*>(a.src) + off);
+                }
+            }
+            // ---- 1x32 quantizer of the same elements ---------------------------
+            if (want_row || a.pre_quant) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    uint32_t r = row0 + j;
+                    uint32_t byte = scale_byte(quad_max(amax_bits8(x[j])), floor_mode);
+                    U4 rnd;
+                    if (ROW_SR) rnd = sr_block((a.index_base + (uint64_t)r * a.cols + c) >> 3, a.tensor_id_row, a.k0, a.k1);
+                    uint32_t pk = encode8<ROW_SR>(x[j], inv_scale(byte), floor_mode, rnd);
+                    if (want_row && ok) {
+                        *reinterpret_cast<uint32_t*>(a.codes_row + (size_t)r * half_cols + (c >> 1)) = pk;
+                        if ((cc & 3) == 0) a.scales_row[(size_t)r * grp_cols + (c >> 5)] = (uint8_t)byte;
+                    }
+                    if (a.pre_quant) {
+                        float sc = fwd_scale(byte);
+#pragma unroll
+                        for (int t = 0; t < 8; ++t) x[j].v[t] = dequant((pk >> (4 * t)) & 15u, sc);
+                    }
+                }
+            }
+        }
+        // ---- 32x1 quantizer: group = this lane's 4 rows x the 8 lanes sharing cc --
+        uint32_t sb[8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            uint32_t m = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                uint32_t b = __float_as_uint(x[j].v[t]) & 0x7FFFFFFFu;
+                m = b > m ? b : m;
+            }
+            m = xor_lane_max(m, 8);
+            m = xor_lane_max(m, 16);
+            m = xor_lane_max(m, 32);
+            sb[t] = scale_byte(m, floor_mode);
+        }
+        uint32_t colpk[8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) colpk[t] = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            U4 rnd;
+            if (T_SR) rnd = sr_block((a.index_base + (uint64_t)(row0 + j) * a.cols + c) >> 3, a.tensor_id_t, a.k0, a.k1);
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                float y = x[j].v[t] * inv_scale(sb[t]);
+                uint32_t code = T_SR ? round_sr(y, sr_field(rnd, t), floor_mode) : round_rtn(y, floor_mode);
+                colpk[t] |= code << (4 * j);
+            }
+        }
+        if (ok) {
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                size_t col = c + t;
+                *reinterpret_cast<uint16_t*>(a.codes_t + col * half_rows + (row0 >> 1)) = (uint16_t)colpk[t];
+                if (rg == 0) a.scales_t[col * grp_rows + rt] = (uint8_t)sb[t];
+            }
+        }
+    }
+}
+
+__global__ void dequantize_kernel(const uint8_t* codes, const uint8_t* scales, int64_t total_bytes,
+                                  int64_t cols, float* out)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;     // one code byte = 2 elements
+    if (i >= total_bytes) return;
+    int64_t half = cols >> 1;
+    int64_t r = i / half, j = i - r * half;
+    float sc = fwd_scale(scales[r * (cols >> 5) + (j >> 4)]);
+    uint32_t b = codes[i];
+    out[2 * i] = dequant(b & 15u, sc);
+    out[2 * i + 1] = dequant(b >> 4, sc);
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ launchers
+
+namespace mxl {
+
+hipError_t launch_quantize_rows(const QuantRowsParams& p, hipStream_t st)
+{
+    RowsArgs a{};
+    a.src = p.src; a.codes = p.codes; a.scales = p.scales; a.ema = nullptr;
+    a.ld = p.ld; a.cpr = (uint32_t)(p.cols / 8); a.total = (uint32_t)(p.rows * (p.cols / 8));
+    a.contiguous = p.ld == p.cols; a.floor_mode = p.floor_mode;
+    a.k0 = (uint32_t)p.seed; a.k1 = (uint32_t)(p.seed >> 32); a.tensor_id = p.tensor_id;
+    a.base_blk = p.index_base >> 3;
+    const uint32_t per_block = ROWS_THREADS * ROWS_UNROLL;
+    dim3 grid((a.total + per_block - 1) / per_block), block(ROWS_THREADS);
+    if (p.bf16) {
+        if (p.sr) hipLaunchKernelGGL((quantize_rows_kernel<uint16_t, true>), grid, block, 0, st, a);
+        else      hipLaunchKernelGGL((quantize_rows_kernel<uint16_t, false>), grid, block, 0, st, a);
+    } else {
+        if (p.sr) hipLaunchKernelGGL((quantize_rows_kernel<float, true>), grid, block, 0, st, a);
+        else      hipLaunchKernelGGL((quantize_rows_kernel<float, false>), grid, block, 0, st, a);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_ema_quantize(const QuantRowsParams& p, float* ema, float beta, int update_ema, hipStream_t st)
+{
+    RowsArgs a{};
+    a.src = p.src; a.codes = p.codes; a.scales = p.scales; a.ema = ema;
+    a.ld = p.ld; a.cpr = (uint32_t)(p.cols / 8); a.total = (uint32_t)(p.rows * (p.cols / 8));
+    a.contiguous = p.ld == p.cols; a.floor_mode = p.floor_mode;
+    a.beta = beta; a.update_ema = update_ema;
+    dim3 grid((a.total + ROWS_THREADS - 1) / ROWS_THREADS), block(ROWS_THREADS);
+    if (p.bf16) hipLaunchKernelGGL((ema_quantize_kernel<uint16_t>), grid, block, 0, st, a);
+    else        hipLaunchKernelGGL((ema_quantize_kernel<float>), grid, block, 0, st, a);
+    return hipGetLastError();
+}
+
+template <int SRC>
+static void launch_tile_src(const TileArgs& a, bool row_sr, bool t_sr, dim3 grid, hipStream_t st)
+{
+    dim3 block(TILE_THREADS);
+    if (row_sr) {
+        if (t_sr) hipLaunchKernelGGL((quantize_tile_kernel<SRC, true, true>), grid, block, 0, st, a);
+        else      hipLaunchKernelGGL((quantize_tile_kernel<SRC, true, false>), grid, block, 0, st, a);
+    } else {
+        if (t_sr) hipLaunchKernelGGL((quantize_tile_kernel<SRC, false, true>), grid, block, 0, st, a);
+        else      hipLaunchKernelGGL((quantize_tile_kernel<SRC, false, false>), grid, block, 0, st, a);
+    }
+}
+
+hipError_t launch_quantize_tile(const QuantTileParams& p, hipStream_t st)
+{
+    TileArgs a{};
+    a.src = p.src; a.row_codes_in = p.row_codes_in; a.row_scales_in = p.row_scales_in;
+    a.codes_t = p.codes_t; a.scales_t = p.scales_t; a.codes_row = p.codes_row; a.scales_row = p.scales_row;
+    a.ld = p.ld; a.rows = (uint32_t)p.rows; a.cols = (uint32_t)p.cols;
+    a.pre_quant = p.pre_quant; a.floor_mode = p.floor_mode;
+    a.k0 = (uint32_t)p.seed; a.k1 = (uint32_t)(p.seed >> 32);
+    a.tensor_id_t = p.tensor_id_t; a.tensor_id_row = p.tensor_id_row; a.index_base = p.index_base;
+    dim3 grid((unsigned)((p.cols + 255) / 256), (unsigned)((p.rows + 255) / 256));
+    if (p.row_codes_in)  launch_tile_src<2>(a, false, p.sr_t, grid, st);
+    else if (p.bf16)     launch_tile_src<1>(a, p.sr_row, p.sr_t, grid, st);
+    else                 launch_tile_src<0>(a, p.sr_row, p.sr_t, grid, st);
+    return hipGetLastError();
+}
+
+hipError_t launch_dequantize(const uint8_t* codes, const uint8_t* scales, int64_t rows, int64_t cols,
+                             float* out, hipStream_t st)
+{
+    int64_t total = rows * (cols / 2);
+    dim3 grid((unsigned)((total + 255) / 256)), block(256);
+    hipLaunchKernelGGL(dequantize_kernel, grid, block, 0, st, codes, scales, total, cols, out);
+    return hipGetLastError();
+}
+
+}  // namespace mxl

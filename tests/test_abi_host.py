@@ -1,0 +1,123 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+symbol the header declares, and rejects bad arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "mxfp4.h")
+
+
+@pytest.fixture(scope="module")
+def L():
+    from paper_2502_20853_amd import binding, build
+    if build.is_stale():
+        build.build()
+    return binding.lib()
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mx_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_symbols_exported(L):
+    from paper_2502_20853_amd import binding
+    names = declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+    for six in ("mx_quantize", "mx_quantize_transposed", "mx_linear_fwd", "mx_linear_bwd_dx",
+                "mx_linear_bwd_dw", "mx_ema_weight_quant"):
+        assert six in names
+    for n in names:
+        assert hasattr(L, n), n
+    assert L.mx_version().decode().startswith("mxfp4-gfx950")
+    assert L.mx_last_hip_error() == 0
+
+
+def test_binding_and_oracle_are_independent():
+    pkg = os.path.join(ROOT, "paper_2502_20853_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h", ".cpp")):
+                src = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in src, f
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith((".py", ".c", ".h")):
+            assert "paper_2502_20853_amd" not in open(os.path.join(ROOT, "oracle", f)).read(), f
+
+
+P = ctypes.c_void_p
+FAKE = 0x7F0000000000          # never dereferenced: every call below fails validation first
+
+
+def q(L, src=FAKE, dtype=1, rows=64, cols=64, ld=64, codes=FAKE, scales=FAKE, rnd=0, mode=0,
+      seed=0, tid=0, base=0):
+    return L.mx_quantize(P(src), dtype, rows, cols, ld, P(codes), P(scales), rnd, mode, seed, tid, base, P(0))
+
+
+def test_quantize_rejects(L):
+    assert q(L, src=0) == -1 and q(L, codes=0) == -1 and q(L, scales=0) == -1
+    assert q(L, dtype=2) == -3
+    assert q(L, mode=2) == -4 and q(L, rnd=5) == -4
+    assert q(L, cols=48) == -2 and q(L, rows=0) == -2 and q(L, ld=32) == -2 and q(L, cols=0) == -2
+    assert q(L, rows=1 << 40, cols=1 << 20, ld=1 << 20) == -2
+    assert q(L, src=FAKE + 2) == -5 and q(L, codes=FAKE + 1) == -5
+    assert q(L, ld=68) == -5                       # bf16 rows must start 16-byte aligned
+    assert q(L, rnd=1, base=4) == -5               # Philox blocks of 8 elements
+
+
+def qt(L, src=FAKE, dtype=1, rows=64, cols=64, ld=64, ct=FAKE, st=FAKE, rt=1, tidt=6, pre=1,
+       cr=FAKE, sr=FAKE, rr=0, tidr=1, rci=0, rsi=0, mode=0, seed=0, base=0):
+    return L.mx_quantize_transposed(P(src), dtype, rows, cols, ld, P(ct), P(st), rt, tidt, pre,
+                                    P(cr), P(sr), rr, tidr, P(rci), P(rsi), mode, seed, base, P(0))
+
+
+def test_quantize_transposed_rejects(L):
+    assert qt(L, ct=0) == -1 and qt(L, src=0) == -1
+    assert qt(L, cr=0) == -1 and qt(L, sr=0) == -1             # half-set optional pair
+    assert qt(L, rci=FAKE) == -1
+    assert qt(L, rows=48) == -2 and qt(L, cols=16) == -2 and qt(L, ld=32) == -2
+    assert qt(L, pre=2) == -4 and qt(L, rt=3) == -4 and qt(L, rr=-1) == -4 and qt(L, mode=9) == -4
+    assert qt(L, rci=FAKE, rsi=FAKE) == -4                      # given row result excludes a row output
+    assert qt(L, rci=FAKE, rsi=FAKE, cr=0, sr=0, pre=0) == -4   # and needs pre_quant
+    assert qt(L, dtype=7) == -3
+    assert qt(L, base=3) == -5 and qt(L, ct=FAKE + 2) == -5
+
+
+def g(L, fn, a=FAKE, as_=FAKE, b=FAKE, bs=FAKE, N=64, C=64, D=64, out=FAKE, dt=0, ldo=64, ws=0, wsb=0):
+    return getattr(L, fn)(P(a), P(as_), P(b), P(bs), N, C, D, P(out), dt, ldo, P(ws), wsb, P(0))
+
+
+def test_linear_rejects(L):
+    for fn in ("mx_linear_fwd", "mx_linear_bwd_dx", "mx_linear_bwd_dw"):
+        assert g(L, fn, a=0) == -1 and g(L, fn, bs=0) == -1 and g(L, fn, out=0) == -1
+        assert g(L, fn, dt=3) == -3
+        assert g(L, fn, N=0) == -2 and g(L, fn, ldo=8) == -2
+        assert g(L, fn, a=FAKE + 8) == -5
+    assert g(L, "mx_linear_fwd", D=48) == -2          # contraction dims must be multiples of 32
+    assert g(L, "mx_linear_bwd_dx", C=48) == -2
+    assert g(L, "mx_linear_bwd_dw", N=48) == -2
+    # a product that splits K demands its workspace
+    need = L.mx_linear_workspace_bytes(2, 50432, 768, 768)
+    assert need > 0 and need % (768 * 768 * 4) == 0
+    assert g(L, "mx_linear_bwd_dw", N=50432, C=768, D=768, ldo=768) == -6
+    assert g(L, "mx_linear_bwd_dw", N=50432, C=768, D=768, ldo=768, ws=FAKE, wsb=need - 1) == -6
+    assert L.mx_linear_workspace_bytes(0, 50432, 2304, 768) == 0
+    assert L.mx_linear_workspace_bytes(9, 64, 64, 64) == 0
+
+
+def test_ema_rejects(L):
+    def e(w=FAKE, dtype=0, ema=FAKE, beta=0.998, upd=1, rows=64, cols=64, ld=64, codes=FAKE, scales=FAKE, mode=0):
+        return L.mx_ema_weight_quant(P(w), dtype, P(ema), beta, upd, rows, cols, ld, P(codes), P(scales), mode, P(0))
+    assert e(ema=0) == -1 and e(w=0) == -1
+    assert e(upd=3) == -4 and e(beta=1.0) == -4 and e(beta=-0.1) == -4 and e(beta=float("nan")) == -4
+    assert e(cols=40) == -2
+    assert e(ema=FAKE + 4) == -5
+
+
+def test_dequantize_rejects(L):
+    assert L.mx_dequantize(P(0), P(FAKE), 4, 32, P(FAKE), P(0)) == -1
+    assert L.mx_dequantize(P(FAKE), P(FAKE), 4, 33, P(FAKE), P(0)) == -2

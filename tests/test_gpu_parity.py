@@ -1,0 +1,320 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle on the same
+seeded inputs.  Codes, scale bytes and rounding decisions must match bit for bit;
+products must agree with the FP64 product of the same dequantized operands to
+1e-5 (normwise, and per entry relative to sum_k |a||b|)."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def mx():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2502_20853_amd as mx
+    mx.binding.lib()
+    return mx
+
+
+def dev(a, dtype="f32"):
+    t = torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    return t.to(torch.bfloat16) if dtype == "bf16" else t
+
+
+def host(t):
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+def assert_same_bytes(got, want, what):
+    got = host(got)
+    assert got.shape == want.shape, (what, got.shape, want.shape)
+    bad = np.flatnonzero(got.ravel() != want.ravel())
+    assert bad.size == 0, "%s: %d of %d bytes differ, first at %d (got %d want %d)" % (
+        what, bad.size, want.size, bad[0], got.ravel()[bad[0]], want.ravel()[bad[0]])
+
+
+def mixed_matrix(rows, cols, seed, dtype):
+    import mx_workloads as wl
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((rows, cols)).astype(np.float32)
+    x *= np.exp(rng.uniform(-6, 6, (rows, 1))).astype(np.float32)     # row scales spread over many binades
+    x[:, rng.integers(0, cols, 3)] *= 20
+    x[rng.integers(0, rows, 4), :32] = 0                              # all-zero groups
+    x[0, :8] = [0.25, 0.75, -0.25, -0.75, 2.5, -2.5, 5.0, -5.0]       # exact midpoints after scaling
+    x[0, 8] = 6.0
+    if rows > 1:
+        x[1, :4] = [-0.0, 0.0, 1e-30, -1e-30]
+    return wl.round_to_bf16(x) if dtype == "bf16" else x
+
+
+# ------------------------------------------------------------------ rows ----
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("rnd", [0, 1])
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("shape", [(256, 192), (37, 1056), (1, 32)])
+def test_quantize_rows(mx, orc, dtype, rnd, mode, shape):
+    x = mixed_matrix(*shape, seed=10 + shape[0], dtype=dtype)
+    want = orc.quantize(x, round=rnd, scale_mode=mode, seed=77, tensor_id=3, index_base=4096)
+    got = mx.mx_quantize(dev(x, dtype), rnd, mode, seed=77, tensor_id=3, index_base=4096)
+    assert_same_bytes(got[1], want[1], "scales")
+    assert_same_bytes(got[0], want[0], "codes")
+
+
+def test_quantize_rows_strided_and_seed_64bit(mx, orc):
+    big = mixed_matrix(64, 256, seed=3, dtype="bf16")
+    view = big[:, 64:192]
+    seed = 0xDEADBEEF12345678
+    want = orc.quantize(view, round=1, seed=seed, tensor_id=0xFFFFFFFF, index_base=(1 << 36) + 8)
+    t = dev(big, "bf16")[:, 64:192]
+    got = mx.mx_quantize(t, 1, 0, seed=seed, tensor_id=0xFFFFFFFF, index_base=(1 << 36) + 8)
+    assert_same_bytes(got[0], want[0], "codes")
+    assert_same_bytes(got[1], want[1], "scales")
+
+
+def test_quantize_extreme_values(mx, orc):
+    # subnormals, the clamp at s = -127, the largest finite inputs, exact powers of two and 1.5*2^e
+    rows = 64
+    x = np.zeros((rows, 64), np.float32)
+    bits = np.array([0x00000001, 0x00000100, 0x007FFFFF, 0x00800000, 0x00C00000, 0x00C00001, 0x01000000,
+                     0x3FC00000, 0x3FC00001, 0x3FBFFFFF, 0x7F7FFFFF, 0x7F000000, 0x7E800000, 0x40C00000,
+                     0x40C00001, 0x3F800000], np.uint32)
+    for i, b in enumerate(bits):
+        x[i, 0] = np.array([b], np.uint32).view(np.float32)[0]
+        x[i, 1:32] = x[i, 0] * np.linspace(-1, 1, 31, dtype=np.float32)
+        x[i, 32] = -x[i, 0]
+        x[i, 33:64] = x[i, 0] * np.float32(2.0) ** -np.arange(1, 32, dtype=np.float32) * 1.7
+    rng = np.random.default_rng(0)
+    x[16:] = rng.standard_normal((rows - 16, 64)).astype(np.float32) * np.float32(2.0) ** rng.integers(-140, 120, (rows - 16, 1)).astype(np.float32)
+    x = np.nan_to_num(x, posinf=3e38, neginf=-3e38)
+    for rnd in (0, 1):
+        for mode in (0, 1):
+            want = orc.quantize(x, round=rnd, scale_mode=mode, seed=5, tensor_id=1)
+            got = mx.mx_quantize(dev(x), rnd, mode, seed=5, tensor_id=1)
+            assert_same_bytes(got[1], want[1], "scales r%d m%d" % (rnd, mode))
+            assert_same_bytes(got[0], want[0], "codes r%d m%d" % (rnd, mode))
+
+
+def test_sr_zero_draw_on_tiny_elements(mx, orc):
+    # elements whose 16 random bits are 0 round up iff p > 0, however small p is:
+    # put values ~2^-40 of the group maximum exactly there
+    seed, tid, n = 9, 2, 1 << 18
+    r = np.array([orc.sr_bits(seed, tid, e) for e in range(n)])
+    zeros = np.flatnonzero(r == 0)
+    assert zeros.size > 0
+    x = np.ones(n, np.float32)
+    x[zeros] = np.float32(2.0) ** -40
+    x[zeros[::2]] = np.float32(2.0) ** -140          # scaled value underflows to a subnormal
+    x = x.reshape(-1, 256)
+    want = orc.quantize(x, round=1, seed=seed, tensor_id=tid)
+    got = mx.mx_quantize(dev(x), 1, 0, seed=seed, tensor_id=tid)
+    assert_same_bytes(got[0], want[0], "codes")
+    flat = orc.dequantize(*want).ravel()
+    assert np.all(flat[zeros] > 0)                   # they did round up to 0.5 * S
+
+
+# ------------------------------------------------------------ transposed ----
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("pre,rr,rt,want_row", [(1, 0, 1, True), (0, 1, 1, True), (1, 0, 0, False),
+                                                 (0, 0, 1, False), (1, 1, 1, True), (0, 0, 0, True)])
+@pytest.mark.parametrize("shape", [(256, 192), (96, 320), (32, 32), (544, 96)])
+def test_quantize_transposed(mx, orc, dtype, pre, rr, rt, want_row, shape):
+    x = mixed_matrix(*shape, seed=20 + shape[1], dtype=dtype)
+    kw = dict(round_t=rt, tensor_id_t=6, pre_quant=pre, want_row=want_row, round_row=rr, tensor_id_row=1,
+              seed=1234, index_base=64)
+    want = orc.quantize_transposed(x, **kw)
+    got = mx.mx_quantize_transposed(dev(x, dtype), **kw)
+    names = ["codes_t", "scales_t", "codes_row", "scales_row"]
+    for i in (1, 0, 3, 2):
+        if want[i] is None:
+            assert got[i] is None
+        else:
+            assert_same_bytes(got[i], want[i], names[i])
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_quantize_transposed_floor_and_given_row(mx, orc, mode):
+    x = mixed_matrix(128, 160, seed=31, dtype="bf16")
+    kw = dict(round_t=1, tensor_id_t=4, pre_quant=1, want_row=True, round_row=0, tensor_id_row=2,
+              scale_mode=mode, seed=99)
+    want = orc.quantize_transposed(x, **kw)
+    got = mx.mx_quantize_transposed(dev(x, "bf16"), **kw)
+    for i, nm in enumerate(["codes_t", "scales_t", "codes_row", "scales_row"]):
+        assert_same_bytes(got[i], want[i], nm)
+    # same result when the row codes are handed in and no source is given
+    rc, rs = dev(want[2]), dev(want[3])
+    got2 = mx.mx_quantize_transposed(None, 1, 4, 1, False, row_in=(rc, rs), scale_mode=mode, seed=99,
+                                     shape=x.shape)
+    assert_same_bytes(got2[0], want[0], "codes_t (given row)")
+    assert_same_bytes(got2[1], want[1], "scales_t (given row)")
+
+
+def test_quantize_transposed_strided(mx, orc):
+    big = mixed_matrix(64, 384, seed=41, dtype="f32")
+    kw = dict(round_t=1, tensor_id_t=5, pre_quant=0, want_row=True, round_row=1, tensor_id_row=3, seed=7)
+    want = orc.quantize_transposed(big[:, 128:352], **kw)
+    got = mx.mx_quantize_transposed(dev(big)[:, 128:352], **kw)
+    for i, nm in enumerate(["codes_t", "scales_t", "codes_row", "scales_row"]):
+        assert_same_bytes(got[i], want[i], nm)
+
+
+# ----------------------------------------------------------------- Q-EMA ----
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("mode", [0, 1])
+def test_ema_weight_quant(mx, orc, dtype, mode):
+    import mx_workloads as wl
+    steps = list(wl.weight_walk(96, 160, seed=0, steps=6, sigma=4e-4))
+    ema_o = np.zeros_like(steps[0])
+    ema_g = torch.zeros(steps[0].shape, dtype=torch.float32, device="cuda")
+    for t, w in enumerate(steps):
+        w = wl.round_to_bf16(w) if dtype == "bf16" else w
+        upd = 2 if t == 0 else 1
+        want = orc.ema_weight_quant(w, ema_o, beta=0.9, update_ema=upd, scale_mode=mode)
+        got = mx.mx_ema_weight_quant(dev(w, dtype), ema_g, 0.9, upd, mode)
+        assert_same_bytes(ema_g.view(torch.uint8), ema_o.view(np.uint8), "w_ema step %d" % t)
+        assert_same_bytes(got[1], want[1], "scales step %d" % t)
+        assert_same_bytes(got[0], want[0], "codes step %d" % t)
+    # update_ema = 0 leaves the state alone; an EMA far from w still stays inside w's bracket
+    before = host(ema_g).copy()
+    far = (steps[-1] * np.float32(-3.0)).astype(np.float32)
+    want = orc.ema_weight_quant(steps[-1], far.copy(), update_ema=0, scale_mode=mode)
+    got = mx.mx_ema_weight_quant(dev(steps[-1]), dev(far), 0.5, 0, mode)
+    assert_same_bytes(got[0], want[0], "codes far ema")
+    assert np.array_equal(host(ema_g), before)
+
+
+# ------------------------------------------------------------------ GEMM ----
+
+def random_packed(rows, k, seed, scale_lo=110, scale_hi=140):
+    rng = np.random.default_rng(seed)
+    codes = rng.integers(0, 256, (rows, k // 2), dtype=np.uint8)
+    scales = rng.integers(scale_lo, scale_hi, (rows, k // 32), dtype=np.uint8)
+    return codes, scales
+
+
+def check_product(orc, got, ac, as_, bc, bs, what, tol=1e-5):
+    ref = orc.gemm_f64(ac, as_, bc, bs)
+    absref = np.abs(orc.dequantize(ac, as_)) @ np.abs(orc.dequantize(bc, bs)).T
+    got = host(got).astype(np.float64)
+    assert got.shape == ref.shape
+    err = np.abs(got - ref)
+    assert np.linalg.norm(err) <= tol * np.linalg.norm(ref), (what, np.linalg.norm(err) / np.linalg.norm(ref))
+    worst = (err / (absref + 1e-300)).max()
+    assert worst <= tol, (what, worst)
+
+
+@pytest.mark.parametrize("m,n,k", [(256, 768, 192), (16, 16, 128), (1, 1, 32), (300, 200, 96),
+                                    (515, 260, 1056), (64, 1000, 4096), (257, 255, 160)])
+def test_gemm_random_codes(mx, orc, m, n, k):
+    ac, as_ = random_packed(m, k, 1)
+    bc, bs = random_packed(n, k, 2)
+    got = mx.mx_linear_fwd(dev(ac), dev(as_), dev(bc), dev(bs))
+    check_product(orc, got, ac, as_, bc, bs, "fwd %dx%dx%d" % (m, n, k))
+
+
+def test_gemm_scale_bytes_and_one_hot(mx, orc):
+    # operand with a single nonzero per row pins the lane <-> (row, K block) mapping of codes and scales
+    m, n, k = 48, 40, 256
+    ac = np.zeros((m, k // 2), np.uint8)
+    bc = np.full((n, k // 2), 0x22, np.uint8)                 # all ones (code 2 = 1.0)
+    as_ = np.full((m, k // 32), 127, np.uint8)
+    bs = np.zeros((n, k // 32), np.uint8)
+    for j in range(n):
+        bs[j] = 120 + (np.arange(k // 32) + j) % 16           # a different power of two per (row, group)
+    for i in range(m):
+        kk = (37 * i + 5) % k
+        ac[i, kk // 2] = 0x05 if kk % 2 == 0 else 0x50        # 3.0 at column kk
+        as_[i, kk // 32] = 127 + (i % 5)
+    got = mx.mx_linear_fwd(dev(ac), dev(as_), dev(bc), dev(bs))
+    ref = orc.gemm_f64(ac, as_, bc, bs)
+    assert np.array_equal(host(got).astype(np.float64), ref)  # single products of powers of two: exact
+
+
+def test_gemm_three_entry_points_and_split_k(mx, orc):
+    N, C, D = 4096 + 32, 96, 160                              # dW contracts over N: K-split path
+    xc, xs = random_packed(N, D, 3)
+    wc, ws = random_packed(C, D, 4)
+    dyc, dys = random_packed(N, C, 5, 100, 120)
+    wtc, wts = random_packed(D, C, 6)
+    dytc, dyts = random_packed(C, N, 7, 100, 120)
+    xtc, xts = random_packed(D, N, 8)
+    check_product(orc, mx.mx_linear_fwd(dev(xc), dev(xs), dev(wc), dev(ws)), xc, xs, wc, ws, "fwd")
+    check_product(orc, mx.mx_linear_bwd_dx(dev(dyc), dev(dys), dev(wtc), dev(wts)), dyc, dys, wtc, wts, "dx")
+    assert mx.mx_linear_workspace_bytes(mx.GEMM_BWD_DW, N, C, D) > 0
+    check_product(orc, mx.mx_linear_bwd_dw(dev(dytc), dev(dyts), dev(xtc), dev(xts)), dytc, dyts, xtc, xts, "dw")
+
+
+def test_gemm_bf16_output_and_ld(mx, orc):
+    m, n, k = 130, 72, 224
+    ac, as_ = random_packed(m, k, 11, 120, 130)
+    bc, bs = random_packed(n, k, 12, 120, 130)
+    ref = orc.gemm_f64(ac, as_, bc, bs)
+    out = torch.full((m, 80), 7.0, dtype=torch.bfloat16, device="cuda")
+    mx.mx_linear_fwd(dev(ac), dev(as_), dev(bc), dev(bs), out=out[:, :n])
+    got = host(out.float())
+    assert np.all(got[:, n:] == 7.0)                          # columns beyond n untouched
+    absref = np.abs(orc.dequantize(ac, as_)) @ np.abs(orc.dequantize(bc, bs)).T
+    assert np.all(np.abs(got[:, :n] - ref) <= np.abs(ref) * 2.0 ** -8 + 1e-5 * absref)   # one bf16 ulp
+    f32 = host(mx.mx_linear_fwd(dev(ac), dev(as_), dev(bc), dev(bs)))
+    want = host(torch.from_numpy(f32).cuda().to(torch.bfloat16).float())
+    assert np.array_equal(got[:, :n], want)                   # RNE of the FP32 result
+
+
+# ------------------------------------------------------------ whole layer ----
+
+def oracle_layer(orc, X, W, dY, seed):
+    xt = orc.quantize_transposed(X, round_t=1, tensor_id_t=6, pre_quant=1, round_row=0, tensor_id_row=1, seed=seed)
+    wt = orc.quantize_transposed(W, round_t=1, tensor_id_t=4, pre_quant=1, round_row=0, tensor_id_row=2, seed=seed)
+    dy = orc.quantize_transposed(dY, round_t=1, tensor_id_t=5, pre_quant=0, round_row=1, tensor_id_row=3, seed=seed)
+    return xt, wt, dy
+
+
+def test_layer_c1_single(mx, orc):
+    import mx_workloads as wl
+    N, D, C = 256, 192, 768
+    X, W, dY = wl.linear_layer(N, D, C, seed=0, dtype="f32", outliers=4)
+    xt, wt, dy = oracle_layer(orc, X, W, dY, seed=0)
+    step = mx.MxLinearStep(N, D, C, out_dtype=torch.float32)
+    y = step.forward(dev(X), dev(W), seed=0)
+    dx, dw = step.backward(dev(dY), seed=0)
+    for got, want, nm in ((step.xq, xt[2], "Q1"), (step.xs, xt[3], "S1"), (step.xtq, xt[0], "Q6"), (step.xts, xt[1], "S6"),
+                          (step.wq, wt[2], "Q2"), (step.ws, wt[3], "S2"), (step.wtq, wt[0], "Q4"), (step.wts, wt[1], "S4"),
+                          (step.dyq, dy[2], "Q3"), (step.dys, dy[3], "S3"), (step.dytq, dy[0], "Q5"), (step.dyts, dy[1], "S5")):
+        assert_same_bytes(got, want, nm)
+    check_product(orc, y, xt[2], xt[3], wt[2], wt[3], "Y")
+    check_product(orc, dx, dy[2], dy[3], wt[0], wt[1], "dX")
+    check_product(orc, dw, dy[0], dy[1], xt[0], xt[1], "dW")
+
+
+def test_layer_qema_variant(mx, orc):
+    import mx_workloads as wl
+    N, D, C = 128, 96, 160
+    X, _, dY = wl.linear_layer(N, D, C, seed=1)
+    step = mx.MxLinearStep(N, D, C, out_dtype=torch.float32, qema=True, beta=0.998)
+    ema = None
+    for t, W in enumerate(wl.weight_walk(C, D, seed=1, steps=3)):
+        if ema is None:
+            ema = np.zeros_like(W)
+        wc, wsc = orc.ema_weight_quant(W, ema, beta=0.998, update_ema=2 if t == 0 else 1)
+        wt = orc.quantize_transposed(W, round_t=1, tensor_id_t=4, pre_quant=1, want_row=False, row_in=(wc, wsc), seed=t)
+        y = step.forward(dev(X), dev(W), seed=t)
+        assert_same_bytes(step.wq, wc, "Q-EMA codes step %d" % t)
+        assert_same_bytes(step.wtq, wt[0], "Q4 of Q-EMA step %d" % t)
+        assert_same_bytes(step.wts, wt[1], "S4 of Q-EMA step %d" % t)
+    xq = orc.quantize(X)
+    check_product(orc, y, xq[0], xq[1], wc, wsc, "Y with Q-EMA weight")
+
+
+def test_determinism(mx):
+    x = dev(mixed_matrix(256, 512, seed=5, dtype="bf16"), "bf16")
+    a = mx.mx_quantize_transposed(x, 1, 6, 1, True, 0, 1, seed=3)
+    b = mx.mx_quantize_transposed(x, 1, 6, 1, True, 0, 1, seed=3)
+    c = mx.mx_quantize_transposed(x, 1, 6, 1, True, 0, 1, seed=4)
+    assert all(torch.equal(p, q) for p, q in zip(a, b))
+    assert torch.equal(a[2], c[2]) and not torch.equal(a[0], c[0])   # RTN row codes ignore the seed
