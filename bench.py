@@ -1,0 +1,171 @@
+"""Benchmark of the MXFP4 linear-layer hot path on one MI355X.
+
+One step = forward + backward of the four linear layers of a ViT-B/16 block
+(qkv, proj, fc1, fc2) at batch 256 (N = 50432 tokens): per layer the fused
+row/transposed quantizers of X, W and dY and the three block-scaled FP4
+products, all through the C ABI.  Prints one JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP4_TFLOPS = 10100.0      # MI355X dense FP4/FP6 matrix peak
+PEAK_HBM_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="vit_base_b256")
+    ap.add_argument("--tokens", type=int, default=None, help="override N (tokens) of the workload")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=1024)
+    ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "gemm_traffic.json"),
+                    help="HBM bytes per GEMM launch measured with rocprofv3 --pmc, if present")
+    return ap.parse_args()
+
+
+def gemm_flops(N, D, C):
+    return 3 * 2.0 * N * D * C
+
+
+def quant_bytes(rows, cols, src_bytes, fused=True):
+    # source read + codes and scales of each output layout
+    return rows * cols * (src_bytes + (2 if fused else 1) * (0.5 + 1.0 / 32))
+
+
+def cpu_baseline(layers, sample_tokens):
+    """The oracle, as it stands, on the first `sample_tokens` tokens of every layer."""
+    import numpy as np
+    import mx_workloads as wl
+    from oracle import mx_oracle as orc
+    orc.lib()
+    flops = 0.0
+    data = []
+    for (name, N, D, C) in layers:
+        X, W, dY = wl.linear_layer(sample_tokens, D, C, seed=0, dtype="bf16")
+        data.append((X, W, dY))
+        flops += gemm_flops(sample_tokens, D, C)
+    t0 = time.perf_counter()
+    for (X, W, dY) in data:
+        xt = orc.quantize_transposed(X, round_t=1, tensor_id_t=6, pre_quant=1, round_row=0, tensor_id_row=1, seed=0)
+        wt = orc.quantize_transposed(W, round_t=1, tensor_id_t=4, pre_quant=1, round_row=0, tensor_id_row=2, seed=0)
+        dy = orc.quantize_transposed(dY, round_t=1, tensor_id_t=5, pre_quant=0, round_row=1, tensor_id_row=3, seed=0)
+        orc.gemm_f64(xt[2], xt[3], wt[2], wt[3])
+        orc.gemm_f64(dy[2], dy[3], wt[0], wt[1])
+        orc.gemm_f64(dy[0], dy[1], xt[0], xt[1])
+    dt = time.perf_counter() - t0
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": orc.num_threads(), "kind": "oracle",
+            "sample": "first %d tokens of each of the %d layers (quantizers + FP64 products), %.1f s" % (
+                sample_tokens, len(layers), dt)}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import mx_workloads as wl
+    import paper_2502_20853_amd as mx
+    mx.binding.lib()                       # fails loudly if the HIP library is not built
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+
+    layers = wl.config_layers(args.workload, args.tokens)
+    cfg = wl.CONFIGS[args.workload]
+    steps_obj, inputs = [], []
+    for li, (name, N, D, C) in enumerate(layers):
+        X, W, dY = wl.device_linear_layer(N, D, C, seed=li, dtype=cfg["dtype"], outliers=cfg["outliers"])
+        inputs.append((X, W, dY))
+        steps_obj.append(mx.MxLinearStep(N, D, C, out_dtype=torch.bfloat16, dw_dtype=torch.float32))
+    torch.cuda.synchronize()
+
+    total_flops = sum(gemm_flops(N, D, C) for (_, N, D, C) in layers)
+    sb = 2 if cfg["dtype"] == "bf16" else 4
+    q_bytes = sum(quant_bytes(N, D, sb) + quant_bytes(C, D, sb) + quant_bytes(N, C, sb) for (_, N, D, C) in layers)
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    gemm_events, quant_events = [], []
+
+    def run_step(seed, record):
+        for st, (X, W, dY) in zip(steps_obj, inputs):
+            B = mx.binding
+            if record:
+                e = [ev() for _ in range(12)]
+                e[0].record()
+            B.mx_quantize_transposed(X, B.ROUND_SR, 6, 1, True, B.ROUND_RTN, 1, seed=seed, out=(st.xtq, st.xts, st.xq, st.xs))
+            if record: e[1].record()
+            st.quantize_weight(W, seed)
+            if record: e[2].record()
+            B.mx_linear_fwd(st.xq, st.xs, st.wq, st.ws, out=st.y, workspace=st.workspace)
+            if record: e[3].record()
+            B.mx_quantize_transposed(dY, B.ROUND_SR, 5, 0, True, B.ROUND_SR, 3, seed=seed, out=(st.dytq, st.dyts, st.dyq, st.dys))
+            if record: e[4].record()
+            B.mx_linear_bwd_dx(st.dyq, st.dys, st.wtq, st.wts, out=st.dx, workspace=st.workspace)
+            if record: e[5].record()
+            B.mx_linear_bwd_dw(st.dytq, st.dyts, st.xtq, st.xts, out=st.dw, workspace=st.workspace)
+            if record:
+                e[6].record()
+                quant_events.extend([(e[0], e[1]), (e[1], e[2]), (e[3], e[4])])
+                gemm_events.extend([(e[2], e[3]), (e[4], e[5]), (e[5], e[6])])
+
+    for w in range(args.warmup):
+        run_step(w, False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        run_step(1000 + s, True)           # events are recorded on the launch stream (torch's current stream)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt * 1e3 / args.steps
+
+    gemm_ms = sum(a.elapsed_time(b) for a, b in gemm_events) / args.steps      # per step, all 12 products
+    quant_ms = sum(a.elapsed_time(b) for a, b in quant_events) / args.steps
+    n_gemm = 3 * len(layers)
+    achieved = total_flops / (gemm_ms * 1e-3) / 1e12
+    traffic = None
+    if os.path.exists(args.traffic_json):
+        try:
+            tj = json.load(open(args.traffic_json))
+            if tj.get("workload") == args.workload and args.tokens is None:
+                traffic = tj.get("hbm_bytes_per_launch")
+        except Exception:
+            traffic = None
+
+    out = {
+        "metric": "MXFP4 linear fwd+bwd TFLOP/s at ViT-B shapes",
+        "value": total_flops / (dt / args.steps) / 1e12,
+        "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "mxfp4 (e2m1 x e8m0) products, f32 accumulate; %s sources" % cfg["dtype"],
+        "data": "synthetic",
+        "config": {"workload": "%s: N=%d tokens, layers %s, Y/dX bf16, dW f32" % (
+            args.workload, layers[0][1], ",".join("%s %d->%d" % (n, d, c) for (n, _, d, c) in layers)),
+            "quantizers": "Q1,Q2 RTN; Q3..Q6 stochastic (Philox4x32-10); truncation-free scale; double quantization"},
+        "roofline": {"bound": "mfma", "kernel": "mx_gemm_kernel (12 launches per step)",
+                     "achieved": achieved, "peak": PEAK_FP4_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_FP4_TFLOPS,
+                     "flops_per_launch": total_flops / n_gemm, "avg_launch_ms": gemm_ms / n_gemm,
+                     "traffic": traffic},
+        "quantizers": {"bound": "hbm", "achieved": q_bytes / (quant_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
+                       "unit": "GB/s", "frac": q_bytes / (quant_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                       "ms_per_step": quant_ms, "bytes_per_step": q_bytes},
+        "gemm_ms_per_step": gemm_ms,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(layers, args.cpu_sample_tokens)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

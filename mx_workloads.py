@@ -95,3 +95,27 @@ def config_layers(name, n_tokens=None):
     cfg = CONFIGS[name]
     N = cfg["N"] if n_tokens is None else n_tokens
     return [(ln, N, d, c) for (ln, d, c) in cfg["layers"]]
+
+
+# ---- the same laws drawn directly in device memory (for the benchmark's large tensors) ----
+
+def device_linear_layer(N, D, C, seed=0, dtype="bf16", outliers=None, device="cuda"):
+    """(X[N,D], W[C,D], dY[N,C]) as torch tensors on `device`, same distributions as
+    linear_layer() but drawn with torch's generator (a different stream of numbers)."""
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed(int(seed) * 1000003 + N * 31 + D * 17 + C)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    x = torch.randn((N, D), generator=g, device=device, dtype=torch.float32)
+    cols = torch.randperm(D, generator=g, device=device)[:_n_outliers(D, outliers)]
+    x[:, cols] *= 20.0
+    w = torch.randn((C, D), generator=g, device=device, dtype=torch.float32) * 0.02
+    z = torch.randn((N, C), generator=g, device=device, dtype=torch.float32)
+    chi = torch.zeros((N, C), device=device, dtype=torch.float32)
+    for _ in range(3):
+        t = torch.randn((N, C), generator=g, device=device, dtype=torch.float32)
+        chi += t * t
+        del t
+    dy = z / torch.sqrt(chi / 3.0) * 1e-3
+    del z, chi
+    return x.to(tdt), w.to(tdt), dy.to(tdt)
