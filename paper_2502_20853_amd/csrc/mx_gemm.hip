@@ -287,18 +287,462 @@ __global__ void splitk_reduce_kernel(const float* part, int split, uint32_t m, u
 
 constexpr int G_BM = 256, G_BN = 256, G_WM = 128, G_WN = 64;
 
+// ---------------------------------------------------------------------------
+// Fast path (K a multiple of 128): V_MFMA_SCALE_F32_32X32X64_F8F6F4, operands
+// streamed global -> LDS by the DMA form of the load instructions.
+//
+//   workgroup 256 threads = 4 waves stacked along m; tile 256 (m) x 128 (n); wave
+//   tile 64 x 128 = 2 x 4 MFMA tiles of 32 x 32 (128 accumulator registers).
+//   Two workgroups fit on a CU (LDS 78 KB, <= 256 VGPRs): while one is waiting for
+//   its first loads, sitting at a barrier or storing its output, the other one
+//   keeps the matrix cores busy.
+//   One 32x32x64 MFMA takes, per lane, the 32 K elements (16 bytes) of row
+//   lane % 32, K block lane / 32, and that group's scale byte.
+//   A stage (K step of 128) holds A codes [256][64 B], B codes [128][64 B],
+//   A scales [256][4 B], B scales [128][4 B]; three stages.  A DMA load of 16 bytes
+//   per lane lands at lds_base + 16 * lane, so lane i of the load that covers 16
+//   rows fetches row i / 4, 16-byte chunk (i % 4) ^ ((row >> 2) & 3): the tile sits
+//   in LDS row-major with XOR-swizzled chunks and the MFMA operand reads (32 rows
+//   of one chunk per half wave) are bank-conflict free.
+//   Rows past the matrix edge read the last valid row instead (their products
+//   land in output rows/columns that are never stored).
+//   Per K step: wait for this wave's loads of the stage, barrier, issue the loads
+//   of stage +2, 12 operand reads + 16 MFMAs.
+//   Epilogue: accumulators go through a per-wave LDS strip so that every global
+//   store is 16 bytes per lane and whole 256/512-byte row segments per wave.
+// ---------------------------------------------------------------------------
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+constexpr int D_BM = 256, D_BN = 128, D_STAGES = 3, D_NT = 256, D_WAVES = 4;
+constexpr int D_A_OFF = 0;
+constexpr int D_B_OFF = D_BM * 64;                          // 16384
+constexpr int D_SA_OFF = (D_BM + D_BN) * 64;                // 24576
+constexpr int D_SB_OFF = D_SA_OFF + D_BM * 4;               // 25600
+constexpr int D_STAGE_BYTES = D_SB_OFF + D_BN * 4;          // 26112
+constexpr int D_LDS_BYTES = D_STAGES * D_STAGE_BYTES;       // 78336: two workgroups per CU
+constexpr int D_LOADS_PER_STAGE = 8;                        // per wave: 4 A + 2 B code loads, 2 scale loads
+constexpr int D_EP_PITCH_F32 = 528, D_EP_PITCH_BF16 = 264;  // bytes per 128-column strip row, padded
+constexpr int D_EP_BYTES = 32 * D_EP_PITCH_F32;             // per wave
+static_assert(D_WAVES * D_EP_BYTES <= D_LDS_BYTES, "epilogue strips must fit in the stage buffers");
+
+#define MX_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
+#define MX_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
+
+// Accumulators -> per-wave LDS strip (32 rows x 128 columns) -> global, so that every
+// store is 16 bytes per lane and a wave writes whole row segments.  The LDS region must
+// no longer be in use by any wave of the workgroup.  The wave owns output rows
+// [mrow0, mrow0 + 64) and columns [nbase, nbase + 128).
+__device__ __forceinline__ void gemm_epilogue_32x32(const GemmArgs& g, uint8_t* ep, v16f (&acc)[2][4],
+                                                    uint32_t mrow0, uint32_t nbase, int lane, uint32_t zsplit)
+{
+    const uint32_t lrow = lane & 31, lhalf = lane >> 5;
+    float* cf = static_cast<float*>(g.c);
+    uint16_t* ch = static_cast<uint16_t*>(g.c);
+    int64_t ldc = g.ldc;
+    if (g.split_k > 1) {
+        cf += (size_t)zsplit * g.m * g.n;
+        ldc = g.n;
+    }
+    const bool as_bf16 = g.c_bf16 && g.split_k == 1;
+    if (as_bf16) {
+        const bool vec_ok = (ldc & 7) == 0 && (reinterpret_cast<uintptr_t>(ch) & 15) == 0;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    uint2 pk;
+                    pk.x = (uint32_t)f32_to_bf16_rne(acc[i][j][4 * q]) | ((uint32_t)f32_to_bf16_rne(acc[i][j][4 * q + 1]) << 16);
+                    pk.y = (uint32_t)f32_to_bf16_rne(acc[i][j][4 * q + 2]) | ((uint32_t)f32_to_bf16_rne(acc[i][j][4 * q + 3]) << 16);
+                    *reinterpret_cast<uint2*>(ep + lrow * D_EP_PITCH_BF16 + (32 * j + 8 * q + 4 * lhalf) * 2) = pk;
+                }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+            for (int it = 0; it < 8; ++it) {
+                const uint32_t row = it * 4 + (lane >> 4), col = (lane & 15) * 8;
+                const uint32_t mm = mrow0 + i * 32 + row, nn = nbase + col;
+                uint4 v = *reinterpret_cast<const uint4*>(ep + row * D_EP_PITCH_BF16 + col * 2);
+                if (mm < g.m && nn < g.n) {
+                    uint16_t* dst = ch + (size_t)mm * ldc + nn;
+                    if (nn + 8 <= g.n && vec_ok) {
+                        *reinterpret_cast<uint4*>(dst) = v;
+                    } else {
+                        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+                        for (int e = 0; e < 8; ++e)
+                            if (nn + e < g.n) dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+                    }
+                }
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        }
+    } else {
+        const bool vec_ok = (ldc & 3) == 0 && (reinterpret_cast<uintptr_t>(cf) & 15) == 0;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    *reinterpret_cast<float4*>(ep + lrow * D_EP_PITCH_F32 + (32 * j + 8 * q + 4 * lhalf) * 4) =
+                        make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+            for (int it = 0; it < 16; ++it) {
+                const uint32_t row = it * 2 + (lane >> 5), col = (lane & 31) * 4;
+                const uint32_t mm = mrow0 + i * 32 + row, nn = nbase + col;
+                float4 v = *reinterpret_cast<const float4*>(ep + row * D_EP_PITCH_F32 + col * 4);
+                if (mm < g.m && nn < g.n) {
+                    float* dst = cf + (size_t)mm * ldc + nn;
+                    if (nn + 4 <= g.n && vec_ok) {
+                        *reinterpret_cast<float4*>(dst) = v;
+                    } else {
+                        const float w[4] = {v.x, v.y, v.z, v.w};
+                        for (int e = 0; e < 4; ++e)
+                            if (nn + e < g.n) dst[e] = w[e];
+                    }
+                }
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        }
+    }
+}
+
+// Workgroup -> (K split, tile).  The grid is one-dimensional over split * tiles.  Workgroup
+// ids go round-robin over the 8 XCDs, each with its own L2, so id % 8 = XCD gets a
+// contiguous range of the logical order (split, m tile, n tile): the workgroups that share
+// an A row panel or a B panel of one K range run on the same XCD at about the same time.
+__device__ __forceinline__ void decode_tile(const GemmArgs& g, uint32_t& zsplit, uint32_t& tm, uint32_t& tn)
+{
+    const uint32_t tiles = g.tiles_m * g.tiles_n, nblk = tiles * (uint32_t)g.split_k;
+    uint32_t bid = blockIdx.x;
+    uint32_t per = nblk / 8, rem = nblk % 8;
+    uint32_t xcd = bid % 8, idx = bid / 8;
+    bid = xcd * per + (xcd < rem ? xcd : rem) + idx;       // bijection on [0, nblk)
+    zsplit = bid / tiles;
+    uint32_t t = bid - zsplit * tiles;
+    tm = t / g.tiles_n;
+    tn = t - tm * g.tiles_n;
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt_then_barrier()
+{
+    // the memory clobber keeps LDS accesses on their side of the barrier
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+
+__global__ __launch_bounds__(D_NT, 2) void mx_gemm_dma_kernel(GemmArgs g)
+{
+    __shared__ __attribute__((aligned(1024))) uint8_t lds[D_LDS_BYTES];
+
+    uint32_t zsplit, tm, tn;
+    decode_tile(g, zsplit, tm, tn);
+    const uint32_t m0 = tm * D_BM, n0 = tn * D_BN;
+    const uint32_t kbeg = zsplit * g.k_per_split;
+    const uint32_t kend = min(g.k, kbeg + g.k_per_split);
+    const int nk = (int)((kend - kbeg) >> 7);
+    const uint32_t kbytes = g.k >> 1, kgroups = g.k >> 5;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t lrow = lane & 31, lhalf = lane >> 5;
+    const uint32_t swz = (lrow >> 2) & 3;
+
+    // ---- DMA sources (per lane): wave w loads A rows [64w, 64w+64) and B rows [32w, 32w+32) ----
+    const uint8_t* a_src[4];
+    const uint8_t* b_src[2];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        uint32_t row = (4 * wave + u) * 16 + (lane >> 2);
+        uint32_t ch = (lane & 3) ^ ((row >> 2) & 3);
+        a_src[u] = g.a_codes + (size_t)min(m0 + row, g.m - 1) * kbytes + (kbeg >> 1) + ch * 16;
+    }
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        uint32_t row = (2 * wave + u) * 16 + (lane >> 2);
+        uint32_t ch = (lane & 3) ^ ((row >> 2) & 3);
+        b_src[u] = g.b_codes + (size_t)min(n0 + row, g.n - 1) * kbytes + (kbeg >> 1) + ch * 16;
+    }
+    const uint8_t* sa_src = g.a_scales + (size_t)min(m0 + wave * 64 + lane, g.m - 1) * kgroups + (kbeg >> 5);
+    const uint8_t* sb_src = g.b_scales + (size_t)min(n0 + wave * 32 + lrow, g.n - 1) * kgroups + (kbeg >> 5);
+
+    auto issue = [&](int buf, int kt) {
+        uint8_t* base = lds + buf * D_STAGE_BYTES;
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            __builtin_amdgcn_global_load_lds(MX_GPTR(a_src[u] + kt * 64), MX_LPTR(base + D_A_OFF + (4 * wave + u) * 1024), 16, 0, 0);
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+            __builtin_amdgcn_global_load_lds(MX_GPTR(b_src[u] + kt * 64), MX_LPTR(base + D_B_OFF + (2 * wave + u) * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(MX_GPTR(sa_src + kt * 4), MX_LPTR(base + D_SA_OFF + wave * 256), 4, 0, 0);
+        if (lane < 32)      // 32 B rows per wave: the upper half wave sits this load out
+            __builtin_amdgcn_global_load_lds(MX_GPTR(sb_src + kt * 4), MX_LPTR(base + D_SB_OFF + wave * 128), 4, 0, 0);
+    };
+
+    v16f acc[2][4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    // Operand registers of one 64-K slice (one MFMA per accumulator tile) and the
+    // scale dwords of one K step, already shifted so that op_sel 0 / 2 picks the byte.
+    struct Frag { v4i a[2]; v4i b[4]; };
+    struct Scales { uint32_t a[2]; uint32_t b[4]; };
+    auto read_frag = [&](int buf, int kk, Frag& f) {
+        const uint8_t* base = lds + buf * D_STAGE_BYTES;
+        const uint32_t coff = ((2 * kk + lhalf) ^ swz) << 4;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            f.a[i] = *reinterpret_cast<const v4i*>(base + D_A_OFF + (wave * 64 + i * 32 + lrow) * 64 + coff);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            f.b[j] = *reinterpret_cast<const v4i*>(base + D_B_OFF + (j * 32 + lrow) * 64 + coff);
+    };
+    auto read_scales = [&](int buf, Scales& sc) {
+        const uint8_t* base = lds + buf * D_STAGE_BYTES;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            sc.a[i] = *reinterpret_cast<const uint32_t*>(base + D_SA_OFF + (wave * 64 + i * 32 + lrow) * 4);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            sc.b[j] = *reinterpret_cast<const uint32_t*>(base + D_SB_OFF + (j * 32 + lrow) * 4);
+    };
+    auto shift_scales = [&](Scales& sc) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) sc.a[i] >>= 8 * lhalf;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) sc.b[j] >>= 8 * lhalf;
+    };
+    auto mma = [&](const Frag& f, const Scales& sc, auto kc) {
+        constexpr int kk = decltype(kc)::value;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            v8i xa = v8i{f.a[i].x, f.a[i].y, f.a[i].z, f.a[i].w, 0, 0, 0, 0};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                v8i xb = v8i{f.b[j].x, f.b[j].y, f.b[j].z, f.b[j].w, 0, 0, 0, 0};
+                // first operand = n side, second = m side: a lane ends up with one m and runs of 4 n
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                    xb, xa, acc[i][j], 4, 4, 2 * kk, (int)sc.b[j], 2 * kk, (int)sc.a[i]);
+            }
+        }
+    };
+
+    // ---- main loop, software-pipelined by half K steps: the LDS reads of the next 64-K
+    //      slice are issued before the 8 MFMAs of the current one ----
+    if (nk > 0) issue(0, 0);
+    if (nk > 1) issue(1, 1);
+    if (nk > 1) wait_vmcnt_then_barrier<D_LOADS_PER_STAGE>();
+    else        wait_vmcnt_then_barrier<0>();
+    Frag f0, f1;
+    Scales sc, scn;
+    read_scales(0, sc);
+    read_frag(0, 0, f0);
+    shift_scales(sc);
+    for (int kt = 0; kt < nk; ++kt) {
+        const int cur = kt % D_STAGES;
+        read_frag(cur, 1, f1);
+        mma(f0, sc, std::integral_constant<int, 0>{});
+        if (kt + 1 < nk) {
+            // stage kt+1 was issued one K step ago; after the barrier every wave has also
+            // finished reading stage kt-1, whose buffer the next load overwrites
+            wait_vmcnt_then_barrier<0>();
+            if (kt + 2 < nk) issue((kt + 2) % D_STAGES, kt + 2);
+            const int nxt = (kt + 1) % D_STAGES;
+            read_scales(nxt, scn);
+            read_frag(nxt, 0, f0);
+        }
+        mma(f1, sc, std::integral_constant<int, 1>{});
+        if (kt + 1 < nk) {
+            shift_scales(scn);
+            sc = scn;
+        }
+    }
+    wait_vmcnt_then_barrier<0>();          // every wave is done reading the stage buffers
+
+    gemm_epilogue_32x32(g, lds + wave * D_EP_BYTES, acc, m0 + wave * 64, n0, lane, zsplit);
+}
+
+
+// ---------------------------------------------------------------------------
+// Main path: K range of at least 512 per split.  Same tile, wave layout and MFMA
+// schedule as mx_gemm_dma_kernel; what changes is how scale bytes travel.  Reading
+// 4 scale bytes per row and K step costs one L2 request per row and step -- as many
+// requests as the codes need.  Here a load brings 16 scale bytes per row (4 K steps)
+// into a two-slot ring, and the code stages shrink to two (the operand reads of a
+// stage are complete before the barrier that frees it).  The last scale block of a K
+// range is shifted back so that it ends where the range ends.
+//   LDS: codes 2 x (A [256][64 B] + B [128][64 B]); scales 2 x [384 rows][16 B].
+// ---------------------------------------------------------------------------
+constexpr int S_CODE_STAGE = (D_BM + D_BN) * 64;            // 24576
+constexpr int S_SCALE_OFF = 2 * S_CODE_STAGE;               // 49152
+constexpr int S_SCALE_SLOT = (D_BM + D_BN) * 16;            // 6144
+constexpr int S_LDS_BYTES = S_SCALE_OFF + 2 * S_SCALE_SLOT; // 61440 (epilogue strips need 67584)
+constexpr int S_LDS_ALLOC = D_WAVES * D_EP_BYTES > S_LDS_BYTES ? D_WAVES * D_EP_BYTES : S_LDS_BYTES;
+static_assert(2 * S_LDS_ALLOC <= 160 * 1024, "two workgroups per CU");
+
+__device__ __forceinline__ void drain_then_barrier()
+{
+    // all of this wave's loads have landed and all of its LDS reads have returned
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+__global__ __launch_bounds__(D_NT, 2) void mx_gemm_dma_sb_kernel(GemmArgs g)
+{
+    __shared__ __attribute__((aligned(1024))) uint8_t lds[S_LDS_ALLOC];
+
+    uint32_t zsplit, tm, tn;
+    decode_tile(g, zsplit, tm, tn);
+    const uint32_t m0 = tm * D_BM, n0 = tn * D_BN;
+    const uint32_t kbeg = zsplit * g.k_per_split;
+    const uint32_t kend = min(g.k, kbeg + g.k_per_split);
+    const int nk = (int)((kend - kbeg) >> 7);               // >= 4
+    const int nsb = (nk + 3) >> 2;                          // scale blocks of 4 K steps
+    const uint32_t kbytes = g.k >> 1, kgroups = g.k >> 5;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t lrow = lane & 31, lhalf = lane >> 5;
+    const uint32_t swz = (lrow >> 2) & 3;
+
+    const uint8_t* a_src[4];
+    const uint8_t* b_src[2];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        uint32_t row = (4 * wave + u) * 16 + (lane >> 2);
+        uint32_t ch = (lane & 3) ^ ((row >> 2) & 3);
+        a_src[u] = g.a_codes + (size_t)min(m0 + row, g.m - 1) * kbytes + (kbeg >> 1) + ch * 16;
+    }
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        uint32_t row = (2 * wave + u) * 16 + (lane >> 2);
+        uint32_t ch = (lane & 3) ^ ((row >> 2) & 3);
+        b_src[u] = g.b_codes + (size_t)min(n0 + row, g.n - 1) * kbytes + (kbeg >> 1) + ch * 16;
+    }
+    const uint8_t* sa_src = g.a_scales + (size_t)min(m0 + wave * 64 + lane, g.m - 1) * kgroups + (kbeg >> 5);
+    const uint8_t* sb_src = g.b_scales + (size_t)min(n0 + wave * 32 + lrow, g.n - 1) * kgroups + (kbeg >> 5);
+
+    auto issue_codes = [&](int kt) {
+        uint8_t* base = lds + (kt & 1) * S_CODE_STAGE;
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            __builtin_amdgcn_global_load_lds(MX_GPTR(a_src[u] + kt * 64), MX_LPTR(base + (4 * wave + u) * 1024), 16, 0, 0);
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+            __builtin_amdgcn_global_load_lds(MX_GPTR(b_src[u] + kt * 64), MX_LPTR(base + D_BM * 64 + (2 * wave + u) * 1024), 16, 0, 0);
+    };
+    auto scale_block_start = [&](int b) { return min(4 * b, nk - 4); };   // first K step the block covers
+    auto issue_scales = [&](int b) {
+        uint8_t* base = lds + S_SCALE_OFF + (b & 1) * S_SCALE_SLOT;
+        const int off = scale_block_start(b) * 4;
+        __builtin_amdgcn_global_load_lds(MX_GPTR(sa_src + off), MX_LPTR(base + wave * 1024), 16, 0, 0);
+        if (lane < 32)
+            __builtin_amdgcn_global_load_lds(MX_GPTR(sb_src + off), MX_LPTR(base + D_BM * 16 + wave * 512), 16, 0, 0);
+    };
+
+    v16f acc[2][4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    struct Frag { v4i a[2]; v4i b[4]; };
+    struct Scales { uint32_t a[2]; uint32_t b[4]; };
+    auto read_frag = [&](int kt, int kk, Frag& f) {
+        const uint8_t* base = lds + (kt & 1) * S_CODE_STAGE;
+        const uint32_t coff = ((2 * kk + lhalf) ^ swz) << 4;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            f.a[i] = *reinterpret_cast<const v4i*>(base + (wave * 64 + i * 32 + lrow) * 64 + coff);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            f.b[j] = *reinterpret_cast<const v4i*>(base + D_BM * 64 + (j * 32 + lrow) * 64 + coff);
+    };
+    auto read_scales = [&](int kt, Scales& sc) {
+        const int blk = kt >> 2;
+        const uint8_t* base = lds + S_SCALE_OFF + (blk & 1) * S_SCALE_SLOT + (kt - scale_block_start(blk)) * 4;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            sc.a[i] = *reinterpret_cast<const uint32_t*>(base + (wave * 64 + i * 32 + lrow) * 16);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            sc.b[j] = *reinterpret_cast<const uint32_t*>(base + (D_BM + j * 32 + lrow) * 16);
+    };
+    auto shift_scales = [&](Scales& sc) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) sc.a[i] >>= 8 * lhalf;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) sc.b[j] >>= 8 * lhalf;
+    };
+    auto mma = [&](const Frag& f, const Scales& sc, auto kc) {
+        constexpr int kk = decltype(kc)::value;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            v8i xa = v8i{f.a[i].x, f.a[i].y, f.a[i].z, f.a[i].w, 0, 0, 0, 0};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                v8i xb = v8i{f.b[j].x, f.b[j].y, f.b[j].z, f.b[j].w, 0, 0, 0, 0};
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                    xb, xa, acc[i][j], 4, 4, 2 * kk, (int)sc.b[j], 2 * kk, (int)sc.a[i]);
+            }
+        }
+    };
+
+    // ---- main loop, software-pipelined by half K steps ----
+    issue_codes(0);
+    issue_scales(0);
+    if (nsb > 1) issue_scales(1);
+    issue_codes(1);
+    wait_vmcnt_then_barrier<6>();          // all but the 6 code loads of stage 1
+    Frag f0, f1;
+    Scales sc, scn;
+    read_scales(0, sc);
+    read_frag(0, 0, f0);
+    shift_scales(sc);
+    for (int kt = 0; kt < nk; ++kt) {
+        read_frag(kt, 1, f1);
+        mma(f0, sc, std::integral_constant<int, 0>{});
+        if (kt + 1 < nk) {
+            // stage kt+1 (issued one K step ago) has landed; every wave's reads of stage kt
+            // have returned, so its buffer can take stage kt+2
+            drain_then_barrier();
+            if (kt + 2 < nk) issue_codes(kt + 2);
+            // the slot of scale block b-1 was last read one K step ago: refill it with block b+1
+            if ((kt & 3) == 3 && (kt >> 2) + 2 < nsb) issue_scales((kt >> 2) + 2);
+            read_scales(kt + 1, scn);
+            read_frag(kt + 1, 0, f0);
+        }
+        mma(f1, sc, std::integral_constant<int, 1>{});
+        if (kt + 1 < nk) {
+            shift_scales(scn);
+            sc = scn;
+        }
+    }
+    drain_then_barrier();                  // every wave is done reading the stage buffers
+
+    gemm_epilogue_32x32(g, lds + wave * D_EP_BYTES, acc, m0 + wave * 64, n0, lane, zsplit);
+}
+
 }  // namespace
 
 namespace mxl {
 
 int gemm_split_k(int64_t m, int64_t n, int64_t k)
 {
-    // Split K only when the output has too few tiles to fill the 256 CUs and K is long.
-    int64_t tiles = ((m + G_BM - 1) / G_BM) * ((n + G_BN - 1) / G_BN);
-    if (tiles >= 128 || k < 4096) return 1;
-    int64_t want = (256 + tiles - 1) / tiles;
+    // Split K only when the output has too few tiles to fill the machine and K is long.
+    // The fast kernel runs two 256 x 128 workgroups per CU: 512 slots on 256 CUs; the
+    // split is the largest that still fits in one round of slots.
+    const bool fast = (k & 127) == 0;
+    const int64_t bm = fast ? D_BM : G_BM, bn = fast ? D_BN : G_BN, slots = fast ? 512 : 256;
+    int64_t tiles = ((m + bm - 1) / bm) * ((n + bn - 1) / bn);
+    if (tiles * 2 > slots || k < 4096) return 1;
+    int64_t s = slots / tiles;
     int64_t max_by_k = k / 1024;                 // keep at least 8 K steps per split
-    int64_t s = want < max_by_k ? want : max_by_k;
+    if (s > max_by_k) s = max_by_k;
     if (s < 1) s = 1;
     if (s > 64) s = 64;
     return (int)s;
@@ -316,10 +760,20 @@ hipError_t launch_gemm(const GemmParams& p, hipStream_t st)
     g.split_k = (int)((ksteps + steps_per - 1) / steps_per);   // drop empty splits
     g.c = g.split_k > 1 ? p.workspace : p.c;
     g.ldc = p.ldc; g.c_bf16 = p.c_bf16;
-    g.tiles_m = (uint32_t)((p.m + G_BM - 1) / G_BM);
-    g.tiles_n = (uint32_t)((p.n + G_BN - 1) / G_BN);
-    dim3 grid(g.tiles_m * g.tiles_n, 1, g.split_k), block((G_BM / G_WM) * (G_BN / G_WN) * 64);
-    hipLaunchKernelGGL((mx_gemm_kernel<G_BM, G_BN, G_WM, G_WN>), grid, block, 0, st, g);
+    if ((p.k & 127) == 0) {
+        g.tiles_m = (uint32_t)((p.m + D_BM - 1) / D_BM);
+        g.tiles_n = (uint32_t)((p.n + D_BN - 1) / D_BN);
+        dim3 grid(g.tiles_m * g.tiles_n * g.split_k);
+        const uint32_t last_steps = ksteps - (uint32_t)(g.split_k - 1) * steps_per;
+        if (steps_per >= 4 && last_steps >= 4) hipLaunchKernelGGL(mx_gemm_dma_sb_kernel, grid, dim3(D_NT), 0, st, g);
+        else                                   hipLaunchKernelGGL(mx_gemm_dma_kernel, grid, dim3(D_NT), 0, st, g);
+    } else {
+        g.tiles_m = (uint32_t)((p.m + G_BM - 1) / G_BM);
+        g.tiles_n = (uint32_t)((p.n + G_BN - 1) / G_BN);
+        dim3 grid(g.tiles_m * g.tiles_n, 1, g.split_k);
+        dim3 block((G_BM / G_WM) * (G_BN / G_WN) * 64);
+        hipLaunchKernelGGL((mx_gemm_kernel<G_BM, G_BN, G_WM, G_WN>), grid, block, 0, st, g);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (g.split_k > 1) {

@@ -210,7 +210,12 @@ def check_product(orc, got, ac, as_, bc, bs, what, tol=1e-5):
 
 
 @pytest.mark.parametrize("m,n,k", [(256, 768, 192), (16, 16, 128), (1, 1, 32), (300, 200, 96),
-                                    (515, 260, 1056), (64, 1000, 4096), (257, 255, 160)])
+                                    (515, 260, 1056), (64, 1000, 4096), (257, 255, 160),
+                                    # K % 128 == 0: the DMA-fed 32x32x64 kernel (1 to 11 K steps, ragged m and n)
+                                    (1, 1, 128), (256, 256, 128), (300, 200, 384), (515, 260, 1024),
+                                    (257, 129, 256), (33, 700, 1408), (768, 768, 512),
+                                    # >= 4 K steps: 256-K stages, odd step counts, shifted last scale block
+                                    (40, 48, 640), (300, 520, 1152), (130, 260, 896), (64, 64, 2688)])
 def test_gemm_random_codes(mx, orc, m, n, k):
     ac, as_ = random_packed(m, k, 1)
     bc, bs = random_packed(n, k, 2)
@@ -250,12 +255,12 @@ def test_gemm_three_entry_points_and_split_k(mx, orc):
     check_product(orc, mx.mx_linear_bwd_dw(dev(dytc), dev(dyts), dev(xtc), dev(xts)), dytc, dyts, xtc, xts, "dw")
 
 
-def test_gemm_bf16_output_and_ld(mx, orc):
-    m, n, k = 130, 72, 224
+@pytest.mark.parametrize("m,n,k", [(130, 72, 224), (130, 72, 256), (300, 263, 384)])
+def test_gemm_bf16_output_and_ld(mx, orc, m, n, k):
     ac, as_ = random_packed(m, k, 11, 120, 130)
     bc, bs = random_packed(n, k, 12, 120, 130)
     ref = orc.gemm_f64(ac, as_, bc, bs)
-    out = torch.full((m, 80), 7.0, dtype=torch.bfloat16, device="cuda")
+    out = torch.full((m, n + 8), 7.0, dtype=torch.bfloat16, device="cuda")
     mx.mx_linear_fwd(dev(ac), dev(as_), dev(bc), dev(bs), out=out[:, :n])
     got = host(out.float())
     assert np.all(got[:, n:] == 7.0)                          # columns beyond n untouched
