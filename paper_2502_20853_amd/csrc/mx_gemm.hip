@@ -65,12 +65,20 @@ __device__ __forceinline__ uint32_t lds_scale_offset(uint32_t row, uint32_t kb, 
     return kb * tile_rows + (tile >> 2) * 64 + (row & 15u) * 4 + (tile & 3u);
 }
 
+// FP32 -> bf16, round to nearest even, with gfx950's packed convert instruction.
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint32_t f32x2_to_bf16x2(float lo, float hi)
+{
+    f32x2_t v = {lo, hi};
+    bf16x2_t b = __builtin_convertvector(v, bf16x2_t);
+    return *reinterpret_cast<uint32_t*>(&b);
+}
+
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
 {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40u);   // NaN stays NaN
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+    return (uint16_t)f32x2_to_bf16x2(f, 0.f);
 }
 
 template <int BM, int BN, int WM, int WN>
@@ -253,8 +261,8 @@ void mx_gemm_kernel(GemmArgs g)
             if (nn + 3 < g.n && vec_ok) {
                 if (as_bf16) {
                     uint2 pk;
-                    pk.x = (uint32_t)f32_to_bf16_rne(v.x) | ((uint32_t)f32_to_bf16_rne(v.y) << 16);
-                    pk.y = (uint32_t)f32_to_bf16_rne(v.z) | ((uint32_t)f32_to_bf16_rne(v.w) << 16);
+                    pk.x = f32x2_to_bf16x2(v.x, v.y);
+                    pk.y = f32x2_to_bf16x2(v.z, v.w);
                     *reinterpret_cast<uint2*>(ch + off) = pk;
                 } else {
                     *reinterpret_cast<float4*>(cf + off) = make_float4(v.x, v.y, v.z, v.w);
@@ -353,8 +361,8 @@ __device__ __forceinline__ void gemm_epilogue_32x32(const GemmArgs& g, uint8_t* 
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     uint2 pk;
-                    pk.x = (uint32_t)f32_to_bf16_rne(acc[i][j][4 * q]) | ((uint32_t)f32_to_bf16_rne(acc[i][j][4 * q + 1]) << 16);
-                    pk.y = (uint32_t)f32_to_bf16_rne(acc[i][j][4 * q + 2]) | ((uint32_t)f32_to_bf16_rne(acc[i][j][4 * q + 3]) << 16);
+                    pk.x = f32x2_to_bf16x2(acc[i][j][4 * q], acc[i][j][4 * q + 1]);
+                    pk.y = f32x2_to_bf16x2(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
                     *reinterpret_cast<uint2*>(ep + lrow * D_EP_PITCH_BF16 + (32 * j + 8 * q + 4 * lhalf) * 2) = pk;
                 }
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
