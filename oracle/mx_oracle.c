@@ -3,10 +3,10 @@
  * (arxiv 2502.20853).  TEST INFRASTRUCTURE ONLY: see mx_oracle.h.
  *
  * Every step is written the way the paper states it, one element at a time.
- * Precision: the scaled value y = x / S is formed in FP32 (exact except when it
- * underflows below 2^-126, where IEEE gradual underflow applies); every
- * comparison that picks a code is then evaluated exactly in FP64 on that FP32
- * value.  The EMA update is FP32.  Matrix products are FP64.
+ * Precision: S is a power of two, so the scaled value y = x / S of an FP32 input
+ * is exact in FP64 (2^-149 * 2^-127 is far inside its range); every comparison
+ * that picks a code is evaluated exactly in FP64 on that exact y.  The EMA
+ * update is FP32.  Matrix products are FP64.
  *
  * Build: gcc -O2 -std=c11 -fopenmp -ffp-contract=off -fPIC -shared mx_oracle.c -lm
  */
@@ -117,24 +117,24 @@ int orc_shared_exponent(float M, int scale_mode)
     return s;
 }
 
-/* x / S with S = 2^s, formed in FP32 (one IEEE rounding, only on underflow). */
-static float scale_to_group(float x, int s, int scale_mode)
+/* x / S with S = 2^s: exact in FP64. */
+static double scale_to_group(float x, int s, int scale_mode)
 {
-    float y = ldexpf(x, -s);
+    double y = ldexp((double)x, -s);
     if (scale_mode == ORC_SCALE_FLOOR) {
         /* Eq. 2's scale can leave |y| > Q_p: "exceeding values will be truncated" */
-        if (y > 6.0f) y = 6.0f;
-        if (y < -6.0f) y = -6.0f;
+        if (y > 6.0) y = 6.0;
+        if (y < -6.0) y = -6.0;
     }
     return y;
 }
 
 /* -------------------------------------------------------------- rounding -- */
 
-int orc_round_rtn(float y)
+static int round_rtn_d(double y)
 {
     int sign = signbit(y) ? 8 : 0;
-    double yd = (double)y, m1, m2, q1, q2;
+    double yd = y, m1, m2, q1, q2;
     bracket(fabs(yd), &m1, &m2);
     if (!sign) { q1 = m1;  q2 = m2;  }           /* q1 < q2 in signed terms */
     else       { q1 = -m2; q2 = -m1; }
@@ -142,24 +142,28 @@ int orc_round_rtn(float y)
     return sign | mag_index(fabs(pick));
 }
 
-int orc_round_sr(float y, uint32_t r16)
+int orc_round_rtn(float y) { return round_rtn_d((double)y); }
+
+static int round_sr_d(double y, uint32_t r16)
 {
     /* round_S: xi ~ U(-D/2, D/2), D = q2 - q1; q1 iff y + xi < (q1+q2)/2, so
      * P(q2) = (y - q1)/D and P(q1) = (q2 - y)/D.  On the magnitude a = |y| both
      * signs read: the larger magnitude m2 is taken with probability
      * p = (a - m1)/(m2 - m1).  The uniform variate is r16/65536. */
     int sign = signbit(y) ? 8 : 0;
-    double a = fabs((double)y), m1, m2;
+    double a = fabs(y), m1, m2;
     bracket(a, &m1, &m2);
     double p = (m2 > m1) ? (a - m1) / (m2 - m1) : 0.0;
     int up = ((double)r16 < 65536.0 * p);
     return sign | mag_index(up ? m2 : m1);
 }
 
-int orc_round_ema(float y, float z)
+int orc_round_sr(float y, uint32_t r16) { return round_sr_d((double)y, r16); }
+
+static int round_ema_d(double y, double z)
 {
     int sign = signbit(y) ? 8 : 0;
-    double yd = (double)y, zd = (double)z, m1, m2, q1, q2;
+    double yd = y, zd = z, m1, m2, q1, q2;
     bracket(fabs(yd), &m1, &m2);
     if (m1 == fabs(yd)) return sign | mag_index(m1);   /* y is an E2M1 value */
     if (!sign) { q1 = m1;  q2 = m2;  }
@@ -167,6 +171,8 @@ int orc_round_ema(float y, float z)
     double pick = (fabs(zd - q1) < fabs(zd - q2)) ? q1 : q2;
     return sign | mag_index(fabs(pick));
 }
+
+int orc_round_ema(float y, float z) { return round_ema_d((double)y, (double)z); }
 
 /* ------------------------------------------------------------ quantizers -- */
 
@@ -208,13 +214,13 @@ void orc_quantize(const float* src, int64_t rows, int64_t cols, int64_t ld,
             scales[r * groups + g] = (uint8_t)(s + 127);
             for (int i = 0; i < 32; ++i) {
                 int64_t c = 32 * g + i;
-                float y = scale_to_group(x[i], s, scale_mode);
+                double y = scale_to_group(x[i], s, scale_mode);
                 int code;
                 if (round == ORC_ROUND_SR) {
                     uint64_t e = index_base + (uint64_t)r * (uint64_t)cols + (uint64_t)c;
-                    code = orc_round_sr(y, orc_sr_bits(seed, tensor_id, e));
+                    code = round_sr_d(y, orc_sr_bits(seed, tensor_id, e));
                 } else {
-                    code = orc_round_rtn(y);
+                    code = round_rtn_d(y);
                 }
                 put_code(codes + r * (cols / 2), c, code);
             }
@@ -288,13 +294,13 @@ void orc_quantize_transposed(const float* src, int64_t rows, int64_t cols, int64
             scales_t[c * groups + g] = (uint8_t)(s + 127);
             for (int t = 0; t < 32; ++t) {
                 int64_t i = 32 * g + t;
-                float y = scale_to_group(x[t * cols], s, scale_mode);
+                double y = scale_to_group(x[t * cols], s, scale_mode);
                 int code;
                 if (round_t == ORC_ROUND_SR) {
                     uint64_t e = index_base + (uint64_t)i * (uint64_t)cols + (uint64_t)c;
-                    code = orc_round_sr(y, orc_sr_bits(seed, tensor_id_t, e));
+                    code = round_sr_d(y, orc_sr_bits(seed, tensor_id_t, e));
                 } else {
-                    code = orc_round_rtn(y);
+                    code = round_rtn_d(y);
                 }
                 put_code(codes_t + c * (rows / 2), i, code);
             }
@@ -330,9 +336,9 @@ void orc_ema_weight_quant(const float* w, float* w_ema, float beta, int update_e
             int s = orc_shared_exponent(M, scale_mode);
             scales[r * groups + g] = (uint8_t)(s + 127);
             for (int i = 0; i < 32; ++i) {
-                float y = scale_to_group(x[i], s, scale_mode);
-                float z = ldexpf(ema[i], -s);
-                put_code(codes + r * (cols / 2), 32 * g + i, orc_round_ema(y, z));
+                double y = scale_to_group(x[i], s, scale_mode);
+                double z = ldexp((double)ema[i], -s);
+                put_code(codes + r * (cols / 2), 32 * g + i, round_ema_d(y, z));
             }
         }
     }

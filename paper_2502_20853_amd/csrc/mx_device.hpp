@@ -1,9 +1,8 @@
 // Device-side building blocks of the MXFP4 quantizers (gfx950).
 //
 // Everything here works on FP32 bit patterns so that each decision (shared
-// exponent, bracket, rounding direction) is an exact integer or exact FP32
-// operation: the scaled value y = x * 2^-s and the position k of |y| inside its
-// E2M1 binade are power-of-two multiples of the input and therefore exact.
+// exponent, bracket, rounding direction) is an exact integer operation on a value
+// that is a power-of-two multiple of the input.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -41,52 +40,61 @@ __device__ __forceinline__ float fwd_scale(uint32_t byte)
 }
 
 // ---- E2M1 rounding (Sec. 3.2) ----------------------------------------------
-// y is the scaled value x / S.  Let a = |y| and E its binade, with everything
-// below 1 treated as the binade of 1 (E2M1's subnormal step equals the step of
-// [1,2)).  k = a / step(E) * ... lies in [0,4): floor(k) and floor(k)+1 are the
-// two neighbouring codes relative to 2*(E-127), and frac(k) is
-// p = (a - m1)/(m2 - m1).
-struct Bracket {
-    uint32_t base;   // code of the lower magnitude m1
-    float frac;      // p in [0,1)
-    uint32_t sign;   // 8 if the sign bit of y is set
-};
+// The quantizers never form y = x / S itself.  They form v = x * 2^-s * 2^-126, which
+// puts |y| in [0, 6] onto FP32 bit patterns whose layout IS the E2M1 grid: |y| < 1 lands
+// in FP32's subnormal range (uniform spacing, like E2M1's subnormals 0 and 0.5), [1,2)
+// in the first normal binade, and so on, so that
+//     bits(v) >> 22           = code of the largest E2M1 magnitude m1 <= |y|,
+//     bits(v) & 0x3FFFFF      = p * 2^22,   p = (|y| - m1) / (m2 - m1).
+// Rounding is then one integer add that carries into bit 22.  The two multiplications
+// are exact except when the result is subnormal and x has bits below 2^-149; the FP32
+// rounding mode is set so that the inexact case still decides correctly:
+//   round_D, ties to the larger value: y > 0 goes up iff p >= 1/2, which floor(p * 2^22)
+//     decides; y < 0 goes up in magnitude iff p > 1/2, which ceil(p * 2^22) decides.  Both
+//     are what round-toward-minus-infinity does to the signed product.
+//   round_S: up iff r16 < 65536 * p  <=>  p * 2^22 > 64 * r16, which ceil decides:
+//     round-toward-plus-infinity on |x|.
+__device__ __forceinline__ void f32_round_toward_plus_inf()  { __builtin_amdgcn_s_setreg(0x801, 1); }   // MODE[1:0]
+__device__ __forceinline__ void f32_round_toward_minus_inf() { __builtin_amdgcn_s_setreg(0x801, 2); }
 
-__device__ __forceinline__ Bracket bracket(float y, bool floor_mode)
+constexpr uint32_t GRID_MAX_BITS = 0x01C00000u;      // 6 * 2^-126
+
+// round_D.  Call with the rounding mode set toward minus infinity.  inv = 2^-s.
+// mag_limit: GRID_MAX_BITS under Eq. 2's scale (which truncates to |y| <= 6), else no limit.
+__device__ __forceinline__ uint32_t mag_limit(bool floor_mode) { return floor_mode ? GRID_MAX_BITS : 0x7FFFFFFFu; }
+
+__device__ __forceinline__ uint32_t rtn_code(float x, float inv, uint32_t limit)
 {
-    uint32_t yb = __float_as_uint(y);
-    uint32_t ab = yb & 0x7FFFFFFFu;
-    if (floor_mode) ab = ab > 0x40C00000u ? 0x40C00000u : ab;   // Eq. 2 truncates to |y| <= 6
-    uint32_t E = ab >> 23;
-    E = E < 127u ? 127u : E;
-    float k = __uint_as_float(ab) * __uint_as_float((255u - E) << 23);   // exact
-    float fl = floorf(k);
-    Bracket br;
-    br.frac = k - fl;                                                    // exact
-    br.base = 2u * (E - 127u) + (uint32_t)fl;
-    br.sign = (yb >> 28) & 8u;
-    return br;
+    float v = (x * inv) * 0x1p-126f;
+    uint32_t vb = __float_as_uint(v);
+    uint32_t mag = vb & 0x7FFFFFFFu;
+    mag = mag > limit ? limit : mag;
+    // + 2^21, minus 1 for negative values: a negative midpoint stays at the smaller magnitude
+    uint32_t t = mag + 0x200000u + (uint32_t)((int32_t)vb >> 31);
+    return (t >> 22) | ((vb >> 28) & 8u);
 }
 
-// round_D: q1 iff strictly nearer, so a midpoint goes to q2, the larger signed
-// value: up in magnitude for y > 0, down in magnitude for y < 0.
-__device__ __forceinline__ uint32_t round_rtn(float y, bool floor_mode)
+// round_S.  Call with the rounding mode set toward plus infinity.
+// rinv = ((65535 - r16) << 6) | 63: the add carries into bit 22 iff p * 2^22 > 64 * r16.
+__device__ __forceinline__ uint32_t sr_code(float x, float inv, uint32_t rinv, uint32_t limit)
 {
-    Bracket br = bracket(y, floor_mode);
-    bool up = br.sign ? (br.frac > 0.5f) : (br.frac >= 0.5f);
-    return (br.base + (up ? 1u : 0u)) | br.sign;
+    float v = (__builtin_fabsf(x) * inv) * 0x1p-126f;
+    uint32_t mag = __float_as_uint(v);
+    mag = mag > limit ? limit : mag;
+    return ((mag + rinv) >> 22) | ((__float_as_uint(x) >> 28) & 8u);
 }
 
-// round_S with 16 random bits: larger magnitude iff r16 < 65536 * p.
-__device__ __forceinline__ uint32_t round_sr(float y, uint32_t r16, bool floor_mode)
+// |value| of an E2M1 code times 2^s, from the same bit layout: (code & 7) << 22 is
+// m * 2^-126 as an FP32 pattern.  Exact in any rounding mode.
+__device__ __forceinline__ float dequant_mag(uint32_t code, float scale)
 {
-    Bracket br = bracket(y, floor_mode);
-    bool up = (float)r16 < br.frac * 65536.0f;                           // both sides exact
-    return (br.base + (up ? 1u : 0u)) | br.sign;
+    return (__uint_as_float((code & 7u) << 22) * 0x1p+126f) * scale;
 }
 
 // Q-EMA (Algorithm 1): bracket from y = w/S, choice by z = w_ema/S.
-__device__ __forceinline__ uint32_t round_ema(float y, float z, bool floor_mode)
+// y_is_exact_zero: w itself is +-0 (then y = 0 is an E2M1 value and is kept); a nonzero w whose
+// y underflowed to 0 in FP32 still has the bracket [0, 0.5].
+__device__ __forceinline__ uint32_t round_ema(float y, float z, bool floor_mode, bool w_is_zero)
 {
     uint32_t yb = __float_as_uint(y);
     uint32_t ab = yb & 0x7FFFFFFFu;
@@ -102,17 +110,14 @@ __device__ __forceinline__ uint32_t round_ema(float y, float z, bool floor_mode)
     float zk = __uint_as_float(__float_as_uint(z) ^ (neg << 31)) * f;
     float mid = fl + 0.5f;
     bool up = neg ? (zk > mid) : (zk >= mid);   // |z-q1| < |z-q2| picks q1, else q2
-    up = up && (fr != 0.0f);                    // w/S already an E2M1 value: keep it
+    up = up && (fr != 0.0f || (ab == 0u && !w_is_zero));   // w/S already an E2M1 value: keep it
     return (2u * (E - 127u) + (uint32_t)fl + (up ? 1u : 0u)) | ((yb >> 28) & 8u);
 }
 
-// value of an E2M1 code times 2^s, exact in FP32 (may be subnormal)
+// signed value of an E2M1 code times 2^s, exact in FP32 (may be subnormal)
 __device__ __forceinline__ float dequant(uint32_t code, float scale)
 {
-    uint32_t n = code & 7u;
-    uint32_t bits = (((n >> 1) + 126u) << 23) | ((n & 1u) << 22);
-    bits = n < 2u ? (n ? 0x3F000000u : 0u) : bits;
-    return __uint_as_float(bits | ((code & 8u) << 28)) * scale;
+    return __uint_as_float(__float_as_uint(dequant_mag(code, scale)) | ((code & 8u) << 28));
 }
 
 // ---- Philox4x32-10 (Salmon et al., SC'11) ----------------------------------
@@ -127,8 +132,8 @@ __device__ __forceinline__ U4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c
     for (int i = 0; i < 10; ++i) {
         uint64_t pa = (uint64_t)MUL_A * c0;
         uint64_t pb = (uint64_t)MUL_B * c2;
-        uint32_t n0 = (uint32_t)(pb >> 32) ^ c1 ^ k0;
-        uint32_t n2 = (uint32_t)(pa >> 32) ^ c3 ^ k1;
+        uint32_t n0 = __builtin_amdgcn_bitop3_b32((uint32_t)(pb >> 32), c1, k0, 0x96);   // three-way xor
+        uint32_t n2 = __builtin_amdgcn_bitop3_b32((uint32_t)(pa >> 32), c3, k1, 0x96);
         c1 = (uint32_t)pb;
         c3 = (uint32_t)pa;
         c0 = n0;
@@ -151,6 +156,22 @@ __device__ __forceinline__ uint32_t sr_field(const U4& r, int t)
 {
     uint32_t w = r.w[t >> 1];
     return (t & 1) ? (w >> 16) : (w & 0xFFFFu);
+}
+
+// The eight rounding addends ((65535 - r16) << 6) | 63 of an 8-element block, for sr_code().
+struct U8 { uint32_t w[8]; };
+
+__device__ __forceinline__ U8 sr_addends(uint64_t blk, uint32_t tensor_id, uint32_t k0, uint32_t k1)
+{
+    U4 r = sr_block(blk, tensor_id, k0, k1);
+    U8 a;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        uint32_t inv = ~r.w[i];
+        a.w[2 * i] = ((inv & 0xFFFFu) << 6) | 63u;
+        a.w[2 * i + 1] = ((inv >> 16) << 6) | 63u;
+    }
+    return a;
 }
 
 // ---- cross-lane max over aligned groups of 4 lanes (one 32-element group) ---

@@ -37,23 +37,31 @@ struct RowsArgs {
     int update_ema;
 };
 
-// Encode 8 scaled elements and pack them low nibble first.
+// Encode 8 elements of one group (inv = 2^-s) and pack them low nibble first.  The FP32
+// rounding mode must be set for the rounding in use (see rtn_code / sr_code).
 template <bool SR>
-__device__ __forceinline__ uint32_t encode8(const F8& x, float inv, bool floor_mode, const U4& rnd)
+__device__ __forceinline__ uint32_t encode8(const F8& x, float inv, uint32_t limit, const U8& add)
 {
     uint32_t packed = 0;
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
-        float y = x.v[t] * inv;     // exact (gradual underflow only below 2^-126)
-        uint32_t c = SR ? round_sr(y, sr_field(rnd, t), floor_mode) : round_rtn(y, floor_mode);
+        uint32_t c = SR ? sr_code(x.v[t], inv, add.w[t], limit) : rtn_code(x.v[t], inv, limit);
         packed |= c << (4 * t);
     }
     return packed;
 }
 
+template <bool SR>
+__device__ __forceinline__ void set_round_mode_for()
+{
+    if (SR) f32_round_toward_plus_inf();
+    else    f32_round_toward_minus_inf();
+}
+
 template <typename SrcT, bool SR>
 __global__ __launch_bounds__(ROWS_THREADS) void quantize_rows_kernel(RowsArgs a)
 {
+    set_round_mode_for<SR>();
     const SrcT* src = static_cast<const SrcT*>(a.src);
     const uint32_t q0 = blockIdx.x * (ROWS_THREADS * ROWS_UNROLL) + threadIdx.x;
     F8 x[ROWS_UNROLL];
@@ -80,9 +88,9 @@ __global__ __launch_bounds__(ROWS_THREADS) void quantize_rows_kernel(RowsArgs a)
         uint32_t q = q0 + u * ROWS_THREADS;
         uint32_t m = quad_max(amax_bits8(x[u]));
         uint32_t byte = scale_byte(m, a.floor_mode);
-        U4 rnd;
-        if (SR) rnd = sr_block(a.base_blk + q, a.tensor_id, a.k0, a.k1);
-        uint32_t packed = encode8<SR>(x[u], inv_scale(byte), a.floor_mode, rnd);
+        U8 rnd;
+        if (SR) rnd = sr_addends(a.base_blk + q, a.tensor_id, a.k0, a.k1);
+        uint32_t packed = encode8<SR>(x[u], inv_scale(byte), mag_limit(a.floor_mode), rnd);
         if (ok[u]) {
             reinterpret_cast<uint32_t*>(a.codes)[q] = packed;
             if ((threadIdx.x & 3) == 0) a.scales[q >> 2] = (uint8_t)byte;
@@ -121,7 +129,8 @@ __global__ __launch_bounds__(ROWS_THREADS) void ema_quantize_kernel(RowsArgs a)
     uint32_t packed = 0;
 #pragma unroll
     for (int t = 0; t < 8; ++t)
-        packed |= round_ema(w.v[t] * inv, e.v[t] * inv, a.floor_mode) << (4 * t);
+        packed |= round_ema(w.v[t] * inv, e.v[t] * inv, a.floor_mode,
+                            (__float_as_uint(w.v[t]) & 0x7FFFFFFFu) == 0u) << (4 * t);
     if (ok) {
         if (a.update_ema != 0) {
             float4* p = reinterpret_cast<float4*>(a.ema + off);
@@ -174,6 +183,7 @@ __device__ __forceinline__ uint32_t xor_lane_max(uint32_t v, int mask)
 template <int SRC, bool ROW_SR, bool T_SR>
 __global__ __launch_bounds__(TILE_THREADS) void quantize_tile_kernel(TileArgs a)
 {
+    if (ROW_SR == T_SR) set_round_mode_for<T_SR>();       // otherwise switched per phase below
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const uint32_t rt = blockIdx.y * 8 + wave;            // 32-row tile index
     if (rt * 32 >= a.rows) return;                        // whole wave leaves; no block barrier is used
@@ -181,6 +191,7 @@ __global__ __launch_bounds__(TILE_THREADS) void quantize_tile_kernel(TileArgs a)
     const uint32_t row0 = rt * 32 + 4 * rg;
     const bool want_row = a.codes_row != nullptr;
     const bool floor_mode = a.floor_mode != 0;
+    const uint32_t limit = mag_limit(floor_mode);
     const uint32_t half_rows = a.rows >> 1, grp_rows = a.rows >> 5;
     const uint32_t half_cols = a.cols >> 1, grp_cols = a.cols >> 5;
 
@@ -215,13 +226,14 @@ __global__ __launch_bounds__(TILE_THREADS) void quantize_tile_kernel(TileArgs a)
             }
             // ---- 1x32 quantizer of the same elements ---------------------------
             if (want_row || a.pre_quant) {
+                if (ROW_SR != T_SR) set_round_mode_for<ROW_SR>();
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     uint32_t r = row0 + j;
                     uint32_t byte = scale_byte(quad_max(amax_bits8(x[j])), floor_mode);
-                    U4 rnd;
-                    if (ROW_SR) rnd = sr_block((a.index_base + (uint64_t)r * a.cols + c) >> 3, a.tensor_id_row, a.k0, a.k1);
-                    uint32_t pk = encode8<ROW_SR>(x[j], inv_scale(byte), floor_mode, rnd);
+                    U8 rnd;
+                    if (ROW_SR) rnd = sr_addends((a.index_base + (uint64_t)r * a.cols + c) >> 3, a.tensor_id_row, a.k0, a.k1);
+                    uint32_t pk = encode8<ROW_SR>(x[j], inv_scale(byte), limit, rnd);
                     if (want_row && ok) {
                         *reinterpret_cast<uint32_t*>(a.codes_row + (size_t)r * half_cols + (c >> 1)) = pk;
                         if ((cc & 3) == 0) a.scales_row[(size_t)r * grp_cols + (c >> 5)] = (uint8_t)byte;
@@ -249,17 +261,18 @@ __global__ __launch_bounds__(TILE_THREADS) void quantize_tile_kernel(TileArgs a)
             m = xor_lane_max(m, 32);
             sb[t] = scale_byte(m, floor_mode);
         }
+        if (ROW_SR != T_SR) set_round_mode_for<T_SR>();
         uint32_t colpk[8];
 #pragma unroll
         for (int t = 0; t < 8; ++t) colpk[t] = 0;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            U4 rnd;
-            if (T_SR) rnd = sr_block((a.index_base + (uint64_t)(row0 + j) * a.cols + c) >> 3, a.tensor_id_t, a.k0, a.k1);
+            U8 rnd;
+            if (T_SR) rnd = sr_addends((a.index_base + (uint64_t)(row0 + j) * a.cols + c) >> 3, a.tensor_id_t, a.k0, a.k1);
 #pragma unroll
             for (int t = 0; t < 8; ++t) {
-                float y = x[j].v[t] * inv_scale(sb[t]);
-                uint32_t code = T_SR ? round_sr(y, sr_field(rnd, t), floor_mode) : round_rtn(y, floor_mode);
+                float inv = inv_scale(sb[t]);
+                uint32_t code = T_SR ? sr_code(x[j].v[t], inv, rnd.w[t], limit) : rtn_code(x[j].v[t], inv, limit);
                 colpk[t] |= code << (4 * j);
             }
         }

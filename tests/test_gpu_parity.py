@@ -117,6 +117,33 @@ def test_sr_zero_draw_on_tiny_elements(mx, orc):
     assert np.all(flat[zeros] > 0)                   # they did round up to 0.5 * S
 
 
+def test_tiny_elements_under_a_large_scale(mx, orc):
+    # quotients far below FP32's range: every rounding rule must still see them as nonzero
+    rng = np.random.default_rng(8)
+    x = np.zeros((64, 128), np.float32)
+    x[:, ::32] = np.float32(2.0) ** rng.integers(0, 60, (64, 4)).astype(np.float32)       # group maxima
+    tiny = np.float32(2.0) ** rng.integers(-149, -100, (64, 128)).astype(np.float32)
+    tiny *= rng.choice(np.array([-1.0, 1.0], np.float32), (64, 128))
+    mask = np.ones_like(x, bool)
+    mask[:, ::32] = False
+    x[mask] = tiny[mask]
+    for rnd in (0, 1):
+        for seed in range(3):
+            want = orc.quantize(x, round=rnd, seed=seed, tensor_id=1)
+            got = mx.mx_quantize(dev(x), rnd, 0, seed=seed, tensor_id=1)
+            assert_same_bytes(got[0], want[0], "codes r%d" % rnd)
+        kw = dict(round_t=rnd, tensor_id_t=2, pre_quant=0, want_row=True, round_row=1 - rnd, tensor_id_row=3, seed=5)
+        want = orc.quantize_transposed(x, **kw)
+        got = mx.mx_quantize_transposed(dev(x), **kw)
+        for i, nm in enumerate(["codes_t", "scales_t", "codes_row", "scales_row"]):
+            assert_same_bytes(got[i], want[i], nm)
+    ema = np.abs(x) * np.float32(2.0) ** 40
+    ema = np.minimum(ema, np.float32(1e30)).astype(np.float32)
+    want = orc.ema_weight_quant(x, ema.copy(), update_ema=0)
+    got = mx.mx_ema_weight_quant(dev(x), dev(ema), 0.5, 0)
+    assert_same_bytes(got[0], want[0], "ema codes")
+
+
 # ------------------------------------------------------------ transposed ----
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])

@@ -311,6 +311,28 @@ def test_quantize_zero_group_and_ld(orc):
     assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
 
 
+def test_quotient_is_exact_below_fp32_range(orc):
+    # x / S is a real quotient (Sec. 3.2): an element 2^-170 of the scale still has p > 0, so a
+    # zero draw rounds it up, and the EMA rule still sees the bracket [0, 0.5] for it
+    seed, tid = 4, 9
+    e0 = next(e for e in range(1 << 20) if orc.sr_bits(seed, tid, e) == 0)
+    x = np.zeros((1, ((e0 // 32) + 1) * 32), np.float32)
+    x[0, (e0 // 32) * 32 + ((e0 + 1) % 32)] = np.float32(2.0) ** 20        # group maximum: s = 18
+    x[0, e0] = np.float32(2.0) ** -149                                     # y = 2^-167
+    codes, scales = orc.quantize(x, round=orc.ROUND_SR, seed=seed, tensor_id=tid)
+    assert scales[0, e0 // 32] == 127 + 18
+    assert (codes[0, e0 // 2] >> (4 * (e0 & 1))) & 15 == 1                  # 0.5 * S
+    xn = -x
+    codes, _ = orc.quantize(xn, round=orc.ROUND_SR, seed=seed, tensor_id=tid)
+    assert (codes[0, e0 // 2] >> (4 * (e0 & 1))) & 15 == 9
+    codes, _ = orc.quantize(x, round=orc.ROUND_RTN)
+    assert (codes[0, e0 // 2] >> (4 * (e0 & 1))) & 15 == 0
+    ema = x.copy()
+    ema[0, e0] = np.float32(2.0) ** 17                                     # z = 0.5: pulls the tiny weight up
+    codes, _ = orc.ema_weight_quant(x, ema, update_ema=0)
+    assert (codes[0, e0 // 2] >> (4 * (e0 & 1))) & 15 == 1
+
+
 def test_quantize_sr_decisions_follow_element_index(orc):
     # compose the whole quantizer from its pinned parts on a small matrix
     rng = np.random.default_rng(6)
