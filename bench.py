@@ -27,9 +27,12 @@ def parse():
     ap.add_argument("--workload", default="vit_base_b256")
     ap.add_argument("--tokens", type=int, default=None, help="override N (tokens) of the workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=1024)
+    ap.add_argument("--cpu-sample-tokens", type=int, default=16384)
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "gemm_traffic.json"),
                     help="HBM bytes per GEMM launch measured with rocprofv3 --pmc, if present")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (reference dispatch for scaling rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()
 
 
@@ -117,6 +120,14 @@ def main():
                 e[6].record()
                 quant_events.extend([(e[0], e[1]), (e[1], e[2]), (e[3], e[4])])
                 gemm_events.extend([(e[2], e[3]), (e[4], e[5]), (e[5], e[6])])
+
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")      # 1 GiB read, 1 GiB written
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        mx.binding.mx_calibration_copy(dst, src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for w in range(args.warmup):
         run_step(w, False)

@@ -156,6 +156,10 @@ size_t mx_linear_workspace_bytes(int which, int64_t N, int64_t C, int64_t D);
 int mx_dequantize(const uint8_t* codes, const uint8_t* scales, int64_t rows, int64_t cols,
                   float* out, void* stream);
 
+/* Plain device-to-device copy kernel of `bytes` bytes (a multiple of 16; 16-byte aligned
+ * pointers): a dispatch with known HBM traffic, used to scale profiler byte counters. */
+int mx_calibration_copy(void* dst, const void* src, size_t bytes, void* stream);
+
 /* Raw hipError_t of the last launch that made a call return MX_ERR_HIP (0 if none). */
 int mx_last_hip_error(void);
 

@@ -26,7 +26,7 @@ GEMM_FWD, GEMM_BWD_DX, GEMM_BWD_DW = 0, 1, 2
 
 EXPORTS = ["mx_quantize", "mx_quantize_transposed", "mx_linear_fwd", "mx_linear_bwd_dx",
            "mx_linear_bwd_dw", "mx_ema_weight_quant", "mx_linear_workspace_bytes",
-           "mx_dequantize", "mx_last_hip_error", "mx_version"]
+           "mx_dequantize", "mx_calibration_copy", "mx_last_hip_error", "mx_version"]
 
 
 class MxError(RuntimeError):
@@ -67,6 +67,8 @@ def lib():
     L.mx_linear_workspace_bytes.argtypes = [ci, i64, i64, i64]
     L.mx_dequantize.restype = ci
     L.mx_dequantize.argtypes = [vp, vp, i64, i64, vp, vp]
+    L.mx_calibration_copy.restype = ci
+    L.mx_calibration_copy.argtypes = [vp, vp, sz, vp]
     L.mx_last_hip_error.restype = ci
     L.mx_last_hip_error.argtypes = []
     L.mx_version.restype = ctypes.c_char_p
@@ -210,3 +212,11 @@ def mx_dequantize(codes, scales, stream=None):
     rc = lib().mx_dequantize(_ptr(codes), _ptr(scales), rows, cols, _ptr(out), _stream(stream))
     _check("mx_dequantize", rc)
     return out
+
+
+def mx_calibration_copy(dst, src, stream=None):
+    """Plain copy kernel (known HBM traffic) for scaling profiler byte counters."""
+    nbytes = src.numel() * src.element_size()
+    rc = lib().mx_calibration_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream))
+    _check("mx_calibration_copy", rc)
+    return dst

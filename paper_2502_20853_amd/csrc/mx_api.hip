@@ -190,6 +190,14 @@ int mx_dequantize(const uint8_t* codes, const uint8_t* scales, int64_t rows, int
     return hip_status(mxl::launch_dequantize(codes, scales, rows, cols, out, static_cast<hipStream_t>(stream)));
 }
 
+int mx_calibration_copy(void* dst, const void* src, size_t bytes, void* stream)
+{
+    if (!dst || !src) return MX_ERR_NULL;
+    if (bytes == 0 || (bytes & 15u) != 0) return MX_ERR_SHAPE;
+    if (!aligned(dst, 16) || !aligned(src, 16)) return MX_ERR_ALIGN;
+    return hip_status(mxl::launch_calibration_copy(dst, src, bytes, static_cast<hipStream_t>(stream)));
+}
+
 int mx_last_hip_error(void) { return g_last_hip_error.load(); }
 
 const char* mx_version(void) { return "mxfp4-gfx950 0.1"; }

@@ -60,6 +60,8 @@ hipError_t launch_quantize_tile(const QuantTileParams& p, hipStream_t st);
 hipError_t launch_dequantize(const uint8_t* codes, const uint8_t* scales, int64_t rows, int64_t cols,
                              float* out, hipStream_t st);
 
+hipError_t launch_calibration_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
+
 // Number of K-splits the product will use for these sizes (1 = none).
 int gemm_split_k(int64_t m, int64_t n, int64_t k);
 hipError_t launch_gemm(const GemmParams& p, hipStream_t st);

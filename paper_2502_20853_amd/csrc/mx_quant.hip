@@ -145,8 +145,8 @@ __global__ __launch_bounds__(ROWS_THREADS) void ema_quantize_kernel(RowsArgs a)
 // ---------------------------------------------------------------------------
 // Transposed / fused quantizer.
 //
-// A workgroup of 8 waves owns a 256 x 256 macro tile of the source; wave w owns
-// rows [32w, 32w+32) of it and walks over four 32 x 64 tiles.  Inside a tile,
+// A workgroup of 8 waves owns a 256 x 256 macro tile of the source (256 x 64 for small
+// tensors); wave w owns rows [32w, 32w+32) of it and walks over its 32 x 64 tiles.  Inside a tile,
 // lane l holds rows 4*(l/8)+j (j = 0..3) x columns 8*(l%8)+t (t = 0..7):
 //   - each load instruction reads 8 full rows of 64 elements,
 //   - a 1x32 row group is 4 neighbouring lanes (DPP quad reduction),
@@ -169,6 +169,7 @@ struct TileArgs {
     uint32_t rows, cols;
     int pre_quant;
     int floor_mode;
+    int tiles_per_wave;    // 32 x 64 tiles a wave walks along the columns (4 for large tensors, 1 for small ones)
     uint32_t k0, k1, tensor_id_t, tensor_id_row;
     uint64_t index_base;
 };
@@ -195,8 +196,8 @@ __global__ __launch_bounds__(TILE_THREADS) void quantize_tile_kernel(TileArgs a)
     const uint32_t half_rows = a.rows >> 1, grp_rows = a.rows >> 5;
     const uint32_t half_cols = a.cols >> 1, grp_cols = a.cols >> 5;
 
-    for (int ci = 0; ci < 4; ++ci) {
-        const uint32_t col0 = blockIdx.x * 256 + ci * 64;
+    for (int ci = 0; ci < a.tiles_per_wave; ++ci) {
+        const uint32_t col0 = (blockIdx.x * a.tiles_per_wave + ci) * 64;
         if (col0 >= a.cols) break;                        // uniform over the wave
         const uint32_t c = col0 + cc * 8;
         const bool ok = c < a.cols;
@@ -300,6 +301,13 @@ __global__ void dequantize_kernel(const uint8_t* codes, const uint8_t* scales, i
     out[2 * i + 1] = dequant(b >> 4, sc);
 }
 
+__global__ __launch_bounds__(256) void calibration_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) dst[i] = src[i];
+}
+
 }  // namespace
 
 // ------------------------------------------------------------------ launchers
@@ -361,10 +369,24 @@ hipError_t launch_quantize_tile(const QuantTileParams& p, hipStream_t st)
     a.pre_quant = p.pre_quant; a.floor_mode = p.floor_mode;
     a.k0 = (uint32_t)p.seed; a.k1 = (uint32_t)(p.seed >> 32);
     a.tensor_id_t = p.tensor_id_t; a.tensor_id_row = p.tensor_id_row; a.index_base = p.index_base;
-    dim3 grid((unsigned)((p.cols + 255) / 256), (unsigned)((p.rows + 255) / 256));
+    // Large tensors: 4 tiles per wave, so that one workgroup writes whole 128-byte lines of the
+    // row codes.  Small ones (weights) need the parallelism more than the write merging.
+    a.tiles_per_wave = (p.rows * p.cols >= (int64_t)8 << 20) ? 4 : 1;
+    const int64_t cols_per_block = 64 * a.tiles_per_wave;
+    dim3 grid((unsigned)((p.cols + cols_per_block - 1) / cols_per_block), (unsigned)((p.rows + 255) / 256));
     if (p.row_codes_in)  launch_tile_src<2>(a, false, p.sr_t, grid, st);
     else if (p.bf16)     launch_tile_src<1>(a, p.sr_row, p.sr_t, grid, st);
     else                 launch_tile_src<0>(a, p.sr_row, p.sr_t, grid, st);
+    return hipGetLastError();
+}
+
+hipError_t launch_calibration_copy(void* dst, const void* src, size_t bytes, hipStream_t st)
+{
+    size_t n = bytes / 16;
+    size_t blocks = (n + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    hipLaunchKernelGGL(calibration_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
+                       static_cast<const uint4*>(src), static_cast<uint4*>(dst), n);
     return hipGetLastError();
 }
 

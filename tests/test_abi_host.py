@@ -118,6 +118,12 @@ def test_ema_rejects(L):
     assert e(ema=FAKE + 4) == -5
 
 
+def test_calibration_copy_rejects(L):
+    assert L.mx_calibration_copy(P(0), P(FAKE), 64, P(0)) == -1
+    assert L.mx_calibration_copy(P(FAKE), P(FAKE), 60, P(0)) == -2
+    assert L.mx_calibration_copy(P(FAKE + 4), P(FAKE), 64, P(0)) == -5
+
+
 def test_dequantize_rejects(L):
     assert L.mx_dequantize(P(0), P(FAKE), 4, 32, P(FAKE), P(0)) == -1
     assert L.mx_dequantize(P(FAKE), P(FAKE), 4, 33, P(FAKE), P(0)) == -2
