@@ -91,8 +91,8 @@ int mx_quantize(const void* src, int dtype, int64_t rows, int64_t cols, int64_t 
  *               pre_quant = 1: take Q_row(src) as given (e.g. the output of
  *               mx_ema_weight_quant) instead of computing it; src is then
  *               unused and may be NULL, and codes_row/scales_row must be NULL.
- *   rows % 32 == 0, cols % 32 == 0, ld >= cols; alignment as mx_quantize;
- *   codes_t 4-byte aligned; rows*cols < 2^35.
+ *   rows % 32 == 0, cols % 32 == 0, ld >= cols; src alignment as mx_quantize;
+ *   codes_t, codes_row and row_codes_in 16-byte aligned; rows*cols < 2^35.
  */
 int mx_quantize_transposed(const void* src, int dtype, int64_t rows, int64_t cols, int64_t ld,
                 uint8_t* codes_t, uint8_t* scales_t,

@@ -108,9 +108,9 @@ int mx_quantize_transposed(const void* src, int dtype, int64_t rows, int64_t col
     if (rows <= 0 || cols <= 0 || (rows % 32) != 0 || (cols % 32) != 0) return MX_ERR_SHAPE;
     if (!given && ld < cols) return MX_ERR_SHAPE;
     if (rows > MAX_ELEMS / cols || rows > 65535LL * 256) return MX_ERR_SHAPE;
-    if (!aligned(codes_t, 4)) return MX_ERR_ALIGN;
-    if (codes_row && !aligned(codes_row, 4)) return MX_ERR_ALIGN;
-    if (given && !aligned(row_codes_in, 4)) return MX_ERR_ALIGN;
+    if (!aligned(codes_t, 16)) return MX_ERR_ALIGN;
+    if (codes_row && !aligned(codes_row, 16)) return MX_ERR_ALIGN;
+    if (given && !aligned(row_codes_in, 16)) return MX_ERR_ALIGN;
     if (!given) {
         if (!aligned(src, 16)) return MX_ERR_ALIGN;
         if (ld % (dtype == MX_DTYPE_BF16 ? 8 : 4) != 0) return MX_ERR_ALIGN;

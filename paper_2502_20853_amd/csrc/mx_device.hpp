@@ -40,18 +40,19 @@ __device__ __forceinline__ float fwd_scale(uint32_t byte)
 }
 
 // ---- E2M1 rounding (Sec. 3.2) ----------------------------------------------
-// The quantizers never form y = x / S itself.  They form v = x * 2^-s * 2^-126, which
+// The quantizers never form y = x / S itself.  They form v = x * 2^(-s-126) (one ldexp), which
 // puts |y| in [0, 6] onto FP32 bit patterns whose layout IS the E2M1 grid: |y| < 1 lands
 // in FP32's subnormal range (uniform spacing, like E2M1's subnormals 0 and 0.5), [1,2)
 // in the first normal binade, and so on, so that
 //     bits(v) >> 22           = code of the largest E2M1 magnitude m1 <= |y|,
 //     bits(v) & 0x3FFFFF      = p * 2^22,   p = (|y| - m1) / (m2 - m1).
-// Rounding is then one integer add that carries into bit 22.  The two multiplications
-// are exact except when the result is subnormal and x has bits below 2^-149; the FP32
-// rounding mode is set so that the inexact case still decides correctly:
+// Rounding is then one integer add that carries into bit 22.  The scaling is exact except
+// when the result is subnormal and x has bits below 2^-149; the FP32 rounding mode is set
+// so that the inexact case still decides correctly (v_ldexp_f32 rounds a subnormal result
+// by the mode, like a multiplication does):
 //   round_D, ties to the larger value: y > 0 goes up iff p >= 1/2, which floor(p * 2^22)
 //     decides; y < 0 goes up in magnitude iff p > 1/2, which ceil(p * 2^22) decides.  Both
-//     are what round-toward-minus-infinity does to the signed product.
+//     are what round-toward-minus-infinity does to the signed value.
 //   round_S: up iff r16 < 65536 * p  <=>  p * 2^22 > 64 * r16, which ceil decides:
 //     round-toward-plus-infinity on |x|.
 __device__ __forceinline__ void f32_round_toward_plus_inf()  { __builtin_amdgcn_s_setreg(0x801, 1); }   // MODE[1:0]
@@ -59,16 +60,17 @@ __device__ __forceinline__ void f32_round_toward_minus_inf() { __builtin_amdgcn_
 
 constexpr uint32_t GRID_MAX_BITS = 0x01C00000u;      // 6 * 2^-126
 
-// round_D.  Call with the rounding mode set toward minus infinity.  inv = 2^-s.
-// mag_limit: GRID_MAX_BITS under Eq. 2's scale (which truncates to |y| <= 6), else no limit.
-__device__ __forceinline__ uint32_t mag_limit(bool floor_mode) { return floor_mode ? GRID_MAX_BITS : 0x7FFFFFFFu; }
+// Exponent to hand to ldexp for scale byte b = s + 127:  -s - 126 = 1 - b.
+__device__ __forceinline__ int grid_exponent(uint32_t byte) { return 1 - (int)byte; }
 
-__device__ __forceinline__ uint32_t rtn_code(float x, float inv, uint32_t limit)
+// round_D.  Call with the rounding mode set toward minus infinity.  e = grid_exponent(byte).
+// FLOOR: Eq. 2's scale, which truncates to |y| <= 6.
+template <bool FLOOR>
+__device__ __forceinline__ uint32_t rtn_code(float x, int e)
 {
-    float v = (x * inv) * 0x1p-126f;
-    uint32_t vb = __float_as_uint(v);
+    uint32_t vb = __float_as_uint(__builtin_ldexpf(x, e));
     uint32_t mag = vb & 0x7FFFFFFFu;
-    mag = mag > limit ? limit : mag;
+    if (FLOOR) mag = mag > GRID_MAX_BITS ? GRID_MAX_BITS : mag;
     // + 2^21, minus 1 for negative values: a negative midpoint stays at the smaller magnitude
     uint32_t t = mag + 0x200000u + (uint32_t)((int32_t)vb >> 31);
     return (t >> 22) | ((vb >> 28) & 8u);
@@ -76,19 +78,19 @@ __device__ __forceinline__ uint32_t rtn_code(float x, float inv, uint32_t limit)
 
 // round_S.  Call with the rounding mode set toward plus infinity.
 // rinv = ((65535 - r16) << 6) | 63: the add carries into bit 22 iff p * 2^22 > 64 * r16.
-__device__ __forceinline__ uint32_t sr_code(float x, float inv, uint32_t rinv, uint32_t limit)
+template <bool FLOOR>
+__device__ __forceinline__ uint32_t sr_code(float x, int e, uint32_t rinv)
 {
-    float v = (__builtin_fabsf(x) * inv) * 0x1p-126f;
-    uint32_t mag = __float_as_uint(v);
-    mag = mag > limit ? limit : mag;
+    uint32_t mag = __float_as_uint(__builtin_ldexpf(__builtin_fabsf(x), e));
+    if (FLOOR) mag = mag > GRID_MAX_BITS ? GRID_MAX_BITS : mag;
     return ((mag + rinv) >> 22) | ((__float_as_uint(x) >> 28) & 8u);
 }
 
 // |value| of an E2M1 code times 2^s, from the same bit layout: (code & 7) << 22 is
 // m * 2^-126 as an FP32 pattern.  Exact in any rounding mode.
-__device__ __forceinline__ float dequant_mag(uint32_t code, float scale)
+__device__ __forceinline__ float dequant_mag(uint32_t code, uint32_t byte)
 {
-    return (__uint_as_float((code & 7u) << 22) * 0x1p+126f) * scale;
+    return __builtin_ldexpf(__uint_as_float((code & 7u) << 22), (int)byte - 1);
 }
 
 // Q-EMA (Algorithm 1): bracket from y = w/S, choice by z = w_ema/S.
@@ -114,10 +116,10 @@ __device__ __forceinline__ uint32_t round_ema(float y, float z, bool floor_mode,
     return (2u * (E - 127u) + (uint32_t)fl + (up ? 1u : 0u)) | ((yb >> 28) & 8u);
 }
 
-// signed value of an E2M1 code times 2^s, exact in FP32 (may be subnormal)
-__device__ __forceinline__ float dequant(uint32_t code, float scale)
+// signed value of an E2M1 code times 2^s (byte = s + 127), exact in FP32 (may be subnormal)
+__device__ __forceinline__ float dequant(uint32_t code, uint32_t byte)
 {
-    return __uint_as_float(__float_as_uint(dequant_mag(code, scale)) | ((code & 8u) << 28));
+    return __uint_as_float(__float_as_uint(dequant_mag(code, byte)) | ((code & 8u) << 28));
 }
 
 // ---- Philox4x32-10 (Salmon et al., SC'11) ----------------------------------

@@ -39,13 +39,13 @@ struct RowsArgs {
 
 // Encode 8 elements of one group (inv = 2^-s) and pack them low nibble first.  The FP32
 // rounding mode must be set for the rounding in use (see rtn_code / sr_code).
-template <bool SR>
-__device__ __forceinline__ uint32_t encode8(const F8& x, float inv, uint32_t limit, const U8& add)
+template <bool SR, bool FLOOR>
+__device__ __forceinline__ uint32_t encode8(const F8& x, int e, const U8& add)
 {
     uint32_t packed = 0;
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
-        uint32_t c = SR ? sr_code(x.v[t], inv, add.w[t], limit) : rtn_code(x.v[t], inv, limit);
+        uint32_t c = SR ? sr_code<FLOOR>(x.v[t], e, add.w[t]) : rtn_code<FLOOR>(x.v[t], e);
         packed |= c << (4 * t);
     }
     return packed;
@@ -58,7 +58,7 @@ __device__ __forceinline__ void set_round_mode_for()
     else    f32_round_toward_minus_inf();
 }
 
-template <typename SrcT, bool SR>
+template <typename SrcT, bool SR, bool FLOOR>
 __global__ __launch_bounds__(ROWS_THREADS) void quantize_rows_kernel(RowsArgs a)
 {
     set_round_mode_for<SR>();
@@ -87,10 +87,10 @@ __global__ __launch_bounds__(ROWS_THREADS) void quantize_rows_kernel(RowsArgs a)
     for (int u = 0; u < ROWS_UNROLL; ++u) {
         uint32_t q = q0 + u * ROWS_THREADS;
         uint32_t m = quad_max(amax_bits8(x[u]));
-        uint32_t byte = scale_byte(m, a.floor_mode);
+        uint32_t byte = scale_byte(m, FLOOR);
         U8 rnd;
         if (SR) rnd = sr_addends(a.base_blk + q, a.tensor_id, a.k0, a.k1);
-        uint32_t packed = encode8<SR>(x[u], inv_scale(byte), mag_limit(a.floor_mode), rnd);
+        uint32_t packed = encode8<SR, FLOOR>(x[u], grid_exponent(byte), rnd);
         if (ok[u]) {
             reinterpret_cast<uint32_t*>(a.codes)[q] = packed;
             if ((threadIdx.x & 3) == 0) a.scales[q >> 2] = (uint8_t)byte;
@@ -146,16 +146,22 @@ __global__ __launch_bounds__(ROWS_THREADS) void ema_quantize_kernel(RowsArgs a)
 // Transposed / fused quantizer.
 //
 // A workgroup of 8 waves owns a 256 x 256 macro tile of the source (256 x 64 for small
-// tensors); wave w owns rows [32w, 32w+32) of it and walks over its 32 x 64 tiles.  Inside a tile,
-// lane l holds rows 4*(l/8)+j (j = 0..3) x columns 8*(l%8)+t (t = 0..7):
+// tensors); wave w owns rows [32w, 32w+32) of it and walks over its 32 x 64 tiles.
+// Inside a tile, lane l holds rows 4*(l/8)+j (j = 0..3) x columns 8*(l%8)+t (t = 0..7):
 //   - each load instruction reads 8 full rows of 64 elements,
 //   - a 1x32 row group is 4 neighbouring lanes (DPP quad reduction),
 //   - a 32x1 column group is 4 registers x 8 lanes (l/8 = 0..7) of one column.
-// All stores of one macro tile come from one workgroup close in time, so the
-// 32-byte (row codes) and 2-byte (transposed codes) pieces merge into full
-// 128-byte lines in that XCD's L2 before they are written back.
+// The 32 elements of a lane stay in registers through both quantizers.  Codes and scale
+// bytes are collected in LDS ([256 rows][128 B] row codes, [256 columns][128 B] transposed
+// codes) and written out at the end as whole 128-byte lines, 16 bytes per lane.
 // ---------------------------------------------------------------------------
 constexpr int TILE_THREADS = 512;
+constexpr int ST_PITCH = 144;                       // bytes per staged row / column of codes (128 + pad)
+constexpr int ST_ROW_OFF = 0;                       // row codes      [256][ST_PITCH]
+constexpr int ST_COL_OFF = 256 * ST_PITCH;          // transposed     [256][ST_PITCH]
+constexpr int ST_SROW_OFF = 2 * 256 * ST_PITCH;     // row scales     [256][8]
+constexpr int ST_SCOL_OFF = ST_SROW_OFF + 256 * 8;  // transposed scales [256][8]
+constexpr int ST_BYTES = ST_SCOL_OFF + 256 * 8;     // 77824: two workgroups per CU
 
 struct TileArgs {
     const void* src;
@@ -168,7 +174,6 @@ struct TileArgs {
     int64_t ld;
     uint32_t rows, cols;
     int pre_quant;
-    int floor_mode;
     int tiles_per_wave;    // 32 x 64 tiles a wave walks along the columns (4 for large tensors, 1 for small ones)
     uint32_t k0, k1, tensor_id_t, tensor_id_row;
     uint64_t index_base;
@@ -181,25 +186,27 @@ __device__ __forceinline__ uint32_t xor_lane_max(uint32_t v, int mask)
 }
 
 // SRC: 0 = FP32 source, 1 = bf16 source, 2 = packed row result given
-template <int SRC, bool ROW_SR, bool T_SR>
-__global__ __launch_bounds__(TILE_THREADS) void quantize_tile_kernel(TileArgs a)
+template <int SRC, bool ROW_SR, bool T_SR, bool FLOOR>
+__global__ __launch_bounds__(TILE_THREADS, 4) void quantize_tile_kernel(TileArgs a)
 {
+    __shared__ __attribute__((aligned(16))) uint8_t st[ST_BYTES];
     if (ROW_SR == T_SR) set_round_mode_for<T_SR>();       // otherwise switched per phase below
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const uint32_t rt = blockIdx.y * 8 + wave;            // 32-row tile index
-    if (rt * 32 >= a.rows) return;                        // whole wave leaves; no block barrier is used
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int cc = lane & 7, rg = lane >> 3;
-    const uint32_t row0 = rt * 32 + 4 * rg;
+    const uint32_t mrow0 = blockIdx.y * 256;              // macro tile origin
+    const uint32_t mcol0 = blockIdx.x * 64 * a.tiles_per_wave;
+    const uint32_t rt = blockIdx.y * 8 + wave;            // 32-row tile index
+    const bool wave_has_rows = rt * 32 < a.rows;
+    const uint32_t lrow0 = wave * 32 + 4 * rg;            // first of this lane's 4 rows inside the macro tile
+    const uint32_t row0 = mrow0 + lrow0;
     const bool want_row = a.codes_row != nullptr;
-    const bool floor_mode = a.floor_mode != 0;
-    const uint32_t limit = mag_limit(floor_mode);
     const uint32_t half_rows = a.rows >> 1, grp_rows = a.rows >> 5;
     const uint32_t half_cols = a.cols >> 1, grp_cols = a.cols >> 5;
 
-    for (int ci = 0; ci < a.tiles_per_wave; ++ci) {
-        const uint32_t col0 = (blockIdx.x * a.tiles_per_wave + ci) * 64;
-        if (col0 >= a.cols) break;                        // uniform over the wave
-        const uint32_t c = col0 + cc * 8;
+    for (int ci = 0; ci < a.tiles_per_wave && wave_has_rows; ++ci) {
+        const uint32_t lcol0 = ci * 64 + cc * 8;          // first of this lane's 8 columns inside the macro tile
+        const uint32_t c = mcol0 + lcol0;
+        if (mcol0 + ci * 64 >= a.cols) break;             // uniform over the wave
         const bool ok = c < a.cols;
         F8 x[4];
         // ---- load -----------------------------------------------------------
@@ -210,9 +217,9 @@ __global__ __launch_bounds__(TILE_THREADS) void quantize_tile_kernel(TileArgs a)
                 if (ok) {
                     uint32_t r = row0 + j;
                     uint32_t pk = *reinterpret_cast<const uint32_t*>(a.row_codes_in + (size_t)r * half_cols + (c >> 1));
-                    float sc = fwd_scale(a.row_scales_in[(size_t)r * grp_cols + (c >> 5)]);
+                    uint32_t byte = a.row_scales_in[(size_t)r * grp_cols + (c >> 5)];
 #pragma unroll
-                    for (int t = 0; t < 8; ++t) x[j].v[t] = dequant((pk >> (4 * t)) & 15u, sc);
+                    for (int t = 0; t < 8; ++t) x[j].v[t] = dequant((pk >> (4 * t)) & 15u, byte);
                 }
             }
         } else {
@@ -231,18 +238,17 @@ __global__ __launch_bounds__(TILE_THREADS) void quantize_tile_kernel(TileArgs a)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     uint32_t r = row0 + j;
-                    uint32_t byte = scale_byte(quad_max(amax_bits8(x[j])), floor_mode);
+                    uint32_t byte = scale_byte(quad_max(amax_bits8(x[j])), FLOOR);
                     U8 rnd;
                     if (ROW_SR) rnd = sr_addends((a.index_base + (uint64_t)r * a.cols + c) >> 3, a.tensor_id_row, a.k0, a.k1);
-                    uint32_t pk = encode8<ROW_SR>(x[j], inv_scale(byte), limit, rnd);
-                    if (want_row && ok) {
-                        *reinterpret_cast<uint32_t*>(a.codes_row + (size_t)r * half_cols + (c >> 1)) = pk;
-                        if ((cc & 3) == 0) a.scales_row[(size_t)r * grp_cols + (c >> 5)] = (uint8_t)byte;
+                    uint32_t pk = encode8<ROW_SR, FLOOR>(x[j], grid_exponent(byte), rnd);
+                    if (want_row) {
+                        *reinterpret_cast<uint32_t*>(st + ST_ROW_OFF + (lrow0 + j) * ST_PITCH + (lcol0 >> 1)) = pk;
+                        if ((cc & 3) == 0) st[ST_SROW_OFF + (lrow0 + j) * 8 + (lcol0 >> 5)] = (uint8_t)byte;
                     }
                     if (a.pre_quant) {
-                        float sc = fwd_scale(byte);
 #pragma unroll
-                        for (int t = 0; t < 8; ++t) x[j].v[t] = dequant((pk >> (4 * t)) & 15u, sc);
+                        for (int t = 0; t < 8; ++t) x[j].v[t] = dequant((pk >> (4 * t)) & 15u, byte);
                     }
                 }
             }
@@ -260,7 +266,7 @@ __global__ __launch_bounds__(TILE_THREADS) void quantize_tile_kernel(TileArgs a)
             m = xor_lane_max(m, 8);
             m = xor_lane_max(m, 16);
             m = xor_lane_max(m, 32);
-            sb[t] = scale_byte(m, floor_mode);
+            sb[t] = scale_byte(m, FLOOR);
         }
         if (ROW_SR != T_SR) set_round_mode_for<T_SR>();
         uint32_t colpk[8];
@@ -272,18 +278,46 @@ __global__ __launch_bounds__(TILE_THREADS) void quantize_tile_kernel(TileArgs a)
             if (T_SR) rnd = sr_addends((a.index_base + (uint64_t)(row0 + j) * a.cols + c) >> 3, a.tensor_id_t, a.k0, a.k1);
 #pragma unroll
             for (int t = 0; t < 8; ++t) {
-                float inv = inv_scale(sb[t]);
-                uint32_t code = T_SR ? sr_code(x[j].v[t], inv, rnd.w[t], limit) : rtn_code(x[j].v[t], inv, limit);
+                int e = grid_exponent(sb[t]);
+                uint32_t code = T_SR ? sr_code<FLOOR>(x[j].v[t], e, rnd.w[t]) : rtn_code<FLOOR>(x[j].v[t], e);
                 colpk[t] |= code << (4 * j);
             }
         }
-        if (ok) {
 #pragma unroll
-            for (int t = 0; t < 8; ++t) {
-                size_t col = c + t;
-                *reinterpret_cast<uint16_t*>(a.codes_t + col * half_rows + (row0 >> 1)) = (uint16_t)colpk[t];
-                if (rg == 0) a.scales_t[col * grp_rows + rt] = (uint8_t)sb[t];
-            }
+        for (int t = 0; t < 8; ++t) {
+            *reinterpret_cast<uint16_t*>(st + ST_COL_OFF + (lcol0 + t) * ST_PITCH + (lrow0 >> 1)) = (uint16_t)colpk[t];
+            if (rg == 0) st[ST_SCOL_OFF + (lcol0 + t) * 8 + wave] = (uint8_t)sb[t];
+        }
+    }
+    __syncthreads();
+
+    // ---- write the staged macro tile out: 16 bytes per lane, whole 128-byte lines ----
+    const uint32_t ncols_here = min(64u * a.tiles_per_wave, a.cols - mcol0);    // multiples of 32
+    const uint32_t nrows_here = min(256u, a.rows - mrow0);                       // multiples of 32
+    if (want_row) {
+        // row codes: nrows_here rows x ncols_here/2 bytes, in 16-byte pieces (32 columns each)
+        const uint32_t pieces = ncols_here >> 5;
+        for (uint32_t q = tid; q < nrows_here * pieces; q += TILE_THREADS) {
+            uint32_t r = q / pieces, pc = q - r * pieces;
+            uint4 v = *reinterpret_cast<const uint4*>(st + ST_ROW_OFF + r * ST_PITCH + pc * 16);
+            *reinterpret_cast<uint4*>(a.codes_row + (size_t)(mrow0 + r) * half_cols + (mcol0 >> 1) + pc * 16) = v;
+        }
+        for (uint32_t q = tid; q < nrows_here * pieces; q += TILE_THREADS) {
+            uint32_t r = q / pieces, pc = q - r * pieces;
+            a.scales_row[(size_t)(mrow0 + r) * grp_cols + (mcol0 >> 5) + pc] = st[ST_SROW_OFF + r * 8 + pc];
+        }
+    }
+    {
+        // transposed codes: ncols_here columns x nrows_here/2 bytes, in 16-byte pieces (32 rows each)
+        const uint32_t pieces = nrows_here >> 5;
+        for (uint32_t q = tid; q < ncols_here * pieces; q += TILE_THREADS) {
+            uint32_t cl = q / pieces, pc = q - cl * pieces;
+            uint4 v = *reinterpret_cast<const uint4*>(st + ST_COL_OFF + cl * ST_PITCH + pc * 16);
+            *reinterpret_cast<uint4*>(a.codes_t + (size_t)(mcol0 + cl) * half_rows + (mrow0 >> 1) + pc * 16) = v;
+        }
+        for (uint32_t q = tid; q < ncols_here * pieces; q += TILE_THREADS) {
+            uint32_t cl = q / pieces, pc = q - cl * pieces;
+            a.scales_t[(size_t)(mcol0 + cl) * grp_rows + (mrow0 >> 5) + pc] = st[ST_SCOL_OFF + cl * 8 + pc];
         }
     }
 }
@@ -295,10 +329,10 @@ __global__ void dequantize_kernel(const uint8_t* codes, const uint8_t* scales, i
     if (i >= total_bytes) return;
     int64_t half = cols >> 1;
     int64_t r = i / half, j = i - r * half;
-    float sc = fwd_scale(scales[r * (cols >> 5) + (j >> 4)]);
+    uint32_t byte = scales[r * (cols >> 5) + (j >> 4)];
     uint32_t b = codes[i];
-    out[2 * i] = dequant(b & 15u, sc);
-    out[2 * i + 1] = dequant(b >> 4, sc);
+    out[2 * i] = dequant(b & 15u, byte);
+    out[2 * i + 1] = dequant(b >> 4, byte);
 }
 
 __global__ __launch_bounds__(256) void calibration_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n)
@@ -324,13 +358,19 @@ hipError_t launch_quantize_rows(const QuantRowsParams& p, hipStream_t st)
     a.base_blk = p.index_base >> 3;
     const uint32_t per_block = ROWS_THREADS * ROWS_UNROLL;
     dim3 grid((a.total + per_block - 1) / per_block), block(ROWS_THREADS);
-    if (p.bf16) {
-        if (p.sr) hipLaunchKernelGGL((quantize_rows_kernel<uint16_t, true>), grid, block, 0, st, a);
-        else      hipLaunchKernelGGL((quantize_rows_kernel<uint16_t, false>), grid, block, 0, st, a);
-    } else {
-        if (p.sr) hipLaunchKernelGGL((quantize_rows_kernel<float, true>), grid, block, 0, st, a);
-        else      hipLaunchKernelGGL((quantize_rows_kernel<float, false>), grid, block, 0, st, a);
+#define MX_ROWS_LAUNCH(T, SR, FL) hipLaunchKernelGGL((quantize_rows_kernel<T, SR, FL>), grid, block, 0, st, a)
+    const int variant = (p.bf16 ? 4 : 0) | (p.sr ? 2 : 0) | (p.floor_mode ? 1 : 0);
+    switch (variant) {
+        case 0: MX_ROWS_LAUNCH(float, false, false); break;
+        case 1: MX_ROWS_LAUNCH(float, false, true); break;
+        case 2: MX_ROWS_LAUNCH(float, true, false); break;
+        case 3: MX_ROWS_LAUNCH(float, true, true); break;
+        case 4: MX_ROWS_LAUNCH(uint16_t, false, false); break;
+        case 5: MX_ROWS_LAUNCH(uint16_t, false, true); break;
+        case 6: MX_ROWS_LAUNCH(uint16_t, true, false); break;
+        default: MX_ROWS_LAUNCH(uint16_t, true, true); break;
     }
+#undef MX_ROWS_LAUNCH
     return hipGetLastError();
 }
 
@@ -347,16 +387,16 @@ hipError_t launch_ema_quantize(const QuantRowsParams& p, float* ema, float beta,
     return hipGetLastError();
 }
 
-template <int SRC>
+template <int SRC, bool FL>
 static void launch_tile_src(const TileArgs& a, bool row_sr, bool t_sr, dim3 grid, hipStream_t st)
 {
     dim3 block(TILE_THREADS);
     if (row_sr) {
-        if (t_sr) hipLaunchKernelGGL((quantize_tile_kernel<SRC, true, true>), grid, block, 0, st, a);
-        else      hipLaunchKernelGGL((quantize_tile_kernel<SRC, true, false>), grid, block, 0, st, a);
+        if (t_sr) hipLaunchKernelGGL((quantize_tile_kernel<SRC, true, true, FL>), grid, block, 0, st, a);
+        else      hipLaunchKernelGGL((quantize_tile_kernel<SRC, true, false, FL>), grid, block, 0, st, a);
     } else {
-        if (t_sr) hipLaunchKernelGGL((quantize_tile_kernel<SRC, false, true>), grid, block, 0, st, a);
-        else      hipLaunchKernelGGL((quantize_tile_kernel<SRC, false, false>), grid, block, 0, st, a);
+        if (t_sr) hipLaunchKernelGGL((quantize_tile_kernel<SRC, false, true, FL>), grid, block, 0, st, a);
+        else      hipLaunchKernelGGL((quantize_tile_kernel<SRC, false, false, FL>), grid, block, 0, st, a);
     }
 }
 
@@ -366,17 +406,24 @@ hipError_t launch_quantize_tile(const QuantTileParams& p, hipStream_t st)
     a.src = p.src; a.row_codes_in = p.row_codes_in; a.row_scales_in = p.row_scales_in;
     a.codes_t = p.codes_t; a.scales_t = p.scales_t; a.codes_row = p.codes_row; a.scales_row = p.scales_row;
     a.ld = p.ld; a.rows = (uint32_t)p.rows; a.cols = (uint32_t)p.cols;
-    a.pre_quant = p.pre_quant; a.floor_mode = p.floor_mode;
+    a.pre_quant = p.pre_quant;
     a.k0 = (uint32_t)p.seed; a.k1 = (uint32_t)(p.seed >> 32);
     a.tensor_id_t = p.tensor_id_t; a.tensor_id_row = p.tensor_id_row; a.index_base = p.index_base;
-    // Large tensors: 4 tiles per wave, so that one workgroup writes whole 128-byte lines of the
-    // row codes.  Small ones (weights) need the parallelism more than the write merging.
+    // Large tensors: 4 tiles per wave (a workgroup then owns whole 128-byte lines of the row
+    // codes).  Small ones (weights) need the parallelism more.
     a.tiles_per_wave = (p.rows * p.cols >= (int64_t)8 << 20) ? 4 : 1;
     const int64_t cols_per_block = 64 * a.tiles_per_wave;
     dim3 grid((unsigned)((p.cols + cols_per_block - 1) / cols_per_block), (unsigned)((p.rows + 255) / 256));
-    if (p.row_codes_in)  launch_tile_src<2>(a, false, p.sr_t, grid, st);
-    else if (p.bf16)     launch_tile_src<1>(a, p.sr_row, p.sr_t, grid, st);
-    else                 launch_tile_src<0>(a, p.sr_row, p.sr_t, grid, st);
+    const bool row_sr = p.row_codes_in ? false : p.sr_row;
+    if (p.floor_mode) {
+        if (p.row_codes_in)  launch_tile_src<2, true>(a, row_sr, p.sr_t, grid, st);
+        else if (p.bf16)     launch_tile_src<1, true>(a, row_sr, p.sr_t, grid, st);
+        else                 launch_tile_src<0, true>(a, row_sr, p.sr_t, grid, st);
+    } else {
+        if (p.row_codes_in)  launch_tile_src<2, false>(a, row_sr, p.sr_t, grid, st);
+        else if (p.bf16)     launch_tile_src<1, false>(a, row_sr, p.sr_t, grid, st);
+        else                 launch_tile_src<0, false>(a, row_sr, p.sr_t, grid, st);
+    }
     return hipGetLastError();
 }
 

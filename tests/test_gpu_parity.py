@@ -350,3 +350,36 @@ def test_determinism(mx):
     c = mx.mx_quantize_transposed(x, 1, 6, 1, True, 0, 1, seed=4)
     assert all(torch.equal(p, q) for p, q in zip(a, b))
     assert torch.equal(a[2], c[2]) and not torch.equal(a[0], c[0])   # RTN row codes ignore the seed
+
+
+# ------------------------------------------------- full size, bench launch configuration ----
+
+def test_full_size_vit_base_qkv_layer(mx, orc):
+    """ViT-B/16 batch 256 qkv layer (N = 50432, 768 -> 2304), bf16 sources, the exact calls and
+    buffers bench.py times: all packed bytes compared in full, products on 4096 sampled entries each."""
+    import mx_workloads as wl
+    N, D, C = 50432, 768, 2304
+    X, W, dY = wl.linear_layer(N, D, C, seed=0, dtype="bf16")
+    step = mx.MxLinearStep(N, D, C, out_dtype=torch.bfloat16, dw_dtype=torch.float32)
+    y = step.forward(dev(X, "bf16"), dev(W, "bf16"), seed=7)
+    dx, dw = step.backward(dev(dY, "bf16"), seed=7)
+    xt, wt, dy = oracle_layer(orc, X, W, dY, seed=7)
+    del X, W, dY
+    for got, want, nm in ((step.xq, xt[2], "Q1"), (step.xs, xt[3], "S1"), (step.xtq, xt[0], "Q6"), (step.xts, xt[1], "S6"),
+                          (step.wq, wt[2], "Q2"), (step.ws, wt[3], "S2"), (step.wtq, wt[0], "Q4"), (step.wts, wt[1], "S4"),
+                          (step.dyq, dy[2], "Q3"), (step.dys, dy[3], "S3"), (step.dytq, dy[0], "Q5"), (step.dyts, dy[1], "S5")):
+        assert_same_bytes(got, want, nm)
+    rng = np.random.default_rng(0)
+
+    def sampled(out, ops, m, n, nm, bf16):
+        ii = rng.integers(0, m, 4096)
+        jj = rng.integers(0, n, 4096)
+        ii[:4], jj[:4] = [0, m - 1, 0, m - 1], [0, 0, n - 1, n - 1]         # corners of the edge tiles
+        ref, absref = orc.gemm_f64_sampled(*ops, ii, jj)
+        got = host(out.float())[ii, jj].astype(np.float64)
+        tol = 1e-5 * absref + (np.abs(ref) * 2.0 ** -8 if bf16 else 0.0)
+        assert np.all(np.abs(got - ref) <= tol), (nm, np.max(np.abs(got - ref) / (absref + 1e-300)))
+
+    sampled(y, (xt[2], xt[3], wt[2], wt[3]), N, C, "Y", True)
+    sampled(dx, (dy[2], dy[3], wt[0], wt[1]), N, D, "dX", True)
+    sampled(dw, (dy[0], dy[1], xt[0], xt[1]), C, D, "dW", False)
