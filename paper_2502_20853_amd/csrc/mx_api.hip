@@ -107,7 +107,7 @@ int mx_quantize_transposed(const void* src, int dtype, int64_t rows, int64_t col
     if (!given && dtype != MX_DTYPE_F32 && dtype != MX_DTYPE_BF16) return MX_ERR_DTYPE;
     if (rows <= 0 || cols <= 0 || (rows % 32) != 0 || (cols % 32) != 0) return MX_ERR_SHAPE;
     if (!given && ld < cols) return MX_ERR_SHAPE;
-    if (rows > MAX_ELEMS / cols || rows > 65535LL * 256) return MX_ERR_SHAPE;
+    if (rows > MAX_ELEMS / cols || rows > 65535LL * 128) return MX_ERR_SHAPE;
     if (!aligned(codes_t, 16)) return MX_ERR_ALIGN;
     if (codes_row && !aligned(codes_row, 16)) return MX_ERR_ALIGN;
     if (given && !aligned(row_codes_in, 16)) return MX_ERR_ALIGN;

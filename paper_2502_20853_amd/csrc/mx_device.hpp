@@ -20,9 +20,9 @@ namespace mxd {
 // M = 0 uses epsilon = 1e-8, for which both rules give s = -29.
 __device__ __forceinline__ uint32_t scale_byte(uint32_t amax_bits, bool floor_mode)
 {
-    uint32_t field = amax_bits >> 23;
-    uint32_t inc = (!floor_mode && (amax_bits & 0x7FFFFFu) > 0x400000u) ? 1u : 0u;
-    int b = (int)field - 2 + (int)inc;
+    // adding 0x3FFFFF carries into the exponent field exactly when the mantissa exceeds 0x400000
+    uint32_t field = (amax_bits + (floor_mode ? 0u : 0x3FFFFFu)) >> 23;
+    int b = (int)field - 2;
     b = b < 0 ? 0 : b;
     return amax_bits == 0u ? 98u : (uint32_t)b;
 }
@@ -84,6 +84,49 @@ __device__ __forceinline__ uint32_t sr_code(float x, int e, uint32_t rinv)
     uint32_t mag = __float_as_uint(__builtin_ldexpf(__builtin_fabsf(x), e));
     if (FLOOR) mag = mag > GRID_MAX_BITS ? GRID_MAX_BITS : mag;
     return ((mag + rinv) >> 22) | ((__float_as_uint(x) >> 28) & 8u);
+}
+
+// round_D that also hands back the rounded magnitude on the grid's bit layout, i.e.
+// (code & 7) << 22 = m * 2^-126, for the double quantization that follows.
+template <bool FLOOR>
+__device__ __forceinline__ uint32_t rtn_code_keep(float x, int e, uint32_t& grid_bits)
+{
+    uint32_t vb = __float_as_uint(__builtin_ldexpf(x, e));
+    uint32_t mag = vb & 0x7FFFFFFFu;
+    if (FLOOR) mag = mag > GRID_MAX_BITS ? GRID_MAX_BITS : mag;
+    uint32_t t = mag + 0x200000u + (uint32_t)((int32_t)vb >> 31);
+    grid_bits = t & 0xFFC00000u;
+    return (t >> 22) | ((vb >> 28) & 8u);
+}
+
+template <bool FLOOR>
+__device__ __forceinline__ uint32_t sr_code_keep(float x, int e, uint32_t rinv, uint32_t& grid_bits)
+{
+    uint32_t mag = __float_as_uint(__builtin_ldexpf(__builtin_fabsf(x), e));
+    if (FLOOR) mag = mag > GRID_MAX_BITS ? GRID_MAX_BITS : mag;
+    uint32_t t = mag + rinv;
+    grid_bits = t & 0xFFC00000u;
+    return (t >> 22) | ((__float_as_uint(x) >> 28) & 8u);
+}
+
+// round_S of a non-negative value whose sign nibble (0 or 8) is supplied separately.
+template <bool FLOOR>
+__device__ __forceinline__ uint32_t sr_code_mag(float a, int e, uint32_t rinv, uint32_t sign8)
+{
+    uint32_t mag = __float_as_uint(__builtin_ldexpf(a, e));
+    if (FLOOR) mag = mag > GRID_MAX_BITS ? GRID_MAX_BITS : mag;
+    return ((mag + rinv) >> 22) | sign8;
+}
+
+// round_D of a non-negative value a with the sign supplied separately (sign8 = 0 or 8).
+// Only for values whose scaled form is exact (E2M1 x 2^s or bf16 sources near a
+// threshold are): the tie then goes up in magnitude for +, down for -.
+template <bool FLOOR>
+__device__ __forceinline__ uint32_t rtn_code_mag(float a, int e, uint32_t sign8)
+{
+    uint32_t mag = __float_as_uint(__builtin_ldexpf(a, e));
+    if (FLOOR) mag = mag > GRID_MAX_BITS ? GRID_MAX_BITS : mag;
+    return ((mag + 0x200000u - (sign8 >> 3)) >> 22) | sign8;
 }
 
 // |value| of an E2M1 code times 2^s, from the same bit layout: (code & 7) << 22 is

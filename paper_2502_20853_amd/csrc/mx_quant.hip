@@ -14,6 +14,9 @@
 #include "mx_device.hpp"
 #include "mx_launch.hpp"
 
+#include <cstdio>
+#include <cstdlib>
+
 using namespace mxd;
 
 namespace {
@@ -174,7 +177,8 @@ struct TileArgs {
     int64_t ld;
     uint32_t rows, cols;
     int pre_quant;
-    int tiles_per_wave;    // 32 x 64 tiles a wave walks along the columns (4 for large tensors, 1 for small ones)
+    int tiles_per_wave;    // 32 x 64 tiles a wave walks along the columns
+    int waves_c;           // waves of the workgroup side by side along the columns (1 or 2); 8 / waves_c along the rows
     uint32_t k0, k1, tensor_id_t, tensor_id_row;
     uint64_t index_base;
 };
@@ -190,23 +194,30 @@ template <int SRC, bool ROW_SR, bool T_SR, bool FLOOR>
 __global__ __launch_bounds__(TILE_THREADS, 4) void quantize_tile_kernel(TileArgs a)
 {
     __shared__ __attribute__((aligned(16))) uint8_t st[ST_BYTES];
-    if (ROW_SR == T_SR) set_round_mode_for<T_SR>();       // otherwise switched per phase below
+    // FP32 sources need the rounding mode of each rule (switched per phase when they differ).
+    // bf16 and packed sources scale exactly wherever a round_D threshold is near (8 significant
+    // bits), so there the mode of round_S, if any, serves the whole kernel.
+    constexpr bool SWITCH_MODES = (SRC == 0) && (ROW_SR != T_SR);
+    if (!SWITCH_MODES) set_round_mode_for<(ROW_SR || T_SR)>();
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int cc = lane & 7, rg = lane >> 3;
-    const uint32_t mrow0 = blockIdx.y * 256;              // macro tile origin
-    const uint32_t mcol0 = blockIdx.x * 64 * a.tiles_per_wave;
-    const uint32_t rt = blockIdx.y * 8 + wave;            // 32-row tile index
-    const bool wave_has_rows = rt * 32 < a.rows;
-    const uint32_t lrow0 = wave * 32 + 4 * rg;            // first of this lane's 4 rows inside the macro tile
+    const int wr = a.waves_c == 2 ? wave >> 1 : wave;     // wave position inside the macro tile
+    const int wc = a.waves_c == 2 ? wave & 1 : 0;
+    const uint32_t macro_rows = 256u / a.waves_c, macro_cols = 64u * a.waves_c * a.tiles_per_wave;
+    const uint32_t mrow0 = blockIdx.y * macro_rows;       // macro tile origin
+    const uint32_t mcol0 = blockIdx.x * macro_cols;
+    const bool wave_has_rows = mrow0 + wr * 32 < a.rows;
+    const uint32_t lrow0 = wr * 32 + 4 * rg;              // first of this lane's 4 rows inside the macro tile
     const uint32_t row0 = mrow0 + lrow0;
     const bool want_row = a.codes_row != nullptr;
     const uint32_t half_rows = a.rows >> 1, grp_rows = a.rows >> 5;
     const uint32_t half_cols = a.cols >> 1, grp_cols = a.cols >> 5;
 
     for (int ci = 0; ci < a.tiles_per_wave && wave_has_rows; ++ci) {
-        const uint32_t lcol0 = ci * 64 + cc * 8;          // first of this lane's 8 columns inside the macro tile
+        const uint32_t tcol0 = (wc * a.tiles_per_wave + ci) * 64;
+        const uint32_t lcol0 = tcol0 + cc * 8;            // first of this lane's 8 columns inside the macro tile
         const uint32_t c = mcol0 + lcol0;
-        if (mcol0 + ci * 64 >= a.cols) break;             // uniform over the wave
+        if (mcol0 + tcol0 >= a.cols) break;               // uniform over the wave
         const bool ok = c < a.cols;
         F8 x[4];
         // ---- load -----------------------------------------------------------
@@ -234,21 +245,32 @@ __global__ __launch_bounds__(TILE_THREADS, 4) void quantize_tile_kernel(TileArgs
             }
             // ---- 1x32 quantizer of the same elements ---------------------------
             if (want_row || a.pre_quant) {
-                if (ROW_SR != T_SR) set_round_mode_for<ROW_SR>();
+                if (SWITCH_MODES) set_round_mode_for<ROW_SR>();
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     uint32_t r = row0 + j;
                     uint32_t byte = scale_byte(quad_max(amax_bits8(x[j])), FLOOR);
+                    const int e = grid_exponent(byte);
                     U8 rnd;
                     if (ROW_SR) rnd = sr_addends((a.index_base + (uint64_t)r * a.cols + c) >> 3, a.tensor_id_row, a.k0, a.k1);
-                    uint32_t pk = encode8<ROW_SR, FLOOR>(x[j], grid_exponent(byte), rnd);
+                    uint32_t pk = 0;
+                    if (a.pre_quant) {
+                        // keep sign in the value: the next quantizer takes |x| and the sign from it
+#pragma unroll
+                        for (int t = 0; t < 8; ++t) {
+                            uint32_t gb;
+                            uint32_t code = ROW_SR ? sr_code_keep<FLOOR>(x[j].v[t], e, rnd.w[t], gb)
+                                                   : rtn_code_keep<FLOOR>(x[j].v[t], e, gb);
+                            pk |= code << (4 * t);
+                            float mag = __builtin_ldexpf(__uint_as_float(gb), (int)byte - 1);      // m * 2^s, exact
+                            x[j].v[t] = __builtin_copysignf(mag, x[j].v[t]);
+                        }
+                    } else {
+                        pk = encode8<ROW_SR, FLOOR>(x[j], e, rnd);
+                    }
                     if (want_row) {
                         *reinterpret_cast<uint32_t*>(st + ST_ROW_OFF + (lrow0 + j) * ST_PITCH + (lcol0 >> 1)) = pk;
                         if ((cc & 3) == 0) st[ST_SROW_OFF + (lrow0 + j) * 8 + (lcol0 >> 5)] = (uint8_t)byte;
-                    }
-                    if (a.pre_quant) {
-#pragma unroll
-                        for (int t = 0; t < 8; ++t) x[j].v[t] = dequant((pk >> (4 * t)) & 15u, byte);
                     }
                 }
             }
@@ -268,7 +290,7 @@ __global__ __launch_bounds__(TILE_THREADS, 4) void quantize_tile_kernel(TileArgs
             m = xor_lane_max(m, 32);
             sb[t] = scale_byte(m, FLOOR);
         }
-        if (ROW_SR != T_SR) set_round_mode_for<T_SR>();
+        if (SWITCH_MODES) set_round_mode_for<T_SR>();
         uint32_t colpk[8];
 #pragma unroll
         for (int t = 0; t < 8; ++t) colpk[t] = 0;
@@ -286,14 +308,14 @@ __global__ __launch_bounds__(TILE_THREADS, 4) void quantize_tile_kernel(TileArgs
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
             *reinterpret_cast<uint16_t*>(st + ST_COL_OFF + (lcol0 + t) * ST_PITCH + (lrow0 >> 1)) = (uint16_t)colpk[t];
-            if (rg == 0) st[ST_SCOL_OFF + (lcol0 + t) * 8 + wave] = (uint8_t)sb[t];
+            if (rg == 0) st[ST_SCOL_OFF + (lcol0 + t) * 8 + wr] = (uint8_t)sb[t];
         }
     }
     __syncthreads();
 
     // ---- write the staged macro tile out: 16 bytes per lane, whole 128-byte lines ----
-    const uint32_t ncols_here = min(64u * a.tiles_per_wave, a.cols - mcol0);    // multiples of 32
-    const uint32_t nrows_here = min(256u, a.rows - mrow0);                       // multiples of 32
+    const uint32_t ncols_here = min(macro_cols, a.cols - mcol0);    // multiples of 32
+    const uint32_t nrows_here = min(macro_rows, a.rows - mrow0);    // multiples of 32
     if (want_row) {
         // row codes: nrows_here rows x ncols_here/2 bytes, in 16-byte pieces (32 columns each)
         const uint32_t pieces = ncols_here >> 5;
@@ -409,11 +431,22 @@ hipError_t launch_quantize_tile(const QuantTileParams& p, hipStream_t st)
     a.pre_quant = p.pre_quant;
     a.k0 = (uint32_t)p.seed; a.k1 = (uint32_t)(p.seed >> 32);
     a.tensor_id_t = p.tensor_id_t; a.tensor_id_row = p.tensor_id_row; a.index_base = p.index_base;
-    // Large tensors: 4 tiles per wave (a workgroup then owns whole 128-byte lines of the row
-    // codes).  Small ones (weights) need the parallelism more.
-    a.tiles_per_wave = (p.rows * p.cols >= (int64_t)8 << 20) ? 4 : 1;
-    const int64_t cols_per_block = 64 * a.tiles_per_wave;
-    dim3 grid((unsigned)((p.cols + cols_per_block - 1) / cols_per_block), (unsigned)((p.rows + 255) / 256));
+    // Macro tile of a workgroup (8 waves): 256 rows x 128 columns (whole 128-byte lines of the
+    // transposed codes, 64-byte pieces of the row codes; measured a few percent faster than
+    // 256 x 256, whose fewer, longer waves leave more slots idle in the last round), 256 x 64 for
+    // small tensors such as weights.
+    const int64_t tiles = (p.rows / 32) * ((p.cols + 63) / 64);
+    if (tiles >= 8192) { a.tiles_per_wave = 2; a.waves_c = 1; }
+    else               { a.tiles_per_wave = 1; a.waves_c = 1; }
+    if (const char* ov = getenv("MX_TILE_SHAPE")) {      // "tiles_per_wave,waves_c": tuning aid
+        int t = 0, w = 0;
+        if (sscanf(ov, "%d,%d", &t, &w) == 2 && (t == 1 || t == 2 || t == 4) && (w == 1 || w == 2) && t * w <= 4) {
+            a.tiles_per_wave = t; a.waves_c = w;
+        }
+    }
+    const int64_t cols_per_block = 64 * a.tiles_per_wave * a.waves_c, rows_per_block = 256 / a.waves_c;
+    dim3 grid((unsigned)((p.cols + cols_per_block - 1) / cols_per_block),
+              (unsigned)((p.rows + rows_per_block - 1) / rows_per_block));
     const bool row_sr = p.row_codes_in ? false : p.sr_row;
     if (p.floor_mode) {
         if (p.row_codes_in)  launch_tile_src<2, true>(a, row_sr, p.sr_t, grid, st);
