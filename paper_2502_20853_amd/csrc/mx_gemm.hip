@@ -541,10 +541,15 @@ __global__ __launch_bounds__(D_NT, 2) void mx_gemm_dma_kernel(GemmArgs g)
 
     // ---- main loop, software-pipelined by half K steps: the LDS reads of the next 64-K
     //      slice are issued before the 8 MFMAs of the current one ----
+    // Three stages, two in flight: at the barrier in the middle of step kt every wave's reads of
+    // stage kt have returned (lgkmcnt(0) before the barrier), so that buffer takes stage kt+3
+    // while stage kt+2 is still on its way and stage kt+1 has just landed.
     if (nk > 0) issue(0, 0);
     if (nk > 1) issue(1, 1);
-    if (nk > 1) wait_vmcnt_then_barrier<D_LOADS_PER_STAGE>();
-    else        wait_vmcnt_then_barrier<0>();
+    if (nk > 2) issue(2, 2);
+    if (nk > 2)      wait_vmcnt_then_barrier<2 * D_LOADS_PER_STAGE>();
+    else if (nk > 1) wait_vmcnt_then_barrier<1 * D_LOADS_PER_STAGE>();
+    else             wait_vmcnt_then_barrier<0>();
     Frag f0, f1;
     Scales sc, scn;
     read_scales(0, sc);
@@ -555,10 +560,10 @@ __global__ __launch_bounds__(D_NT, 2) void mx_gemm_dma_kernel(GemmArgs g)
         read_frag(cur, 1, f1);
         mma(f0, sc, std::integral_constant<int, 0>{});
         if (kt + 1 < nk) {
-            // stage kt+1 was issued one K step ago; after the barrier every wave has also
-            // finished reading stage kt-1, whose buffer the next load overwrites
-            wait_vmcnt_then_barrier<0>();
-            if (kt + 2 < nk) issue((kt + 2) % D_STAGES, kt + 2);
+            // stage kt+1 must have landed; stage kt+2, if any, may stay in flight
+            if (kt + 2 < nk) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(D_LOADS_PER_STAGE) : "memory");
+            else             asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            if (kt + 3 < nk) issue(cur, kt + 3);
             const int nxt = (kt + 1) % D_STAGES;
             read_scales(nxt, scn);
             read_frag(nxt, 0, f0);
