@@ -582,20 +582,17 @@ __global__ __launch_bounds__(D_NT, 2) void mx_gemm_dma_kernel(GemmArgs g)
 
 // ---------------------------------------------------------------------------
 // Main path: K range of at least 512 per split.  Same tile, wave layout and MFMA
-// schedule as mx_gemm_dma_kernel; what changes is how scale bytes travel.  Reading
-// 4 scale bytes per row and K step costs one L2 request per row and step -- as many
-// requests as the codes need.  Here a load brings 16 scale bytes per row (4 K steps)
-// into a two-slot ring, and the code stages shrink to two (the operand reads of a
-// stage are complete before the barrier that frees it).  The last scale block of a K
-// range is shifted back so that it ends where the range ends.
-//   LDS: codes 2 x (A [256][64 B] + B [128][64 B]); scales 2 x [384 rows][16 B].
+// schedule as mx_gemm_dma_kernel; what changes is how scale bytes travel and that the
+// kernel is persistent.  Reading 4 scale bytes per row and K step costs one L2 request
+// per row and step -- as many requests as the codes need.  Here a load brings 16 scale
+// bytes per row (4 K steps) into a two-slot ring, and the code stages shrink to two (the
+// operand reads of a stage are complete before the barrier that frees it).  The last
+// scale block of a K range is shifted back so that it ends where the range ends.
 // ---------------------------------------------------------------------------
 constexpr int S_CODE_STAGE = (D_BM + D_BN) * 64;            // 24576
 constexpr int S_SCALE_OFF = 2 * S_CODE_STAGE;               // 49152
 constexpr int S_SCALE_SLOT = (D_BM + D_BN) * 16;            // 6144
-constexpr int S_LDS_BYTES = S_SCALE_OFF + 2 * S_SCALE_SLOT; // 61440 (epilogue strips need 67584)
-constexpr int S_LDS_ALLOC = D_WAVES * D_EP_BYTES > S_LDS_BYTES ? D_WAVES * D_EP_BYTES : S_LDS_BYTES;
-static_assert(2 * S_LDS_ALLOC <= 160 * 1024, "two workgroups per CU");
+constexpr int S_LDS_BYTES = S_SCALE_OFF + 2 * S_SCALE_SLOT; // 61440
 
 __device__ __forceinline__ void drain_then_barrier()
 {
@@ -603,70 +600,214 @@ __device__ __forceinline__ void drain_then_barrier()
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-__global__ __launch_bounds__(D_NT, 2) void mx_gemm_dma_sb_kernel(GemmArgs g)
+// ---------------------------------------------------------------------------
+// The grid is two workgroups per CU and each workgroup walks a list of tiles.  While the last two K steps of a tile are being
+// multiplied the first two stages (and scale blocks) of the next tile are already on
+// their way, and the output goes through an LDS region of its own, so the stores of
+// one tile overlap the loads of the next and there is no per-tile launch gap.
+//   LDS: codes 2 x 24576 | scales 2 x 6144 | output staging 4 waves x [32 rows][144 B].
+// Stage buffers and scale slots alternate over the whole tile sequence: a tile whose K
+// range has nk steps and nsb scale blocks hands parity (nk & 1) and slot (nsb & 1) on.
+// ---------------------------------------------------------------------------
+constexpr int P_EP_PITCH = 144;                              // 128 bytes of payload per row, padded
+constexpr int P_EP_BYTES = 32 * P_EP_PITCH;                  // per wave
+constexpr int P_EP_OFF = S_LDS_BYTES;
+constexpr int P_LDS_BYTES = P_EP_OFF + D_WAVES * P_EP_BYTES; // 79872
+static_assert(2 * P_LDS_BYTES <= 160 * 1024, "two workgroups per CU");
+constexpr unsigned P_SLOTS = 512;                            // 256 CUs x 2 resident workgroups
+
+// Lane index within the wave, computed anew at each use (two VALU instructions): code that
+// needs lane-derived values once per tile does not hold registers for them across the K loop.
+__device__ __forceinline__ uint32_t fresh_lane_id()
 {
-    __shared__ __attribute__((aligned(1024))) uint8_t lds[S_LDS_ALLOC];
+    uint32_t l;
+    asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(l));
+    return l;
+}
 
-    uint32_t zsplit, tm, tn;
-    decode_tile(g, zsplit, tm, tn);
-    const uint32_t m0 = tm * D_BM, n0 = tn * D_BN;
-    const uint32_t kbeg = zsplit * g.k_per_split;
-    const uint32_t kend = min(g.k, kbeg + g.k_per_split);
-    const int nk = (int)((kend - kbeg) >> 7);               // >= 4
-    const int nsb = (nk + 3) >> 2;                          // scale blocks of 4 K steps
+// A wave-uniform pointer, forced into scalar registers: an address formed as this plus a
+// 32-bit lane offset uses the scalar-base form of the global load.
+__device__ __forceinline__ const uint8_t* uniform_ptr(const uint8_t* p)
+{
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<const uint8_t*>(((uint64_t)hi << 32) | lo);
+}
+
+// Accumulators of one wave (64 rows x 128 columns) -> global through a 32-row LDS strip
+// holding 128 bytes per row: 64 bf16 or 32 fp32 columns at a time.  A store instruction
+// of the wave covers 8 whole 128-byte row segments.
+__device__ __forceinline__ void gemm_epilogue_chunked(const GemmArgs& g, uint8_t* ep, v16f (&acc)[2][4],
+                                                      uint32_t mrow0, uint32_t nbase, int lane_in, uint32_t zsplit)
+{
+    // lane-derived indices are recomputed at every call instead of living across the K loop
+    (void)lane_in;
+    const uint32_t lane = fresh_lane_id();
+    const uint32_t lrow = lane & 31, lhalf = lane >> 5;
+    const uint32_t rrow = lane >> 3, rchunk = lane & 7;
+    float* cf = static_cast<float*>(g.c);
+    uint16_t* ch = static_cast<uint16_t*>(g.c);
+    int64_t ldc = g.ldc;
+    if (g.split_k > 1) {
+        cf += (size_t)zsplit * g.m * g.n;
+        ldc = g.n;
+    }
+    const bool as_bf16 = g.c_bf16 && g.split_k == 1;
+    if (as_bf16) {
+        const bool vec_ok = (ldc & 7) == 0 && (reinterpret_cast<uintptr_t>(ch) & 15) == 0;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int jp = 0; jp < 2; ++jp) {
+#pragma unroll
+                for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const v16f& a = acc[i][2 * jp + jj];
+                        uint2 pk;
+                        pk.x = f32x2_to_bf16x2(a[4 * q], a[4 * q + 1]);
+                        pk.y = f32x2_to_bf16x2(a[4 * q + 2], a[4 * q + 3]);
+                        *reinterpret_cast<uint2*>(ep + lrow * P_EP_PITCH + (32 * jj + 8 * q + 4 * lhalf) * 2) = pk;
+                    }
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+                for (int it = 0; it < 4; ++it) {
+                    const uint32_t row = it * 8 + rrow;
+                    const uint32_t mm = mrow0 + i * 32 + row, nn = nbase + jp * 64 + rchunk * 8;
+                    uint4 v = *reinterpret_cast<const uint4*>(ep + row * P_EP_PITCH + rchunk * 16);
+                    if (mm < g.m && nn < g.n) {
+                        uint16_t* dst = ch + (size_t)mm * ldc + nn;
+                        if (nn + 8 <= g.n && vec_ok) {
+                            *reinterpret_cast<uint4*>(dst) = v;
+                        } else {
+                            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+                            for (int e = 0; e < 8; ++e)
+                                if (nn + e < g.n) dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+                        }
+                    }
+                }
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            }
+    } else {
+        const bool vec_ok = (ldc & 3) == 0 && (reinterpret_cast<uintptr_t>(cf) & 15) == 0;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    *reinterpret_cast<float4*>(ep + lrow * P_EP_PITCH + (8 * q + 4 * lhalf) * 4) =
+                        make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+                for (int it = 0; it < 4; ++it) {
+                    const uint32_t row = it * 8 + rrow;
+                    const uint32_t mm = mrow0 + i * 32 + row, nn = nbase + j * 32 + rchunk * 4;
+                    float4 v = *reinterpret_cast<const float4*>(ep + row * P_EP_PITCH + rchunk * 16);
+                    if (mm < g.m && nn < g.n) {
+                        float* dst = cf + (size_t)mm * ldc + nn;
+                        if (nn + 4 <= g.n && vec_ok) {
+                            *reinterpret_cast<float4*>(dst) = v;
+                        } else {
+                            const float w[4] = {v.x, v.y, v.z, v.w};
+                            for (int e = 0; e < 4; ++e)
+                                if (nn + e < g.n) dst[e] = w[e];
+                        }
+                    }
+                }
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            }
+    }
+}
+
+__global__ __launch_bounds__(D_NT, 2) void mx_gemm_persistent_kernel(GemmArgs g)
+{
+    __shared__ __attribute__((aligned(1024))) uint8_t lds[P_LDS_BYTES];
+
+    // ---- this workgroup's tile list: XCD x (= id % 8) owns a contiguous range of the logical
+    //      order (split, m tile, n tile); its workgroups take that range round-robin ----
+    const uint32_t tiles = g.tiles_m * g.tiles_n, total = tiles * (uint32_t)g.split_k;
+    const uint32_t xcd = blockIdx.x % 8, per = total / 8, rem = total % 8;
+    const uint32_t range_end = (xcd + 1) * per + min(xcd + 1, rem);
+    const uint32_t stride = (gridDim.x - xcd + 7) / 8;          // workgroups on this XCD
+    uint32_t L = xcd * per + min(xcd, rem) + blockIdx.x / 8;
+    if (L >= range_end) return;
+
     const uint32_t kbytes = g.k >> 1, kgroups = g.k >> 5;
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform, lives in an SGPR
     const uint32_t lrow = lane & 31, lhalf = lane >> 5;
     const uint32_t swz = (lrow >> 2) & 3;
 
-    const uint8_t* a_src[4];
-    const uint8_t* b_src[2];
+    // DMA sources: a uniform 64-bit base per tile (row m0 / n0, start of the K range) plus one
+    // 32-bit offset per lane and load (row within the tile, clamped at the matrix edge, and chunk).
+    uint32_t a_off[4], b_off[2], sa_off, sb_off;
+    const uint8_t *a_ptr, *b_ptr;       // codes of the next stage to issue (advance by 64 bytes per stage)
+    const uint8_t *sa_base, *sb_base;
+    uint32_t s_m0, s_n0, s_z;       // tile the sources currently point at
+    // Point the DMA sources at tile t; returns its number of K steps (>= 4).
+    auto set_sources = [&](uint32_t t) -> int {
+        s_z = t / tiles;
+        const uint32_t r = t - s_z * tiles, tm = r / g.tiles_n;
+        s_m0 = tm * D_BM;
+        s_n0 = (r - tm * g.tiles_n) * D_BN;
+        const uint32_t kbeg = s_z * g.k_per_split;
+        const uint32_t kend = min(g.k, kbeg + g.k_per_split);
+        const uint32_t mlast = g.m - 1 - s_m0, nlast = g.n - 1 - s_n0;    // last valid row of the tile
+        a_ptr = g.a_codes + (size_t)s_m0 * kbytes + (kbeg >> 1);
+        b_ptr = g.b_codes + (size_t)s_n0 * kbytes + (kbeg >> 1);
+        sa_base = g.a_scales + (size_t)s_m0 * kgroups + (kbeg >> 5);
+        sb_base = g.b_scales + (size_t)s_n0 * kgroups + (kbeg >> 5);
+        // lane i of a 16-row load fetches row i / 4, chunk (i % 4) ^ ((row >> 2) & 3); the row
+        // bases are multiples of 16, so the chunk depends on the lane only
+        const uint32_t ln = fresh_lane_id();    // recompute per tile rather than keep the products live
+        const uint32_t lr = ln >> 2, lc = ((ln & 3) ^ ((ln >> 4) & 3)) << 4;
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        uint32_t row = (4 * wave + u) * 16 + (lane >> 2);
-        uint32_t ch = (lane & 3) ^ ((row >> 2) & 3);
-        a_src[u] = g.a_codes + (size_t)min(m0 + row, g.m - 1) * kbytes + (kbeg >> 1) + ch * 16;
-    }
+        for (int u = 0; u < 4; ++u) a_off[u] = min(lr + (4 * wave + u) * 16, mlast) * kbytes + lc;
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-        uint32_t row = (2 * wave + u) * 16 + (lane >> 2);
-        uint32_t ch = (lane & 3) ^ ((row >> 2) & 3);
-        b_src[u] = g.b_codes + (size_t)min(n0 + row, g.n - 1) * kbytes + (kbeg >> 1) + ch * 16;
-    }
-    const uint8_t* sa_src = g.a_scales + (size_t)min(m0 + wave * 64 + lane, g.m - 1) * kgroups + (kbeg >> 5);
-    const uint8_t* sb_src = g.b_scales + (size_t)min(n0 + wave * 32 + lrow, g.n - 1) * kgroups + (kbeg >> 5);
+        for (int u = 0; u < 2; ++u) b_off[u] = min(lr + (2 * wave + u) * 16, nlast) * kbytes + lc;
+        sa_off = min((uint32_t)(wave * 64) + ln, mlast) * kgroups;
+        sb_off = min((uint32_t)(wave * 32) + (ln & 31), nlast) * kgroups;
+        return (int)((kend - kbeg) >> 7);
+    };
 
-    auto issue_codes = [&](int kt) {
-        uint8_t* base = lds + (kt & 1) * S_CODE_STAGE;
+    auto issue_codes = [&](int buf) {
+        uint8_t* base = lds + buf * S_CODE_STAGE;
+        const uint8_t* ap = uniform_ptr(a_ptr);
+        const uint8_t* bp = uniform_ptr(b_ptr);
+        // keep the 32-bit offsets opaque here so that their widening is not hoisted out of the
+        // K loop as 64-bit register pairs (the scalar-base address form takes the 32-bit value)
+#pragma unroll
+        for (int u = 0; u < 4; ++u) asm volatile("" : "+v"(a_off[u]));
+#pragma unroll
+        for (int u = 0; u < 2; ++u) asm volatile("" : "+v"(b_off[u]));
 #pragma unroll
         for (int u = 0; u < 4; ++u)
-            __builtin_amdgcn_global_load_lds(MX_GPTR(a_src[u] + kt * 64), MX_LPTR(base + (4 * wave + u) * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(MX_GPTR(ap + a_off[u]), MX_LPTR(base + (4 * wave + u) * 1024), 16, 0, 0);
 #pragma unroll
         for (int u = 0; u < 2; ++u)
-            __builtin_amdgcn_global_load_lds(MX_GPTR(b_src[u] + kt * 64), MX_LPTR(base + D_BM * 64 + (2 * wave + u) * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(MX_GPTR(bp + b_off[u]), MX_LPTR(base + D_BM * 64 + (2 * wave + u) * 1024), 16, 0, 0);
+        a_ptr += 64;
+        b_ptr += 64;
     };
-    auto scale_block_start = [&](int b) { return min(4 * b, nk - 4); };   // first K step the block covers
-    auto issue_scales = [&](int b) {
-        uint8_t* base = lds + S_SCALE_OFF + (b & 1) * S_SCALE_SLOT;
-        const int off = scale_block_start(b) * 4;
-        __builtin_amdgcn_global_load_lds(MX_GPTR(sa_src + off), MX_LPTR(base + wave * 1024), 16, 0, 0);
+    // scale block b of a K range of `steps` steps covers steps [min(4b, steps-4), +4)
+    auto issue_scales = [&](int slot, int b, int steps) {
+        uint8_t* base = lds + S_SCALE_OFF + slot * S_SCALE_SLOT;
+        const int off = min(4 * b, steps - 4) * 4;
+        const uint8_t* sap = uniform_ptr(sa_base + off);
+        const uint8_t* sbp = uniform_ptr(sb_base + off);
+        asm volatile("" : "+v"(sa_off));
+        asm volatile("" : "+v"(sb_off));
+        __builtin_amdgcn_global_load_lds(MX_GPTR(sap + sa_off), MX_LPTR(base + wave * 1024), 16, 0, 0);
         if (lane < 32)
-            __builtin_amdgcn_global_load_lds(MX_GPTR(sb_src + off), MX_LPTR(base + D_BM * 16 + wave * 512), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(MX_GPTR(sbp + sb_off), MX_LPTR(base + D_BM * 16 + wave * 512), 16, 0, 0);
     };
-
-    v16f acc[2][4];
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     struct Frag { v4i a[2]; v4i b[4]; };
     struct Scales { uint32_t a[2]; uint32_t b[4]; };
-    auto read_frag = [&](int kt, int kk, Frag& f) {
-        const uint8_t* base = lds + (kt & 1) * S_CODE_STAGE;
+    auto read_frag = [&](int buf, int kk, Frag& f) {
+        const uint8_t* base = lds + buf * S_CODE_STAGE;
         const uint32_t coff = ((2 * kk + lhalf) ^ swz) << 4;
 #pragma unroll
         for (int i = 0; i < 2; ++i)
@@ -675,9 +816,8 @@ __global__ __launch_bounds__(D_NT, 2) void mx_gemm_dma_sb_kernel(GemmArgs g)
         for (int j = 0; j < 4; ++j)
             f.b[j] = *reinterpret_cast<const v4i*>(base + D_BM * 64 + (j * 32 + lrow) * 64 + coff);
     };
-    auto read_scales = [&](int kt, Scales& sc) {
-        const int blk = kt >> 2;
-        const uint8_t* base = lds + S_SCALE_OFF + (blk & 1) * S_SCALE_SLOT + (kt - scale_block_start(blk)) * 4;
+    auto read_scales = [&](int slot, int within, Scales& sc) {
+        const uint8_t* base = lds + S_SCALE_OFF + slot * S_SCALE_SLOT + within * 4;
 #pragma unroll
         for (int i = 0; i < 2; ++i)
             sc.a[i] = *reinterpret_cast<const uint32_t*>(base + (wave * 64 + i * 32 + lrow) * 16);
@@ -691,6 +831,7 @@ __global__ __launch_bounds__(D_NT, 2) void mx_gemm_dma_sb_kernel(GemmArgs g)
 #pragma unroll
         for (int j = 0; j < 4; ++j) sc.b[j] >>= 8 * lhalf;
     };
+    v16f acc[2][4];
     auto mma = [&](const Frag& f, const Scales& sc, auto kc) {
         constexpr int kk = decltype(kc)::value;
 #pragma unroll
@@ -705,39 +846,89 @@ __global__ __launch_bounds__(D_NT, 2) void mx_gemm_dma_sb_kernel(GemmArgs g)
         }
     };
 
-    // ---- main loop, software-pipelined by half K steps ----
+    // ---- first tile: stages 0 and 1, scale blocks 0 and 1 ----
+    int nk = set_sources(L);
+    int pb = 0;                     // buffer of K step kt is (pb + kt) & 1
+    int sbase = 0;                  // slot of scale block b is (sbase + b) & 1
     issue_codes(0);
-    issue_scales(0);
-    if (nsb > 1) issue_scales(1);
+    issue_scales(0, 0, nk);
+    if (nk > 4) issue_scales(1, 1, nk);
     issue_codes(1);
-    wait_vmcnt_then_barrier<6>();          // all but the 6 code loads of stage 1
-    Frag f0, f1;
-    Scales sc, scn;
-    read_scales(0, sc);
-    read_frag(0, 0, f0);
-    shift_scales(sc);
-    for (int kt = 0; kt < nk; ++kt) {
-        read_frag(kt, 1, f1);
-        mma(f0, sc, std::integral_constant<int, 0>{});
-        if (kt + 1 < nk) {
-            // stage kt+1 (issued one K step ago) has landed; every wave's reads of stage kt
-            // have returned, so its buffer can take stage kt+2
+    wait_vmcnt_then_barrier<6>();   // all but the 6 code loads of stage 1
+
+    for (;;) {
+        // Here stage 0 and scale block 0 of the tile are visible to every wave; stage 1 and
+        // scale block 1 are in flight.
+        const uint32_t m0 = s_m0, n0 = s_n0, zsplit = s_z;
+        const int nsb = (nk + 3) >> 2;
+        const bool has_next = L + stride < range_end;
+        int nk_next = 0;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+        Frag f0, f1;
+        Scales sc, scn;
+        auto next_scales = [&](int kt1) {       // scales of K step kt1 of this tile
+            const int blk = kt1 >> 2;
+            read_scales((sbase + blk) & 1, kt1 - min(4 * blk, nk - 4), scn);
+        };
+        read_scales(sbase & 1, 0, sc);
+        read_frag(pb, 0, f0);
+        shift_scales(sc);
+        int buf = pb;
+        for (int kt = 0; kt < nk - 2; ++kt) {
+            read_frag(buf, 1, f1);
+            mma(f0, sc, std::integral_constant<int, 0>{});
+            // stage kt+1 has landed; every wave's reads of stage kt have returned, so its
+            // buffer can take stage kt+2
             drain_then_barrier();
-            if (kt + 2 < nk) issue_codes(kt + 2);
+            issue_codes(buf);
             // the slot of scale block b-1 was last read one K step ago: refill it with block b+1
-            if ((kt & 3) == 3 && (kt >> 2) + 2 < nsb) issue_scales((kt >> 2) + 2);
-            read_scales(kt + 1, scn);
-            read_frag(kt + 1, 0, f0);
-        }
-        mma(f1, sc, std::integral_constant<int, 1>{});
-        if (kt + 1 < nk) {
+            if ((kt & 3) == 3 && (kt >> 2) + 2 < nsb) issue_scales((sbase + (kt >> 2)) & 1, (kt >> 2) + 2, nk);
+            next_scales(kt + 1);
+            buf ^= 1;
+            read_frag(buf, 0, f0);
+            mma(f1, sc, std::integral_constant<int, 1>{});
             shift_scales(scn);
             sc = scn;
         }
+        // ---- K step nk-2: this tile issues no more loads; the freed buffer takes stage 0 of the
+        //      next tile.  Slot (sbase+nsb)&1 held scale block nsb-2, last read a K step ago. ----
+        read_frag(buf, 1, f1);
+        mma(f0, sc, std::integral_constant<int, 0>{});
+        drain_then_barrier();
+        if (has_next) {
+            nk_next = set_sources(L + stride);
+            issue_codes(buf);
+            issue_scales((sbase + nsb) & 1, 0, nk_next);
+        }
+        next_scales(nk - 1);
+        buf ^= 1;
+        read_frag(buf, 0, f0);
+        mma(f1, sc, std::integral_constant<int, 1>{});
+        shift_scales(scn);
+        // ---- K step nk-1 ----
+        read_frag(buf, 1, f1);
+        mma(f0, scn, std::integral_constant<int, 0>{});
+        mma(f1, scn, std::integral_constant<int, 1>{});
+        // Every wave is done reading this tile's buffers; stage 0 and scale block 0 of the next
+        // tile have landed.
+        drain_then_barrier();
+        if (has_next) {
+            issue_codes(buf);
+            if (nk_next > 4) issue_scales((sbase + nsb + 1) & 1, 1, nk_next);
+        }
+        gemm_epilogue_chunked(g, lds + P_EP_OFF + wave * P_EP_BYTES, acc, m0 + wave * 64, n0, lane, zsplit);
+        if (!has_next) break;
+        L += stride;
+        pb = (pb + nk) & 1;
+        sbase = (sbase + nsb) & 1;
+        nk = nk_next;
     }
-    drain_then_barrier();                  // every wave is done reading the stage buffers
-
-    gemm_epilogue_32x32(g, lds + wave * D_EP_BYTES, acc, m0 + wave * 64, n0, lane, zsplit);
 }
 
 }  // namespace
@@ -778,8 +969,12 @@ hipError_t launch_gemm(const GemmParams& p, hipStream_t st)
         g.tiles_n = (uint32_t)((p.n + D_BN - 1) / D_BN);
         dim3 grid(g.tiles_m * g.tiles_n * g.split_k);
         const uint32_t last_steps = ksteps - (uint32_t)(g.split_k - 1) * steps_per;
-        if (steps_per >= 4 && last_steps >= 4) hipLaunchKernelGGL(mx_gemm_dma_sb_kernel, grid, dim3(D_NT), 0, st, g);
-        else                                   hipLaunchKernelGGL(mx_gemm_dma_kernel, grid, dim3(D_NT), 0, st, g);
+        if (steps_per >= 4 && last_steps >= 4) {
+            const unsigned nblk = g.tiles_m * g.tiles_n * g.split_k;
+            hipLaunchKernelGGL(mx_gemm_persistent_kernel, dim3(nblk < P_SLOTS ? nblk : P_SLOTS), dim3(D_NT), 0, st, g);
+        } else {
+            hipLaunchKernelGGL(mx_gemm_dma_kernel, grid, dim3(D_NT), 0, st, g);
+        }
     } else {
         g.tiles_m = (uint32_t)((p.m + G_BM - 1) / G_BM);
         g.tiles_n = (uint32_t)((p.n + G_BN - 1) / G_BN);

@@ -250,6 +250,28 @@ def test_gemm_random_codes(mx, orc, m, n, k):
     check_product(orc, got, ac, as_, bc, bs, "fwd %dx%dx%d" % (m, n, k))
 
 
+@pytest.mark.parametrize("m,n,k", [(6100, 2900, 640), (9000, 2500, 896), (4200, 4000, 512)])
+def test_gemm_more_tiles_than_resident_workgroups(mx, orc, m, n, k):
+    # over 512 output tiles: workgroups of the persistent kernel walk several tiles, with odd and even
+    # K step counts (the stage-buffer parity carries over from tile to tile) and ragged edge tiles
+    ac, as_ = random_packed(m, k, 21, 120, 134)
+    bc, bs = random_packed(n, k, 22, 120, 134)
+    got = host(mx.mx_linear_fwd(dev(ac), dev(as_), dev(bc), dev(bs))).astype(np.float64)
+    rng = np.random.default_rng(k)
+    ii = np.concatenate([rng.integers(0, m, 20000), [0, m - 1, 0, m - 1]])
+    jj = np.concatenate([rng.integers(0, n, 20000), [0, 0, n - 1, n - 1]])
+    ref, absref = orc.gemm_f64_sampled(ac, as_, bc, bs, ii, jj)
+    assert np.all(np.abs(got[ii, jj] - ref) <= 1e-5 * absref)
+    # every tile is covered: row and column sums of the full product against FP64 sums
+    A, B = orc.dequantize(ac, as_), orc.dequantize(bc, bs)
+    col = A.sum(axis=0) @ B.T
+    colabs = np.abs(A).sum(axis=0) @ np.abs(B).T
+    assert np.all(np.abs(got.sum(axis=0) - col) <= 1e-5 * colabs)
+    row = A @ B.sum(axis=0)
+    rowabs = np.abs(A) @ np.abs(B).sum(axis=0)
+    assert np.all(np.abs(got.sum(axis=1) - row) <= 1e-5 * rowabs)
+
+
 def test_gemm_scale_bytes_and_one_hot(mx, orc):
     # operand with a single nonzero per row pins the lane <-> (row, K block) mapping of codes and scales
     m, n, k = 48, 40, 256
