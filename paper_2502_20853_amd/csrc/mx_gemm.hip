@@ -594,6 +594,25 @@ constexpr int S_SCALE_OFF = 2 * S_CODE_STAGE;               // 49152
 constexpr int S_SCALE_SLOT = (D_BM + D_BN) * 16;            // 6144
 constexpr int S_LDS_BYTES = S_SCALE_OFF + 2 * S_SCALE_SLOT; // 61440
 
+// No instruction is scheduled across this point.
+#define MX_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+// The same, placed after the MFMAs that produce acc and after the LDS reads that fill the operand
+// registers r0..r5.  Both are passed through the statement: the compiler can then neither sink
+// those MFMAs below the barrier nor keep the reads on its list of outstanding LDS operations (it
+// does not see the wait inside the statement and would wait for them again, together with
+// every read issued since, before their first use).
+__device__ __forceinline__ void drain_then_barrier_after(v16f (&acc)[2][4], v4i& r0, v4i& r1, v4i& r2, v4i& r3,
+                                                         v4i& r4, v4i& r5)
+{
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier"
+                 : "+v"(acc[0][0]), "+v"(acc[0][1]), "+v"(acc[0][2]), "+v"(acc[0][3]),
+                   "+v"(acc[1][0]), "+v"(acc[1][1]), "+v"(acc[1][2]), "+v"(acc[1][3]),
+                   "+v"(r0), "+v"(r1), "+v"(r2), "+v"(r3), "+v"(r4), "+v"(r5)
+                 :
+                 : "memory");
+}
+
 __device__ __forceinline__ void drain_then_barrier()
 {
     // all of this wave's loads have landed and all of its LDS reads have returned
@@ -625,6 +644,24 @@ __device__ __forceinline__ uint32_t fresh_lane_id()
     return l;
 }
 
+// DMA load, 16 bytes per lane: lane i's bytes [base + voff, +16) land at LDS address dst + 16 * i.
+// Written as an assembly statement for two reasons.  The compiler then keeps no record of
+// outstanding loads into LDS: with the builtin it waits for all of them (vmcnt(0)) before the
+// first LDS write that might overlap, which here is the output staging that is meant to run
+// while the next tile's loads are in flight; this kernel places every such wait itself.  And the
+// address takes the scalar-base form directly (uniform 64-bit base, 32-bit lane offset).
+// M0 (the LDS destination) is a reserved register that compiled code of this kernel does not
+// otherwise use, so it is not listed as clobbered.
+__device__ __forceinline__ void dma_load16(const uint8_t* lds_dst, const uint8_t* base, uint32_t voff)
+{
+    const uint32_t dst = __builtin_amdgcn_readfirstlane(
+        (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const uint8_t*)lds_dst);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(dst), "v"(voff), "s"(base)
+                 : "memory");
+}
+
 // A wave-uniform pointer, forced into scalar registers: an address formed as this plus a
 // 32-bit lane offset uses the scalar-base form of the global load.
 __device__ __forceinline__ const uint8_t* uniform_ptr(const uint8_t* p)
@@ -638,6 +675,17 @@ __device__ __forceinline__ const uint8_t* uniform_ptr(const uint8_t* p)
 // Accumulators of one wave (64 rows x 128 columns) -> global through a 32-row LDS strip
 // holding 128 bytes per row: 64 bf16 or 32 fp32 columns at a time.  A store instruction
 // of the wave covers 8 whole 128-byte row segments.
+// 16-byte store.  A final output is written with the nontemporal hint: it is not read again
+// here, and without the hint an output larger than the last-level cache slows the whole kernel
+// down while it drains (split-K partials keep the default policy, the reduction reads them).
+template <bool STREAM>
+__device__ __forceinline__ void store16(void* dst, v4i v)
+{
+    if (STREAM) __builtin_nontemporal_store(v, reinterpret_cast<v4i*>(dst));
+    else        *reinterpret_cast<v4i*>(dst) = v;
+}
+
+template <bool STREAM>
 __device__ __forceinline__ void gemm_epilogue_chunked(const GemmArgs& g, uint8_t* ep, v16f (&acc)[2][4],
                                                       uint32_t mrow0, uint32_t nbase, int lane_in, uint32_t zsplit)
 {
@@ -679,7 +727,7 @@ __device__ __forceinline__ void gemm_epilogue_chunked(const GemmArgs& g, uint8_t
                     if (mm < g.m && nn < g.n) {
                         uint16_t* dst = ch + (size_t)mm * ldc + nn;
                         if (nn + 8 <= g.n && vec_ok) {
-                            *reinterpret_cast<uint4*>(dst) = v;
+                            store16<STREAM>(dst, v4i{(int)v.x, (int)v.y, (int)v.z, (int)v.w});
                         } else {
                             const uint32_t w[4] = {v.x, v.y, v.z, v.w};
                             for (int e = 0; e < 8; ++e)
@@ -708,7 +756,7 @@ __device__ __forceinline__ void gemm_epilogue_chunked(const GemmArgs& g, uint8_t
                     if (mm < g.m && nn < g.n) {
                         float* dst = cf + (size_t)mm * ldc + nn;
                         if (nn + 4 <= g.n && vec_ok) {
-                            *reinterpret_cast<float4*>(dst) = v;
+                            store16<STREAM>(dst, v4i{__float_as_int(v.x), __float_as_int(v.y), __float_as_int(v.z), __float_as_int(v.w)});
                         } else {
                             const float w[4] = {v.x, v.y, v.z, v.w};
                             for (int e = 0; e < 4; ++e)
@@ -776,18 +824,12 @@ __global__ __launch_bounds__(D_NT, 2) void mx_gemm_persistent_kernel(GemmArgs g)
         uint8_t* base = lds + buf * S_CODE_STAGE;
         const uint8_t* ap = uniform_ptr(a_ptr);
         const uint8_t* bp = uniform_ptr(b_ptr);
-        // keep the 32-bit offsets opaque here so that their widening is not hoisted out of the
-        // K loop as 64-bit register pairs (the scalar-base address form takes the 32-bit value)
-#pragma unroll
-        for (int u = 0; u < 4; ++u) asm volatile("" : "+v"(a_off[u]));
-#pragma unroll
-        for (int u = 0; u < 2; ++u) asm volatile("" : "+v"(b_off[u]));
 #pragma unroll
         for (int u = 0; u < 4; ++u)
-            __builtin_amdgcn_global_load_lds(MX_GPTR(ap + a_off[u]), MX_LPTR(base + (4 * wave + u) * 1024), 16, 0, 0);
+            dma_load16(base + (4 * wave + u) * 1024, ap, a_off[u]);
 #pragma unroll
         for (int u = 0; u < 2; ++u)
-            __builtin_amdgcn_global_load_lds(MX_GPTR(bp + b_off[u]), MX_LPTR(base + D_BM * 64 + (2 * wave + u) * 1024), 16, 0, 0);
+            dma_load16(base + D_BM * 64 + (2 * wave + u) * 1024, bp, b_off[u]);
         a_ptr += 64;
         b_ptr += 64;
     };
@@ -797,11 +839,8 @@ __global__ __launch_bounds__(D_NT, 2) void mx_gemm_persistent_kernel(GemmArgs g)
         const int off = min(4 * b, steps - 4) * 4;
         const uint8_t* sap = uniform_ptr(sa_base + off);
         const uint8_t* sbp = uniform_ptr(sb_base + off);
-        asm volatile("" : "+v"(sa_off));
-        asm volatile("" : "+v"(sb_off));
-        __builtin_amdgcn_global_load_lds(MX_GPTR(sap + sa_off), MX_LPTR(base + wave * 1024), 16, 0, 0);
-        if (lane < 32)
-            __builtin_amdgcn_global_load_lds(MX_GPTR(sbp + sb_off), MX_LPTR(base + D_BM * 16 + wave * 512), 16, 0, 0);
+        dma_load16(base + wave * 1024, sap, sa_off);
+        if (lane < 32) dma_load16(base + D_BM * 16 + wave * 512, sbp, sb_off);
     };
 
     struct Frag { v4i a[2]; v4i b[4]; };
@@ -880,27 +919,37 @@ __global__ __launch_bounds__(D_NT, 2) void mx_gemm_persistent_kernel(GemmArgs g)
         read_frag(pb, 0, f0);
         shift_scales(sc);
         int buf = pb;
+        // The instruction scheduler is fenced (MX_SCHED_FENCE) so that each half step keeps the
+        // order written here: the LDS reads of the next half are issued first and return while the
+        // 8 MFMAs of the current half run.  Left alone it sinks the MFMAs below the barrier and
+        // waits for every batch of reads right after issuing it.
         for (int kt = 0; kt < nk - 2; ++kt) {
             read_frag(buf, 1, f1);
+            MX_SCHED_FENCE();
             mma(f0, sc, std::integral_constant<int, 0>{});
+            MX_SCHED_FENCE();
             // stage kt+1 has landed; every wave's reads of stage kt have returned, so its
             // buffer can take stage kt+2
-            drain_then_barrier();
+            drain_then_barrier_after(acc, f1.a[0], f1.a[1], f1.b[0], f1.b[1], f1.b[2], f1.b[3]);
             issue_codes(buf);
             // the slot of scale block b-1 was last read one K step ago: refill it with block b+1
             if ((kt & 3) == 3 && (kt >> 2) + 2 < nsb) issue_scales((sbase + (kt >> 2)) & 1, (kt >> 2) + 2, nk);
             next_scales(kt + 1);
             buf ^= 1;
             read_frag(buf, 0, f0);
+            MX_SCHED_FENCE();
             mma(f1, sc, std::integral_constant<int, 1>{});
+            MX_SCHED_FENCE();
             shift_scales(scn);
             sc = scn;
         }
         // ---- K step nk-2: this tile issues no more loads; the freed buffer takes stage 0 of the
         //      next tile.  Slot (sbase+nsb)&1 held scale block nsb-2, last read a K step ago. ----
         read_frag(buf, 1, f1);
+        MX_SCHED_FENCE();
         mma(f0, sc, std::integral_constant<int, 0>{});
-        drain_then_barrier();
+        MX_SCHED_FENCE();
+        drain_then_barrier_after(acc, f1.a[0], f1.a[1], f1.b[0], f1.b[1], f1.b[2], f1.b[3]);
         if (has_next) {
             nk_next = set_sources(L + stride);
             issue_codes(buf);
@@ -909,12 +958,16 @@ __global__ __launch_bounds__(D_NT, 2) void mx_gemm_persistent_kernel(GemmArgs g)
         next_scales(nk - 1);
         buf ^= 1;
         read_frag(buf, 0, f0);
+        MX_SCHED_FENCE();
         mma(f1, sc, std::integral_constant<int, 1>{});
+        MX_SCHED_FENCE();
         shift_scales(scn);
         // ---- K step nk-1 ----
         read_frag(buf, 1, f1);
+        MX_SCHED_FENCE();
         mma(f0, scn, std::integral_constant<int, 0>{});
         mma(f1, scn, std::integral_constant<int, 1>{});
+        MX_SCHED_FENCE();
         // Every wave is done reading this tile's buffers; stage 0 and scale block 0 of the next
         // tile have landed.
         drain_then_barrier();
@@ -922,7 +975,9 @@ __global__ __launch_bounds__(D_NT, 2) void mx_gemm_persistent_kernel(GemmArgs g)
             issue_codes(buf);
             if (nk_next > 4) issue_scales((sbase + nsb + 1) & 1, 1, nk_next);
         }
-        gemm_epilogue_chunked(g, lds + P_EP_OFF + wave * P_EP_BYTES, acc, m0 + wave * 64, n0, lane, zsplit);
+        // a final output (no K split) is streamed: it is not read again by this library
+        if (g.split_k == 1) gemm_epilogue_chunked<true>(g, lds + P_EP_OFF + wave * P_EP_BYTES, acc, m0 + wave * 64, n0, lane, zsplit);
+        else                gemm_epilogue_chunked<false>(g, lds + P_EP_OFF + wave * P_EP_BYTES, acc, m0 + wave * 64, n0, lane, zsplit);
         if (!has_next) break;
         L += stride;
         pb = (pb + nk) & 1;
