@@ -228,13 +228,15 @@ __device__ __forceinline__ uint32_t quad_max(uint32_t v)
     return v > o ? v : o;
 }
 
-// ---- source loads: 8 consecutive elements as FP32 --------------------------
+// ---- source loads: 8 consecutive elements as FP32; a source is read once, so the loads
+//      carry the nontemporal hint --------------------------
 struct F8 { float v[8]; };
 
 __device__ __forceinline__ F8 load8(const float* p)
 {
-    const float4* q = reinterpret_cast<const float4*>(p);
-    float4 a = q[0], b = q[1];
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    const f4* q = reinterpret_cast<const f4*>(p);
+    const f4 a = __builtin_nontemporal_load(q), b = __builtin_nontemporal_load(q + 1);
     F8 r;
     r.v[0] = a.x; r.v[1] = a.y; r.v[2] = a.z; r.v[3] = a.w;
     r.v[4] = b.x; r.v[5] = b.y; r.v[6] = b.z; r.v[7] = b.w;
@@ -243,7 +245,8 @@ __device__ __forceinline__ F8 load8(const float* p)
 
 __device__ __forceinline__ F8 load8(const uint16_t* p)   // bf16 bit patterns
 {
-    uint4 a = *reinterpret_cast<const uint4*>(p);
+    typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+    const u4 a = __builtin_nontemporal_load(reinterpret_cast<const u4*>(p));
     F8 r;
     r.v[0] = __uint_as_float(a.x << 16); r.v[1] = __uint_as_float(a.x & 0xFFFF0000u);
     r.v[2] = __uint_as_float(a.y << 16); r.v[3] = __uint_as_float(a.y & 0xFFFF0000u);
