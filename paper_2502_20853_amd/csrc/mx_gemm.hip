@@ -287,7 +287,7 @@ __global__ void splitk_reduce_kernel(const float* part, int split, uint32_t m, u
     size_t total = (size_t)m * n;
     if (idx >= total) return;
     float s = 0.f;
-    for (int z = 0; z < split; ++z) s += __builtin_nontemporal_load(part + (size_t)z * total + idx);   // read once
+    for (int z = 0; z < split; ++z) s += part[(size_t)z * total + idx];
     uint32_t r = (uint32_t)(idx / n), col = (uint32_t)(idx - (size_t)r * n);
     if (c_bf16) static_cast<uint16_t*>(c)[(size_t)r * ldc + col] = f32_to_bf16_rne(s);
     else        static_cast<float*>(c)[(size_t)r * ldc + col] = s;
