@@ -374,6 +374,85 @@ def test_determinism(mx):
     assert torch.equal(a[2], c[2]) and not torch.equal(a[0], c[0])   # RTN row codes ignore the seed
 
 
+# ------------------------------------------------- the other workload configurations ----
+
+def _check_layer(mx, orc, step, xt, wt, dy, y, dx, dw, N, D, C, bf16_out, sampled_only, tag):
+    for got, want, nm in ((step.xq, xt[2], "Q1"), (step.xs, xt[3], "S1"), (step.xtq, xt[0], "Q6"), (step.xts, xt[1], "S6"),
+                          (step.wq, wt[2], "Q2"), (step.ws, wt[3], "S2"), (step.wtq, wt[0], "Q4"), (step.wts, wt[1], "S4"),
+                          (step.dyq, dy[2], "Q3"), (step.dys, dy[3], "S3"), (step.dytq, dy[0], "Q5"), (step.dyts, dy[1], "S5")):
+        if want is not None:
+            assert_same_bytes(got, want, "%s %s" % (tag, nm))
+    rng = np.random.default_rng(N + D + C)
+    for out, ops, m, n, nm, bf in ((y, (xt[2], xt[3], wt[2], wt[3]), N, C, "Y", bf16_out),
+                                   (dx, (dy[2], dy[3], wt[0], wt[1]), N, D, "dX", bf16_out),
+                                   (dw, (dy[0], dy[1], xt[0], xt[1]), C, D, "dW", False)):
+        if not sampled_only and not bf:
+            check_product(orc, out, *ops, "%s %s" % (tag, nm))
+            continue
+        ii = rng.integers(0, m, 4096)
+        jj = rng.integers(0, n, 4096)
+        ii[:4], jj[:4] = [0, m - 1, 0, m - 1], [0, 0, n - 1, n - 1]
+        ref, absref = orc.gemm_f64_sampled(*ops, ii, jj)
+        got = host(out.float())[ii, jj].astype(np.float64)
+        tol = 1e-5 * absref + (np.abs(ref) * 2.0 ** -8 if bf else 0.0)
+        assert np.all(np.abs(got - ref) <= tol), (tag, nm, np.max(np.abs(got - ref) / (absref + 1e-300)))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_config_vit_tiny_all_layers(mx, orc, dtype):
+    """ViT-Tiny batch 64 (N = 12608, not a multiple of 128): the four layers of a block, FP32 and bf16
+    sources, FP32 outputs, every packed byte and every product entry checked."""
+    import mx_workloads as wl
+    for li, (name, N, D, C) in enumerate(wl.config_layers("vit_tiny_b64")):
+        X, W, dY = wl.linear_layer(N, D, C, seed=li, dtype=dtype, outliers=4)
+        step = mx.MxLinearStep(N, D, C, out_dtype=torch.float32)
+        y = step.forward(dev(X, dtype), dev(W, dtype), seed=li)
+        dx, dw = step.backward(dev(dY, dtype), seed=li)
+        xt, wt, dy = oracle_layer(orc, X, W, dY, seed=li)
+        _check_layer(mx, orc, step, xt, wt, dy, y, dx, dw, N, D, C, False, False, "vit_tiny %s %s" % (name, dtype))
+
+
+def test_config_vit_small_fc_layers(mx, orc):
+    """ViT-Small batch 128 (N = 25216 = 98.5 x 256): fc1 and fc2, bf16 sources and outputs."""
+    import mx_workloads as wl
+    for li, (name, N, D, C) in enumerate(wl.config_layers("vit_small_b128")):
+        if name not in ("fc1", "fc2"):
+            continue
+        X, W, dY = wl.linear_layer(N, D, C, seed=10 + li, dtype="bf16")
+        step = mx.MxLinearStep(N, D, C, out_dtype=torch.bfloat16, dw_dtype=torch.float32)
+        y = step.forward(dev(X, "bf16"), dev(W, "bf16"), seed=li)
+        dx, dw = step.backward(dev(dY, "bf16"), seed=li)
+        xt, wt, dy = oracle_layer(orc, X, W, dY, seed=li)
+        _check_layer(mx, orc, step, xt, wt, dy, y, dx, dw, N, D, C, True, True, "vit_small " + name)
+
+
+def test_config_vit_large_qema_layer(mx, orc):
+    """ViT-Large batch 256, proj layer (1024 -> 1024) with the weight through Q-EMA: 20 steps of the
+    master-weight walk, each followed by the EMA update and quantization; the last step's codes feed
+    the forward product and (re-quantized by Q4) the dX product."""
+    import mx_workloads as wl
+    N, D, C = 50432, 1024, 1024
+    X, _, dY = wl.linear_layer(N, D, C, seed=5, dtype="bf16")
+    step = mx.MxLinearStep(N, D, C, out_dtype=torch.bfloat16, dw_dtype=torch.float32, qema=True, beta=0.998)
+    ema = None
+    for t, W in enumerate(wl.weight_walk(C, D, seed=5, steps=20)):
+        if ema is None:
+            ema = np.zeros_like(W)
+        wc, wsc = orc.ema_weight_quant(W, ema, beta=0.998, update_ema=2 if t == 0 else 1)
+        step.quantize_weight(dev(W), seed=t)                  # EMA update + Q-EMA + Q4 of its result
+        assert_same_bytes(step.wq, wc, "Q-EMA codes step %d" % t)
+    assert np.array_equal(host(step.w_ema), ema)
+    # X and the products with the step-20 weight (forward() would update the EMA once more)
+    mx.mx_quantize_transposed(dev(X, "bf16"), 1, 6, 1, True, 0, 1, seed=20, out=(step.xtq, step.xts, step.xq, step.xs))
+    y = mx.mx_linear_fwd(step.xq, step.xs, step.wq, step.ws, out=step.y, workspace=step.workspace)
+    dx, dw = step.backward(dev(dY, "bf16"), seed=20)
+    wt4 = orc.quantize_transposed(W, round_t=1, tensor_id_t=4, pre_quant=1, want_row=False, row_in=(wc, wsc), seed=20)
+    xt = orc.quantize_transposed(X, round_t=1, tensor_id_t=6, pre_quant=1, round_row=0, tensor_id_row=1, seed=20)
+    dy = orc.quantize_transposed(dY, round_t=1, tensor_id_t=5, pre_quant=0, round_row=1, tensor_id_row=3, seed=20)
+    wt = (wt4[0], wt4[1], wc, wsc)
+    _check_layer(mx, orc, step, xt, wt, dy, y, dx, dw, N, D, C, True, True, "vit_large proj q-ema")
+
+
 # ------------------------------------------------- full size, bench launch configuration ----
 
 def test_full_size_vit_base_qkv_layer(mx, orc):
