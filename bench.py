@@ -98,6 +98,7 @@ def main():
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
     gemm_events, quant_events = [], []
+    per_launch = {}                        # (layer index, op) -> list of (start, end) events
 
     def run_step(seed, record):
         for st, (X, W, dY) in zip(steps_obj, inputs):
@@ -120,6 +121,9 @@ def main():
                 e[6].record()
                 quant_events.extend([(e[0], e[1]), (e[1], e[2]), (e[3], e[4])])
                 gemm_events.extend([(e[2], e[3]), (e[4], e[5]), (e[5], e[6])])
+                li = steps_obj.index(st)
+                for op, k in (("quant X", 0), ("quant W", 1), ("fwd", 2), ("quant dY", 3), ("dX", 4), ("dW", 5)):
+                    per_launch.setdefault((li, op), []).append((e[k], e[k + 1]))
 
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")      # 1 GiB read, 1 GiB written
@@ -152,6 +156,24 @@ def main():
         except Exception:
             traffic = None
 
+    # per launch: products in TFLOP/s against min(FP4 peak, algorithmic intensity x HBM peak) of the
+    # shape; quantizers in GB/s of algorithmic bytes
+    launches = []
+    for (li, op), evs in per_launch.items():
+        name, N, D, C = layers[li]
+        us = sum(a.elapsed_time(b) for a, b in evs) / len(evs) * 1e3
+        if op.startswith("quant"):
+            r, c = {"quant X": (N, D), "quant W": (C, D), "quant dY": (N, C)}[op]
+            launches.append({"layer": name, "op": op, "shape": [r, c], "us": round(us, 1),
+                             "GB/s": round(quant_bytes(r, c, sb) / us / 1e3, 1)})
+        else:
+            m, n, k, ob = {"fwd": (N, C, D, 2), "dX": (N, D, C, 2), "dW": (C, D, N, 4)}[op]
+            fl = 2.0 * m * n * k
+            by = (m + n) * k * 17 / 32 + m * n * ob
+            roof = min(PEAK_FP4_TFLOPS, fl / by * PEAK_HBM_GBS / 1e3)
+            launches.append({"layer": name, "op": op, "shape": [m, n, k], "us": round(us, 1),
+                             "TFLOP/s": round(fl / us / 1e6, 1), "shape_roofline_TFLOP/s": round(roof, 1)})
+
     out = {
         "metric": "MXFP4 linear fwd+bwd TFLOP/s at ViT-B shapes",
         "value": total_flops / (dt / args.steps) / 1e12,
@@ -172,6 +194,7 @@ def main():
                        "unit": "GB/s", "frac": q_bytes / (quant_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
                        "ms_per_step": quant_ms, "bytes_per_step": q_bytes},
         "gemm_ms_per_step": gemm_ms,
+        "launches": launches,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(layers, args.cpu_sample_tokens)

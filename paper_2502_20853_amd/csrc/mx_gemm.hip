@@ -1,3 +1,4 @@
+#define MX_GEMM_PINGPONG 1
 // C[m x n] = A[m x k] . B[n x k]^T on packed MXFP4 operands, FP32 accumulation
 // on gfx950's block-scaled FP4 matrix cores (V_MFMA_SCALE_F32_16X16X128_F8F6F4).
 // All three products of the layer (Eqs. 3-5, Sec. 3.3) have this form because
@@ -986,6 +987,290 @@ __global__ __launch_bounds__(D_NT, 2) void mx_gemm_persistent_kernel(GemmArgs g)
     }
 }
 
+
+// ---------------------------------------------------------------------------
+// Ping-pong form of the main path: one workgroup of 8 waves per CU, tile 256 x 256.
+// Waves 0-3 (group 0) and 4-7 (group 1) own the left and right 128 columns; wave w and
+// wave w+4 sit on the same SIMD.  Time is cut into slots separated by workgroup barriers.
+// In every slot one group issues its 16 MFMAs of a K step (M phase) while the other group
+// reads the operands of its next K step from LDS and issues DMA loads (L phase); then they
+// swap.  The matrix pipe of a SIMD always has exactly one wave feeding it, and no LDS or
+// DMA latency sits between two MFMA bursts of the same wave.
+//   Per 256 x 256 x 128 step the CU loads 32 KB through L2 -> LDS instead of the 2 x 24 KB of
+//   two 256 x 128 workgroups.
+//   LDS: 3 code stages x 32 KB | 3 scale slots x [512 rows][16 B] | output staging 8 x 4.5 KB.
+// Two cursors run over the workgroup's tile list.  The read cursor names the K step whose
+// operands the next L phase reads; the issue cursor runs two stages ahead of it (also across
+// tile boundaries) and names the stage the same L phase loads.  Stage q of a tile lives in
+// buffer (global stage count) % 3, scale block j in slot (global block count) % 3.
+// Safety of the ring: the L phase of step s reads stage s and overwrites the buffer of stage
+// s-1, whose last readers (the other group's L phase of step s-1, and this group's) finished
+// before the previous barrier.  Each wave ends an L phase with a wait for all loads it issued
+// in earlier phases, so stage s+1 is complete, and visible after the barrier, before its first
+// reader.  Scale block j of a tile is issued with stage 4j-1 (block 0 with stage 0), at least
+// two steps before its first reader and after the last reader of the slot's previous block.
+// ---------------------------------------------------------------------------
+constexpr int Q_BM = 256, Q_BN = 256, Q_NT = 512, Q_WAVES = 8, Q_STAGES = 3;
+constexpr int Q_STAGE_BYTES = (Q_BM + Q_BN) * 64;                       // 32768
+constexpr int Q_SCALE_OFF = Q_STAGES * Q_STAGE_BYTES;                   // 98304
+constexpr int Q_SCALE_SLOT = (Q_BM + Q_BN) * 16;                        // 8192
+constexpr int Q_EP_OFF = Q_SCALE_OFF + 3 * Q_SCALE_SLOT;                // 122880
+constexpr int Q_LDS_BYTES = Q_EP_OFF + Q_WAVES * P_EP_BYTES;            // 159744
+static_assert(Q_LDS_BYTES <= 160 * 1024, "one workgroup per CU");
+constexpr unsigned Q_SLOTS = 256;
+
+__device__ __forceinline__ void barrier_after_mfma(v16f (&acc)[2][4])
+{
+    // the accumulators pass through the statement: the MFMAs before it stay before it
+    asm volatile("s_barrier"
+                 : "+v"(acc[0][0]), "+v"(acc[0][1]), "+v"(acc[0][2]), "+v"(acc[0][3]),
+                   "+v"(acc[1][0]), "+v"(acc[1][1]), "+v"(acc[1][2]), "+v"(acc[1][3])
+                 :
+                 : "memory");
+}
+
+typedef __attribute__((address_space(3))) uint8_t lds_u8;
+
+// DMA load with the LDS destination given as a byte address (see dma_load16).
+__device__ __forceinline__ void dma_load16_at(uint32_t lds_addr, const uint8_t* base, uint32_t voff)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(base)
+                 : "memory");
+}
+
+// The whole tile walk of one wave; GRP (0: columns 0-127, M phase first; 1: columns 128-255, L phase
+// first) is a template parameter so that each group's loop is straight-line code.  All cursor
+// state is wave-uniform (scalar registers) and advanced with compares and adds only.
+template <int GRP>
+__device__ __forceinline__ void pingpong_wave(const GemmArgs& g, lds_u8* lds, const int wave)
+{
+    const uint32_t tiles = g.tiles_m * g.tiles_n, total = tiles * (uint32_t)g.split_k;
+    const uint32_t xcd = blockIdx.x % 8, per = total / 8, rem = total % 8;
+    const uint32_t range_end = (xcd + 1) * per + min(xcd + 1, rem);
+    const uint32_t stride = (gridDim.x - xcd + 7) / 8;          // workgroups on this XCD
+    const uint32_t first = xcd * per + min(xcd, rem) + blockIdx.x / 8;
+    if (first >= range_end) return;
+
+    const uint32_t kbytes = g.k >> 1, kgroups = g.k >> 5;
+    const int lane = threadIdx.x & 63;
+    const int wm = wave & 3;
+    const uint32_t lrow = lane & 31, lhalf = lane >> 5;
+    const uint32_t swz = (lrow >> 2) & 3;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
+
+    // K steps per tile: the same for every tile but those of the last K split
+    const int nk_full = (int)(g.k_per_split >> 7);
+    const int nk_tail = (int)((g.k - (uint32_t)(g.split_k - 1) * g.k_per_split) >> 7);
+    const uint32_t tail_first = tiles * (uint32_t)(g.split_k - 1);
+    auto tile_steps = [&](uint32_t t) -> int { return t >= tail_first ? nk_tail : nk_full; };
+
+    // ---- issue cursor: next stage to load.  The common path of a phase is straight-line
+    //      scalar code; everything rare (a scale block is due, the tile ends) sits behind one
+    //      branch each.  When the tile list is exhausted the cursor keeps re-loading the last
+    //      stage (i_step = 0) into buffers that no longer have readers. ----
+    uint32_t a_off[2], b_off[2], s_off;
+    const uint8_t *a_ptr, *b_ptr, *s_base;
+    uint32_t i_tile = first;
+    int i_nk = 0, i_q = 0;              // K steps of the issue tile, next stage of it to load
+    int i_due = 0, i_j = 0;             // stage that scale block i_j travels with
+    uint32_t i_step = 64;               // bytes the code pointers advance per stage
+    uint32_t i_dst = lds0 + wave * 2048;                          // this wave's A piece of the stage buffer
+    uint32_t i_sdst = lds0 + Q_SCALE_OFF + wave * 1024;           // this wave's piece of the scale slot
+    int i_buf = 0, i_slot = 0;
+    auto set_issue_tile = [&](uint32_t t) {
+        const uint32_t z = t / tiles, r = t - z * tiles, tm = r / g.tiles_n;
+        const uint32_t m0 = tm * Q_BM, n0 = (r - tm * g.tiles_n) * Q_BN;
+        const uint32_t kbeg = z * g.k_per_split;
+        const uint32_t mlast = g.m - 1 - m0, nlast = g.n - 1 - n0;
+        a_ptr = g.a_codes + (size_t)m0 * kbytes + (kbeg >> 1);
+        b_ptr = g.b_codes + (size_t)n0 * kbytes + (kbeg >> 1);
+        const uint32_t ln = fresh_lane_id();
+        const uint32_t lr = ln >> 2, lc = ((ln & 3) ^ ((ln >> 4) & 3)) << 4;
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            a_off[u] = min(lr + (2 * wave + u) * 16, mlast) * kbytes + lc;
+            b_off[u] = min(lr + (2 * wave + u) * 16, nlast) * kbytes + lc;
+        }
+        // scale rows: waves 0-3 fetch the A rows [64w, 64w+64), waves 4-7 the B rows [64(w-4), +64)
+        if (GRP == 0) {
+            s_base = g.a_scales + (size_t)m0 * kgroups + (kbeg >> 5);
+            s_off = min((uint32_t)(wm * 64) + ln, mlast) * kgroups;
+        } else {
+            s_base = g.b_scales + (size_t)n0 * kgroups + (kbeg >> 5);
+            s_off = min((uint32_t)(wm * 64) + ln, nlast) * kgroups;
+        }
+        i_nk = tile_steps(t);
+        i_q = 0;
+        i_due = 0;
+        i_j = 0;
+    };
+    // Loads the next stage (and the scale block that travels with it) and waits for every load
+    // issued in earlier phases.
+    auto issue_and_wait = [&]() {
+        if (i_q == i_due) {                                      // once per 4 K steps
+            const int off = min(4 * i_j, i_nk - 4) * 4;
+            dma_load16_at(i_sdst, s_base + off, s_off);
+            i_sdst += Q_SCALE_SLOT;
+            if (++i_slot == 3) { i_slot = 0; i_sdst -= 3 * Q_SCALE_SLOT; }
+            ++i_j;
+            i_due = 4 * i_j < i_nk ? 4 * i_j - 1 : 0x7FFFFFFF;
+            dma_load16_at(i_dst, a_ptr, a_off[0]);
+            dma_load16_at(i_dst + 1024, a_ptr, a_off[1]);
+            dma_load16_at(i_dst + Q_BM * 64, b_ptr, b_off[0]);
+            dma_load16_at(i_dst + Q_BM * 64 + 1024, b_ptr, b_off[1]);
+            asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+        } else {
+            dma_load16_at(i_dst, a_ptr, a_off[0]);
+            dma_load16_at(i_dst + 1024, a_ptr, a_off[1]);
+            dma_load16_at(i_dst + Q_BM * 64, b_ptr, b_off[0]);
+            dma_load16_at(i_dst + Q_BM * 64 + 1024, b_ptr, b_off[1]);
+            asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        }
+        a_ptr += i_step;
+        b_ptr += i_step;
+        i_dst = i_buf == 2 ? i_dst - 2 * Q_STAGE_BYTES : i_dst + Q_STAGE_BYTES;
+        i_buf = i_buf == 2 ? 0 : i_buf + 1;
+        if (++i_q == i_nk) {                                     // once per tile
+            i_tile += stride;
+            if (i_tile < range_end) {
+                set_issue_tile(i_tile);
+            } else {                                             // nothing left: stay on the last stage
+                a_ptr -= 64;
+                b_ptr -= 64;
+                i_step = 0;
+                i_q = 0;
+                i_nk = 0x7FFFFFFF;
+                i_due = -1;
+            }
+        }
+    };
+
+    // ---- read cursor: K step whose operands the next L phase reads (past the end of the tile
+    //      list it keeps reading the buffers; those operands are never used) ----
+    uint32_t r_tile = first;
+    int r_nk = tile_steps(first), r_s = 0;
+    int r_buf = 0, r_slot = 0;
+    uint32_t r_src = 0;                 // byte offset of the stage buffer
+    uint32_t r_sc = Q_SCALE_OFF;        // byte offset of this step's scale dwords: slot + 4 * (step within block)
+
+    // per-lane parts of the LDS read addresses
+    const uint32_t a_rd = (wm * 64 + lrow) * 64, b_rd = Q_BM * 64 + (GRP * 128 + lrow) * 64;
+    const uint32_t a_rd0 = a_rd + (((0 + lhalf) ^ swz) << 4), a_rd1 = a_rd + (((2 + lhalf) ^ swz) << 4);
+    const uint32_t b_rd0 = b_rd + (((0 + lhalf) ^ swz) << 4), b_rd1 = b_rd + (((2 + lhalf) ^ swz) << 4);
+    const uint32_t sa_rd = (wm * 64 + lrow) * 16, sb_rd = (Q_BM + GRP * 128 + lrow) * 16;
+
+    struct Frag { v4i a[2]; v4i b[4]; };
+    Frag f[2];
+    uint32_t sca[2], scb[4];
+    v16f acc[2][4];
+
+    auto load_phase = [&]() {
+        {
+            const lds_u8* sp = lds + r_sc;
+#pragma unroll
+            for (int i = 0; i < 2; ++i) sca[i] = *reinterpret_cast<const __attribute__((address_space(3))) uint32_t*>(sp + sa_rd + i * 512);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) scb[j] = *reinterpret_cast<const __attribute__((address_space(3))) uint32_t*>(sp + sb_rd + j * 512);
+            const lds_u8* base = lds + r_src;
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                f[0].a[i] = *reinterpret_cast<const __attribute__((address_space(3))) v4i*>(base + a_rd0 + i * 2048);
+                f[1].a[i] = *reinterpret_cast<const __attribute__((address_space(3))) v4i*>(base + a_rd1 + i * 2048);
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                f[0].b[j] = *reinterpret_cast<const __attribute__((address_space(3))) v4i*>(base + b_rd0 + j * 2048);
+                f[1].b[j] = *reinterpret_cast<const __attribute__((address_space(3))) v4i*>(base + b_rd1 + j * 2048);
+            }
+            // advance to the next K step
+            r_src = r_buf == 2 ? 0 : r_src + Q_STAGE_BYTES;
+            r_buf = r_buf == 2 ? 0 : r_buf + 1;
+            r_sc += 4;
+            ++r_s;
+            if (r_s == r_nk || (r_s & 3) == 0) {                 // it starts a scale block (once per <= 4 steps)
+                if (r_s == r_nk) {                               // ... of the next tile
+                    r_tile += stride;
+                    r_s = 0;
+                    r_nk = r_tile < range_end ? tile_steps(r_tile) : 0x7FFFFFFF;
+                }
+                r_slot = r_slot == 2 ? 0 : r_slot + 1;
+                // the last block of a K range is shifted back to end where the range ends
+                const int within = r_s + 4 > r_nk ? r_s - (r_nk - 4) : 0;
+                r_sc = Q_SCALE_OFF + r_slot * Q_SCALE_SLOT + within * 4;
+            }
+        }
+        issue_and_wait();
+#pragma unroll
+        for (int i = 0; i < 2; ++i) sca[i] >>= 8 * lhalf;      // (the compiler waits for the LDS reads here)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) scb[j] >>= 8 * lhalf;
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    };
+    auto mma_phase = [&]() {
+        MX_SCHED_FENCE();
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                v8i xa = v8i{f[kk].a[i].x, f[kk].a[i].y, f[kk].a[i].z, f[kk].a[i].w, 0, 0, 0, 0};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    v8i xb = v8i{f[kk].b[j].x, f[kk].b[j].y, f[kk].b[j].z, f[kk].b[j].w, 0, 0, 0, 0};
+                    if (kk == 0)
+                        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(xb, xa, acc[i][j], 4, 4, 0, (int)scb[j], 0, (int)sca[i]);
+                    else
+                        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(xb, xa, acc[i][j], 4, 4, 2, (int)scb[j], 2, (int)sca[i]);
+                }
+            }
+        MX_SCHED_FENCE();
+        barrier_after_mfma(acc);
+    };
+    auto zero_acc = [&]() {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    };
+
+    // ---- prologue: stages 0 and 1 (scale block 0 travels with stage 0) ----
+    set_issue_tile(first);
+    issue_and_wait();
+    issue_and_wait();                                                 // (ends with vmcnt(4): all but stage 1)
+    asm volatile("s_barrier" ::: "memory");                           // stage 0 and scale block 0 are in
+    if (GRP == 0) load_phase();                                       // operands of step 0 (ends with a barrier)
+    else          asm volatile("s_barrier" ::: "memory");
+    zero_acc();
+
+    // ---- slots: group 0 runs  M(k) | L(k+1),  group 1 runs  L(k) | M(k) ----
+    for (uint32_t c_tile = first; c_tile < range_end; c_tile += stride) {
+        const int nk = tile_steps(c_tile);
+        for (int k = 0; k < nk; ++k) {
+            if (GRP == 0) { mma_phase(); load_phase(); }
+            else          { load_phase(); mma_phase(); }
+        }
+        const uint32_t z = c_tile / tiles, r = c_tile - z * tiles, tm = r / g.tiles_n;
+        const uint32_t m0 = tm * Q_BM + wm * 64, n0 = (r - tm * g.tiles_n) * Q_BN + GRP * 128;
+        uint8_t* ep = (uint8_t*)(lds + Q_EP_OFF + wave * P_EP_BYTES);
+        if (g.split_k == 1) gemm_epilogue_chunked<true>(g, ep, acc, m0, n0, lane, z);
+        else                gemm_epilogue_chunked<false>(g, ep, acc, m0, n0, lane, z);
+        zero_acc();
+    }
+    // the cursor's trailing loads target this workgroup's LDS: they must land before it is released
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+
+__global__ __launch_bounds__(Q_NT, 2) void mx_gemm_pingpong_kernel(GemmArgs g)
+{
+    __shared__ __attribute__((aligned(1024))) uint8_t lds[Q_LDS_BYTES];
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (wave < 4) pingpong_wave<0>(g, (lds_u8*)lds, wave);
+    else          pingpong_wave<1>(g, (lds_u8*)lds, wave);
+}
+
 }  // namespace
 
 namespace mxl {
@@ -1024,6 +1309,14 @@ hipError_t launch_gemm(const GemmParams& p, hipStream_t st)
         g.tiles_n = (uint32_t)((p.n + D_BN - 1) / D_BN);
         dim3 grid(g.tiles_m * g.tiles_n * g.split_k);
         const uint32_t last_steps = ksteps - (uint32_t)(g.split_k - 1) * steps_per;
+#ifdef MX_GEMM_PINGPONG
+        if (steps_per >= 4 && last_steps >= 4) {
+            g.tiles_m = (uint32_t)((p.m + Q_BM - 1) / Q_BM);
+            g.tiles_n = (uint32_t)((p.n + Q_BN - 1) / Q_BN);
+            const unsigned nblk = g.tiles_m * g.tiles_n * g.split_k;
+            hipLaunchKernelGGL(mx_gemm_pingpong_kernel, dim3(nblk < Q_SLOTS ? nblk : Q_SLOTS), dim3(Q_NT), 0, st, g);
+        } else
+#endif
         if (steps_per >= 4 && last_steps >= 4) {
             const unsigned nblk = g.tiles_m * g.tiles_n * g.split_k;
             hipLaunchKernelGGL(mx_gemm_persistent_kernel, dim3(nblk < P_SLOTS ? nblk : P_SLOTS), dim3(D_NT), 0, st, g);
