@@ -1,4 +1,3 @@
-#define MX_GEMM_PINGPONG 1
 // C[m x n] = A[m x k] . B[n x k]^T on packed MXFP4 operands, FP32 accumulation
 // on gfx950's block-scaled FP4 matrix cores (V_MFMA_SCALE_F32_16X16X128_F8F6F4).
 // All three products of the layer (Eqs. 3-5, Sec. 3.3) have this form because
@@ -582,59 +581,14 @@ __global__ __launch_bounds__(D_NT, 2) void mx_gemm_dma_kernel(GemmArgs g)
 
 
 // ---------------------------------------------------------------------------
-// Main path: K range of at least 512 per split.  Same tile, wave layout and MFMA
-// schedule as mx_gemm_dma_kernel; what changes is how scale bytes travel and that the
-// kernel is persistent.  Reading 4 scale bytes per row and K step costs one L2 request
-// per row and step -- as many requests as the codes need.  Here a load brings 16 scale
-// bytes per row (4 K steps) into a two-slot ring, and the code stages shrink to two (the
-// operand reads of a stage are complete before the barrier that frees it).  The last
-// scale block of a K range is shifted back so that it ends where the range ends.
+// Helpers of the main path (K range of at least 512 per split; mx_gemm_pingpong_kernel below).
 // ---------------------------------------------------------------------------
-constexpr int S_CODE_STAGE = (D_BM + D_BN) * 64;            // 24576
-constexpr int S_SCALE_OFF = 2 * S_CODE_STAGE;               // 49152
-constexpr int S_SCALE_SLOT = (D_BM + D_BN) * 16;            // 6144
-constexpr int S_LDS_BYTES = S_SCALE_OFF + 2 * S_SCALE_SLOT; // 61440
 
 // No instruction is scheduled across this point.
 #define MX_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
-// The same, placed after the MFMAs that produce acc and after the LDS reads that fill the operand
-// registers r0..r5.  Both are passed through the statement: the compiler can then neither sink
-// those MFMAs below the barrier nor keep the reads on its list of outstanding LDS operations (it
-// does not see the wait inside the statement and would wait for them again, together with
-// every read issued since, before their first use).
-__device__ __forceinline__ void drain_then_barrier_after(v16f (&acc)[2][4], v4i& r0, v4i& r1, v4i& r2, v4i& r3,
-                                                         v4i& r4, v4i& r5)
-{
-    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier"
-                 : "+v"(acc[0][0]), "+v"(acc[0][1]), "+v"(acc[0][2]), "+v"(acc[0][3]),
-                   "+v"(acc[1][0]), "+v"(acc[1][1]), "+v"(acc[1][2]), "+v"(acc[1][3]),
-                   "+v"(r0), "+v"(r1), "+v"(r2), "+v"(r3), "+v"(r4), "+v"(r5)
-                 :
-                 : "memory");
-}
-
-__device__ __forceinline__ void drain_then_barrier()
-{
-    // all of this wave's loads have landed and all of its LDS reads have returned
-    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-}
-
-// ---------------------------------------------------------------------------
-// The grid is two workgroups per CU and each workgroup walks a list of tiles.  While the last two K steps of a tile are being
-// multiplied the first two stages (and scale blocks) of the next tile are already on
-// their way, and the output goes through an LDS region of its own, so the stores of
-// one tile overlap the loads of the next and there is no per-tile launch gap.
-//   LDS: codes 2 x 24576 | scales 2 x 6144 | output staging 4 waves x [32 rows][144 B].
-// Stage buffers and scale slots alternate over the whole tile sequence: a tile whose K
-// range has nk steps and nsb scale blocks hands parity (nk & 1) and slot (nsb & 1) on.
-// ---------------------------------------------------------------------------
-constexpr int P_EP_PITCH = 144;                              // 128 bytes of payload per row, padded
+constexpr int P_EP_PITCH = 144;                              // output staging: 128 bytes of payload per row, padded
 constexpr int P_EP_BYTES = 32 * P_EP_PITCH;                  // per wave
-constexpr int P_EP_OFF = S_LDS_BYTES;
-constexpr int P_LDS_BYTES = P_EP_OFF + D_WAVES * P_EP_BYTES; // 79872
-static_assert(2 * P_LDS_BYTES <= 160 * 1024, "two workgroups per CU");
-constexpr unsigned P_SLOTS = 512;                            // 256 CUs x 2 resident workgroups
 
 // Lane index within the wave, computed anew at each use (two VALU instructions): code that
 // needs lane-derived values once per tile does not hold registers for them across the K loop.
@@ -643,34 +597,6 @@ __device__ __forceinline__ uint32_t fresh_lane_id()
     uint32_t l;
     asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(l));
     return l;
-}
-
-// DMA load, 16 bytes per lane: lane i's bytes [base + voff, +16) land at LDS address dst + 16 * i.
-// Written as an assembly statement for two reasons.  The compiler then keeps no record of
-// outstanding loads into LDS: with the builtin it waits for all of them (vmcnt(0)) before the
-// first LDS write that might overlap, which here is the output staging that is meant to run
-// while the next tile's loads are in flight; this kernel places every such wait itself.  And the
-// address takes the scalar-base form directly (uniform 64-bit base, 32-bit lane offset).
-// M0 (the LDS destination) is a reserved register that compiled code of this kernel does not
-// otherwise use, so it is not listed as clobbered.
-__device__ __forceinline__ void dma_load16(const uint8_t* lds_dst, const uint8_t* base, uint32_t voff)
-{
-    const uint32_t dst = __builtin_amdgcn_readfirstlane(
-        (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const uint8_t*)lds_dst);
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :
-                 : "s"(dst), "v"(voff), "s"(base)
-                 : "memory");
-}
-
-// A wave-uniform pointer, forced into scalar registers: an address formed as this plus a
-// 32-bit lane offset uses the scalar-base form of the global load.
-__device__ __forceinline__ const uint8_t* uniform_ptr(const uint8_t* p)
-{
-    const uint64_t v = reinterpret_cast<uint64_t>(p);
-    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
-    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
-    return reinterpret_cast<const uint8_t*>(((uint64_t)hi << 32) | lo);
 }
 
 // Accumulators of one wave (64 rows x 128 columns) -> global through a 32-row LDS strip
@@ -770,224 +696,6 @@ __device__ __forceinline__ void gemm_epilogue_chunked(const GemmArgs& g, uint8_t
     }
 }
 
-__global__ __launch_bounds__(D_NT, 2) void mx_gemm_persistent_kernel(GemmArgs g)
-{
-    __shared__ __attribute__((aligned(1024))) uint8_t lds[P_LDS_BYTES];
-
-    // ---- this workgroup's tile list: XCD x (= id % 8) owns a contiguous range of the logical
-    //      order (split, m tile, n tile); its workgroups take that range round-robin ----
-    const uint32_t tiles = g.tiles_m * g.tiles_n, total = tiles * (uint32_t)g.split_k;
-    const uint32_t xcd = blockIdx.x % 8, per = total / 8, rem = total % 8;
-    const uint32_t range_end = (xcd + 1) * per + min(xcd + 1, rem);
-    const uint32_t stride = (gridDim.x - xcd + 7) / 8;          // workgroups on this XCD
-    uint32_t L = xcd * per + min(xcd, rem) + blockIdx.x / 8;
-    if (L >= range_end) return;
-
-    const uint32_t kbytes = g.k >> 1, kgroups = g.k >> 5;
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform, lives in an SGPR
-    const uint32_t lrow = lane & 31, lhalf = lane >> 5;
-    const uint32_t swz = (lrow >> 2) & 3;
-
-    // DMA sources: a uniform 64-bit base per tile (row m0 / n0, start of the K range) plus one
-    // 32-bit offset per lane and load (row within the tile, clamped at the matrix edge, and chunk).
-    uint32_t a_off[4], b_off[2], sa_off, sb_off;
-    const uint8_t *a_ptr, *b_ptr;       // codes of the next stage to issue (advance by 64 bytes per stage)
-    const uint8_t *sa_base, *sb_base;
-    uint32_t s_m0, s_n0, s_z;       // tile the sources currently point at
-    // Point the DMA sources at tile t; returns its number of K steps (>= 4).
-    auto set_sources = [&](uint32_t t) -> int {
-        s_z = t / tiles;
-        const uint32_t r = t - s_z * tiles, tm = r / g.tiles_n;
-        s_m0 = tm * D_BM;
-        s_n0 = (r - tm * g.tiles_n) * D_BN;
-        const uint32_t kbeg = s_z * g.k_per_split;
-        const uint32_t kend = min(g.k, kbeg + g.k_per_split);
-        const uint32_t mlast = g.m - 1 - s_m0, nlast = g.n - 1 - s_n0;    // last valid row of the tile
-        a_ptr = g.a_codes + (size_t)s_m0 * kbytes + (kbeg >> 1);
-        b_ptr = g.b_codes + (size_t)s_n0 * kbytes + (kbeg >> 1);
-        sa_base = g.a_scales + (size_t)s_m0 * kgroups + (kbeg >> 5);
-        sb_base = g.b_scales + (size_t)s_n0 * kgroups + (kbeg >> 5);
-        // lane i of a 16-row load fetches row i / 4, chunk (i % 4) ^ ((row >> 2) & 3); the row
-        // bases are multiples of 16, so the chunk depends on the lane only
-        const uint32_t ln = fresh_lane_id();    // recompute per tile rather than keep the products live
-        const uint32_t lr = ln >> 2, lc = ((ln & 3) ^ ((ln >> 4) & 3)) << 4;
-#pragma unroll
-        for (int u = 0; u < 4; ++u) a_off[u] = min(lr + (4 * wave + u) * 16, mlast) * kbytes + lc;
-#pragma unroll
-        for (int u = 0; u < 2; ++u) b_off[u] = min(lr + (2 * wave + u) * 16, nlast) * kbytes + lc;
-        sa_off = min((uint32_t)(wave * 64) + ln, mlast) * kgroups;
-        sb_off = min((uint32_t)(wave * 32) + (ln & 31), nlast) * kgroups;
-        return (int)((kend - kbeg) >> 7);
-    };
-
-    auto issue_codes = [&](int buf) {
-        uint8_t* base = lds + buf * S_CODE_STAGE;
-        const uint8_t* ap = uniform_ptr(a_ptr);
-        const uint8_t* bp = uniform_ptr(b_ptr);
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-            dma_load16(base + (4 * wave + u) * 1024, ap, a_off[u]);
-#pragma unroll
-        for (int u = 0; u < 2; ++u)
-            dma_load16(base + D_BM * 64 + (2 * wave + u) * 1024, bp, b_off[u]);
-        a_ptr += 64;
-        b_ptr += 64;
-    };
-    // scale block b of a K range of `steps` steps covers steps [min(4b, steps-4), +4)
-    auto issue_scales = [&](int slot, int b, int steps) {
-        uint8_t* base = lds + S_SCALE_OFF + slot * S_SCALE_SLOT;
-        const int off = min(4 * b, steps - 4) * 4;
-        const uint8_t* sap = uniform_ptr(sa_base + off);
-        const uint8_t* sbp = uniform_ptr(sb_base + off);
-        dma_load16(base + wave * 1024, sap, sa_off);
-        if (lane < 32) dma_load16(base + D_BM * 16 + wave * 512, sbp, sb_off);
-    };
-
-    struct Frag { v4i a[2]; v4i b[4]; };
-    struct Scales { uint32_t a[2]; uint32_t b[4]; };
-    auto read_frag = [&](int buf, int kk, Frag& f) {
-        const uint8_t* base = lds + buf * S_CODE_STAGE;
-        const uint32_t coff = ((2 * kk + lhalf) ^ swz) << 4;
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-            f.a[i] = *reinterpret_cast<const v4i*>(base + (wave * 64 + i * 32 + lrow) * 64 + coff);
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            f.b[j] = *reinterpret_cast<const v4i*>(base + D_BM * 64 + (j * 32 + lrow) * 64 + coff);
-    };
-    auto read_scales = [&](int slot, int within, Scales& sc) {
-        const uint8_t* base = lds + S_SCALE_OFF + slot * S_SCALE_SLOT + within * 4;
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-            sc.a[i] = *reinterpret_cast<const uint32_t*>(base + (wave * 64 + i * 32 + lrow) * 16);
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            sc.b[j] = *reinterpret_cast<const uint32_t*>(base + (D_BM + j * 32 + lrow) * 16);
-    };
-    auto shift_scales = [&](Scales& sc) {
-#pragma unroll
-        for (int i = 0; i < 2; ++i) sc.a[i] >>= 8 * lhalf;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) sc.b[j] >>= 8 * lhalf;
-    };
-    v16f acc[2][4];
-    auto mma = [&](const Frag& f, const Scales& sc, auto kc) {
-        constexpr int kk = decltype(kc)::value;
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            v8i xa = v8i{f.a[i].x, f.a[i].y, f.a[i].z, f.a[i].w, 0, 0, 0, 0};
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                v8i xb = v8i{f.b[j].x, f.b[j].y, f.b[j].z, f.b[j].w, 0, 0, 0, 0};
-                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                    xb, xa, acc[i][j], 4, 4, 2 * kk, (int)sc.b[j], 2 * kk, (int)sc.a[i]);
-            }
-        }
-    };
-
-    // ---- first tile: stages 0 and 1, scale blocks 0 and 1 ----
-    int nk = set_sources(L);
-    int pb = 0;                     // buffer of K step kt is (pb + kt) & 1
-    int sbase = 0;                  // slot of scale block b is (sbase + b) & 1
-    issue_codes(0);
-    issue_scales(0, 0, nk);
-    if (nk > 4) issue_scales(1, 1, nk);
-    issue_codes(1);
-    wait_vmcnt_then_barrier<6>();   // all but the 6 code loads of stage 1
-
-    for (;;) {
-        // Here stage 0 and scale block 0 of the tile are visible to every wave; stage 1 and
-        // scale block 1 are in flight.
-        const uint32_t m0 = s_m0, n0 = s_n0, zsplit = s_z;
-        const int nsb = (nk + 3) >> 2;
-        const bool has_next = L + stride < range_end;
-        int nk_next = 0;
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-        Frag f0, f1;
-        Scales sc, scn;
-        auto next_scales = [&](int kt1) {       // scales of K step kt1 of this tile
-            const int blk = kt1 >> 2;
-            read_scales((sbase + blk) & 1, kt1 - min(4 * blk, nk - 4), scn);
-        };
-        read_scales(sbase & 1, 0, sc);
-        read_frag(pb, 0, f0);
-        shift_scales(sc);
-        int buf = pb;
-        // The instruction scheduler is fenced (MX_SCHED_FENCE) so that each half step keeps the
-        // order written here: the LDS reads of the next half are issued first and return while the
-        // 8 MFMAs of the current half run.  Left alone it sinks the MFMAs below the barrier and
-        // waits for every batch of reads right after issuing it.
-        for (int kt = 0; kt < nk - 2; ++kt) {
-            read_frag(buf, 1, f1);
-            MX_SCHED_FENCE();
-            mma(f0, sc, std::integral_constant<int, 0>{});
-            MX_SCHED_FENCE();
-            // stage kt+1 has landed; every wave's reads of stage kt have returned, so its
-            // buffer can take stage kt+2
-            drain_then_barrier_after(acc, f1.a[0], f1.a[1], f1.b[0], f1.b[1], f1.b[2], f1.b[3]);
-            issue_codes(buf);
-            // the slot of scale block b-1 was last read one K step ago: refill it with block b+1
-            if ((kt & 3) == 3 && (kt >> 2) + 2 < nsb) issue_scales((sbase + (kt >> 2)) & 1, (kt >> 2) + 2, nk);
-            next_scales(kt + 1);
-            buf ^= 1;
-            read_frag(buf, 0, f0);
-            MX_SCHED_FENCE();
-            mma(f1, sc, std::integral_constant<int, 1>{});
-            MX_SCHED_FENCE();
-            shift_scales(scn);
-            sc = scn;
-        }
-        // ---- K step nk-2: this tile issues no more loads; the freed buffer takes stage 0 of the
-        //      next tile.  Slot (sbase+nsb)&1 held scale block nsb-2, last read a K step ago. ----
-        read_frag(buf, 1, f1);
-        MX_SCHED_FENCE();
-        mma(f0, sc, std::integral_constant<int, 0>{});
-        MX_SCHED_FENCE();
-        drain_then_barrier_after(acc, f1.a[0], f1.a[1], f1.b[0], f1.b[1], f1.b[2], f1.b[3]);
-        if (has_next) {
-            nk_next = set_sources(L + stride);
-            issue_codes(buf);
-            issue_scales((sbase + nsb) & 1, 0, nk_next);
-        }
-        next_scales(nk - 1);
-        buf ^= 1;
-        read_frag(buf, 0, f0);
-        MX_SCHED_FENCE();
-        mma(f1, sc, std::integral_constant<int, 1>{});
-        MX_SCHED_FENCE();
-        shift_scales(scn);
-        // ---- K step nk-1 ----
-        read_frag(buf, 1, f1);
-        MX_SCHED_FENCE();
-        mma(f0, scn, std::integral_constant<int, 0>{});
-        mma(f1, scn, std::integral_constant<int, 1>{});
-        MX_SCHED_FENCE();
-        // Every wave is done reading this tile's buffers; stage 0 and scale block 0 of the next
-        // tile have landed.
-        drain_then_barrier();
-        if (has_next) {
-            issue_codes(buf);
-            if (nk_next > 4) issue_scales((sbase + nsb + 1) & 1, 1, nk_next);
-        }
-        // a final output (no K split) is streamed: it is not read again by this library
-        if (g.split_k == 1) gemm_epilogue_chunked<true>(g, lds + P_EP_OFF + wave * P_EP_BYTES, acc, m0 + wave * 64, n0, lane, zsplit);
-        else                gemm_epilogue_chunked<false>(g, lds + P_EP_OFF + wave * P_EP_BYTES, acc, m0 + wave * 64, n0, lane, zsplit);
-        if (!has_next) break;
-        L += stride;
-        pb = (pb + nk) & 1;
-        sbase = (sbase + nsb) & 1;
-        nk = nk_next;
-    }
-}
-
-
 // ---------------------------------------------------------------------------
 // Ping-pong form of the main path: one workgroup of 8 waves per CU, tile 256 x 256.
 // Waves 0-3 (group 0) and 4-7 (group 1) own the left and right 128 columns; wave w and
@@ -1031,7 +739,14 @@ __device__ __forceinline__ void barrier_after_mfma(v16f (&acc)[2][4])
 
 typedef __attribute__((address_space(3))) uint8_t lds_u8;
 
-// DMA load with the LDS destination given as a byte address (see dma_load16).
+// DMA load, 16 bytes per lane: lane i's bytes [base + voff, +16) land at LDS byte address
+// lds_addr + 16 * i.  Written as an assembly statement for two reasons.  The compiler then keeps no
+// record of outstanding loads into LDS: with the builtin it waits for all of them (vmcnt(0)) before
+// the first LDS write that might overlap, which here is the output staging that runs while the
+// next tile's loads are in flight; this kernel places every such wait itself.  And the address
+// takes the scalar-base form directly (uniform 64-bit base, 32-bit lane offset) instead of 64-bit
+// per-lane addresses.  M0 (the LDS destination) is a reserved register that compiled code of
+// this kernel does not otherwise use, so it is not listed as clobbered.
 __device__ __forceinline__ void dma_load16_at(uint32_t lds_addr, const uint8_t* base, uint32_t voff)
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
@@ -1159,7 +874,7 @@ __device__ __forceinline__ void pingpong_wave(const GemmArgs& g, lds_u8* lds, co
     const uint32_t a_rd = (wm * 64 + lrow) * 64, b_rd = Q_BM * 64 + (GRP * 128 + lrow) * 64;
     const uint32_t a_rd0 = a_rd + (((0 + lhalf) ^ swz) << 4), a_rd1 = a_rd + (((2 + lhalf) ^ swz) << 4);
     const uint32_t b_rd0 = b_rd + (((0 + lhalf) ^ swz) << 4), b_rd1 = b_rd + (((2 + lhalf) ^ swz) << 4);
-    const uint32_t sa_rd = (wm * 64 + lrow) * 16, sb_rd = (Q_BM + GRP * 128 + lrow) * 16;
+    const uint32_t sa_rd = (wm * 64 + lane) * 16, sb_rd = (Q_BM + GRP * 128 + lane) * 16;    // lane, not lane % 32
 
     struct Frag { v4i a[2]; v4i b[4]; };
     Frag f[2];
@@ -1167,12 +882,15 @@ __device__ __forceinline__ void pingpong_wave(const GemmArgs& g, lds_u8* lds, co
     v16f acc[2][4];
 
     auto load_phase = [&]() {
+        uint32_t va, vb0, vb1;
         {
+            // scale dwords of this K step: one read serves two 32-row blocks (lanes 0-31 the first,
+            // lanes 32-63 the second; the 16-byte row pitch makes each read a 4-way bank conflict
+            // whether or not the two half waves read the same rows), then the halves are exchanged
             const lds_u8* sp = lds + r_sc;
-#pragma unroll
-            for (int i = 0; i < 2; ++i) sca[i] = *reinterpret_cast<const __attribute__((address_space(3))) uint32_t*>(sp + sa_rd + i * 512);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) scb[j] = *reinterpret_cast<const __attribute__((address_space(3))) uint32_t*>(sp + sb_rd + j * 512);
+            va = *reinterpret_cast<const __attribute__((address_space(3))) uint32_t*>(sp + sa_rd);
+            vb0 = *reinterpret_cast<const __attribute__((address_space(3))) uint32_t*>(sp + sb_rd);
+            vb1 = *reinterpret_cast<const __attribute__((address_space(3))) uint32_t*>(sp + sb_rd + 1024);
             const lds_u8* base = lds + r_src;
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
@@ -1202,10 +920,13 @@ __device__ __forceinline__ void pingpong_wave(const GemmArgs& g, lds_u8* lds, co
             }
         }
         issue_and_wait();
-#pragma unroll
-        for (int i = 0; i < 2; ++i) sca[i] >>= 8 * lhalf;      // (the compiler waits for the LDS reads here)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) scb[j] >>= 8 * lhalf;
+        // (the compiler waits for the LDS reads here)
+        const auto pa = __builtin_amdgcn_permlane32_swap(va, va, false, false);
+        const auto pb0 = __builtin_amdgcn_permlane32_swap(vb0, vb0, false, false);
+        const auto pb1 = __builtin_amdgcn_permlane32_swap(vb1, vb1, false, false);
+        sca[0] = pa[0] >> 8 * lhalf; sca[1] = pa[1] >> 8 * lhalf;
+        scb[0] = pb0[0] >> 8 * lhalf; scb[1] = pb0[1] >> 8 * lhalf;
+        scb[2] = pb1[0] >> 8 * lhalf; scb[3] = pb1[1] >> 8 * lhalf;
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     };
     auto mma_phase = [&]() {
@@ -1309,17 +1030,11 @@ hipError_t launch_gemm(const GemmParams& p, hipStream_t st)
         g.tiles_n = (uint32_t)((p.n + D_BN - 1) / D_BN);
         dim3 grid(g.tiles_m * g.tiles_n * g.split_k);
         const uint32_t last_steps = ksteps - (uint32_t)(g.split_k - 1) * steps_per;
-#ifdef MX_GEMM_PINGPONG
         if (steps_per >= 4 && last_steps >= 4) {
             g.tiles_m = (uint32_t)((p.m + Q_BM - 1) / Q_BM);
             g.tiles_n = (uint32_t)((p.n + Q_BN - 1) / Q_BN);
             const unsigned nblk = g.tiles_m * g.tiles_n * g.split_k;
             hipLaunchKernelGGL(mx_gemm_pingpong_kernel, dim3(nblk < Q_SLOTS ? nblk : Q_SLOTS), dim3(Q_NT), 0, st, g);
-        } else
-#endif
-        if (steps_per >= 4 && last_steps >= 4) {
-            const unsigned nblk = g.tiles_m * g.tiles_n * g.split_k;
-            hipLaunchKernelGGL(mx_gemm_persistent_kernel, dim3(nblk < P_SLOTS ? nblk : P_SLOTS), dim3(D_NT), 0, st, g);
         } else {
             hipLaunchKernelGGL(mx_gemm_dma_kernel, grid, dim3(D_NT), 0, st, g);
         }
