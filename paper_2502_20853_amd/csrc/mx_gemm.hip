@@ -927,7 +927,6 @@ __device__ __forceinline__ void pingpong_wave(const GemmArgs& g, lds_u8* lds, co
         sca[0] = pa[0] >> 8 * lhalf; sca[1] = pa[1] >> 8 * lhalf;
         scb[0] = pb0[0] >> 8 * lhalf; scb[1] = pb0[1] >> 8 * lhalf;
         scb[2] = pb1[0] >> 8 * lhalf; scb[3] = pb1[1] >> 8 * lhalf;
-        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     };
     auto mma_phase = [&]() {
         MX_SCHED_FENCE();
@@ -946,7 +945,6 @@ __device__ __forceinline__ void pingpong_wave(const GemmArgs& g, lds_u8* lds, co
                 }
             }
         MX_SCHED_FENCE();
-        barrier_after_mfma(acc);
     };
     auto zero_acc = [&]() {
 #pragma unroll
@@ -962,16 +960,27 @@ __device__ __forceinline__ void pingpong_wave(const GemmArgs& g, lds_u8* lds, co
     issue_and_wait();
     issue_and_wait();                                                 // (ends with vmcnt(4): all but stage 1)
     asm volatile("s_barrier" ::: "memory");                           // stage 0 and scale block 0 are in
-    if (GRP == 0) load_phase();                                       // operands of step 0 (ends with a barrier)
-    else          asm volatile("s_barrier" ::: "memory");
+    if (GRP == 0) load_phase();                                       // operands of step 0
     zero_acc();
 
-    // ---- slots: group 0 runs  M(k) | L(k+1),  group 1 runs  L(k) | M(k) ----
+    // ---- per K step one barrier: group 0 runs  M(k) | barrier | L(k+1),  group 1 runs
+    //      L(k) | barrier | M(k).  At the barrier every read of stage k has returned (group 0's were
+    //      consumed by M(k), group 1 waits for its own), so the loads issued after it may overwrite
+    //      that buffer; and every wave has waited for its part of stage k+1, which group 0 reads
+    //      right after it.  Between barriers the two waves of a SIMD drift freely: one is in its
+    //      MFMA burst while the other reads and loads. ----
     for (uint32_t c_tile = first; c_tile < range_end; c_tile += stride) {
         const int nk = tile_steps(c_tile);
         for (int k = 0; k < nk; ++k) {
-            if (GRP == 0) { mma_phase(); load_phase(); }
-            else          { load_phase(); mma_phase(); }
+            if (GRP == 0) {
+                mma_phase();
+                barrier_after_mfma(acc);
+                load_phase();
+            } else {
+                load_phase();
+                asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+                mma_phase();
+            }
         }
         const uint32_t z = c_tile / tiles, r = c_tile - z * tiles, tm = r / g.tiles_n;
         const uint32_t m0 = tm * Q_BM + wm * 64, n0 = (r - tm * g.tiles_n) * Q_BN + GRP * 128;
