@@ -293,6 +293,42 @@ __global__ void splitk_reduce_kernel(const float* part, int split, uint32_t m, u
     else        static_cast<float*>(c)[(size_t)r * ldc + col] = s;
 }
 
+// The same for n % 4 == 0 and 16-byte aligned rows of the output: four columns per thread, the
+// partial loads of a thread issued back to back (same summation order per element).
+__global__ void splitk_reduce4_kernel(const float* part, int split, uint32_t m, uint32_t n,
+                                      void* c, int64_t ldc, int c_bf16)
+{
+    const size_t q = (size_t)blockIdx.x * blockDim.x + threadIdx.x;       // index of a group of 4 columns
+    const size_t total = (size_t)m * n;
+    if (q * 4 >= total) return;
+    const float4* p4 = reinterpret_cast<const float4*>(part) + q;
+    const size_t zstride = total / 4;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    int z = 0;
+    for (; z + 4 <= split; z += 4) {
+        const float4 a = p4[(size_t)z * zstride], b = p4[(size_t)(z + 1) * zstride];
+        const float4 d = p4[(size_t)(z + 2) * zstride], e = p4[(size_t)(z + 3) * zstride];
+        s.x = (((s.x + a.x) + b.x) + d.x) + e.x;
+        s.y = (((s.y + a.y) + b.y) + d.y) + e.y;
+        s.z = (((s.z + a.z) + b.z) + d.z) + e.z;
+        s.w = (((s.w + a.w) + b.w) + d.w) + e.w;
+    }
+    for (; z < split; ++z) {
+        const float4 a = p4[(size_t)z * zstride];
+        s.x += a.x; s.y += a.y; s.z += a.z; s.w += a.w;
+    }
+    const size_t idx = q * 4;
+    const uint32_t r = (uint32_t)(idx / n), col = (uint32_t)(idx - (size_t)r * n);
+    if (c_bf16) {
+        uint2 o;
+        o.x = f32x2_to_bf16x2(s.x, s.y);
+        o.y = f32x2_to_bf16x2(s.z, s.w);
+        *reinterpret_cast<uint2*>(static_cast<uint16_t*>(c) + (size_t)r * ldc + col) = o;
+    } else {
+        *reinterpret_cast<float4*>(static_cast<float*>(c) + (size_t)r * ldc + col) = s;
+    }
+}
+
 constexpr int G_BM = 256, G_BN = 256, G_WM = 128, G_WN = 64;
 
 // ---------------------------------------------------------------------------
@@ -1058,9 +1094,18 @@ hipError_t launch_gemm(const GemmParams& p, hipStream_t st)
     if (e != hipSuccess) return e;
     if (g.split_k > 1) {
         size_t total = (size_t)p.m * p.n;
-        dim3 rgrid((unsigned)((total + 255) / 256)), rblock(256);
-        hipLaunchKernelGGL(splitk_reduce_kernel, rgrid, rblock, 0, st,
-                           static_cast<const float*>(p.workspace), g.split_k, g.m, g.n, p.c, p.ldc, (int)p.c_bf16);
+        const size_t out_bytes = p.c_bf16 ? 2 : 4;
+        const bool vec = (p.n & 3) == 0 && ((size_t)p.ldc * out_bytes & 15) == 0 &&
+                         (reinterpret_cast<uintptr_t>(p.c) & 15) == 0 && (reinterpret_cast<uintptr_t>(p.workspace) & 15) == 0;
+        if (vec) {
+            dim3 rgrid((unsigned)((total / 4 + 255) / 256)), rblock(256);
+            hipLaunchKernelGGL(splitk_reduce4_kernel, rgrid, rblock, 0, st,
+                               static_cast<const float*>(p.workspace), g.split_k, g.m, g.n, p.c, p.ldc, (int)p.c_bf16);
+        } else {
+            dim3 rgrid((unsigned)((total + 255) / 256)), rblock(256);
+            hipLaunchKernelGGL(splitk_reduce_kernel, rgrid, rblock, 0, st,
+                               static_cast<const float*>(p.workspace), g.split_k, g.m, g.n, p.c, p.ldc, (int)p.c_bf16);
+        }
         e = hipGetLastError();
     }
     return e;
