@@ -242,7 +242,10 @@ def check_product(orc, got, ac, as_, bc, bs, what, tol=1e-5):
                                     (1, 1, 128), (256, 256, 128), (300, 200, 384), (515, 260, 1024),
                                     (257, 129, 256), (33, 700, 1408), (768, 768, 512),
                                     # >= 4 K steps: 256-K stages, odd step counts, shifted last scale block
-                                    (40, 48, 640), (300, 520, 1152), (130, 260, 896), (64, 64, 2688)])
+                                    (40, 48, 640), (300, 520, 1152), (130, 260, 896), (64, 64, 2688),
+                                    # K splits of unequal length (10,10,10,7 steps) and a last split too short
+                                    # for the main kernel (9 x 6 + 3 steps: the short-K kernel takes it all)
+                                    (100, 300, 4736), (70, 130, 7296)])
 def test_gemm_random_codes(mx, orc, m, n, k):
     ac, as_ = random_packed(m, k, 1)
     bc, bs = random_packed(n, k, 2)
