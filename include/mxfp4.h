@@ -108,7 +108,8 @@ int mx_quantize_transposed(const void* src, int dtype, int64_t rows, int64_t col
  * The three products (Sec. 3.3, Eqs. 3-5), FP32 accumulation on the
  * block-scaled FP4 matrix cores.  X[N x D], W[C x D], Y[N x C].  Every operand
  * is packed along the product's contraction dimension, which must be a
- * multiple of 32; the other two dimensions are arbitrary (>= 1).
+ * multiple of 32 and at most 2^24; the other two dimensions are arbitrary
+ * (>= 1, below 2^31, with fewer than 2^30 output tiles of 256 x 128).
  * Operand code pointers must be 16-byte aligned and the contraction dimension
  * a multiple of 32; out dtype F32 or BF16 (round to nearest even), ld >= row
  * length.  workspace: device, 256-byte aligned, at least

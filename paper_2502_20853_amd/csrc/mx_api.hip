@@ -40,8 +40,9 @@ int check_gemm_call(const uint8_t* aq, const uint8_t* as, const uint8_t* bq, con
     if (!aq || !as || !bq || !bs || !out) return MX_ERR_NULL;
     if (out_dtype != MX_DTYPE_F32 && out_dtype != MX_DTYPE_BF16) return MX_ERR_DTYPE;
     if (m <= 0 || n <= 0 || k <= 0 || (k % 32) != 0 || ldo < n) return MX_ERR_SHAPE;
-    if (m > 0x7FFFFFFFLL || n > 0x7FFFFFFFLL || k > 0x7FFFFFFFLL) return MX_ERR_SHAPE;
-    if (((m + 255) / 256) * ((n + 255) / 256) > 0x7FFFFFFFLL) return MX_ERR_SHAPE;
+    // the kernels index with 32 bits: tile counts, and byte offsets of up to 256 packed rows
+    if (m > 0x7FFFFFFFLL || n > 0x7FFFFFFFLL || k > (1LL << 24)) return MX_ERR_SHAPE;
+    if (((m + 255) / 256) * ((n + 127) / 128) > 0x3FFFFFFFLL) return MX_ERR_SHAPE;
     if (!aligned(aq, 16) || !aligned(bq, 16) || !aligned(as, 4) || !aligned(bs, 4)) return MX_ERR_ALIGN;
     if (!aligned(out, out_dtype == MX_DTYPE_BF16 ? 8 : 16)) return MX_ERR_ALIGN;
     return MX_OK;

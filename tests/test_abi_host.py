@@ -100,6 +100,7 @@ def test_linear_rejects(L):
     assert g(L, "mx_linear_fwd", D=48) == -2          # contraction dims must be multiples of 32
     assert g(L, "mx_linear_bwd_dx", C=48) == -2
     assert g(L, "mx_linear_bwd_dw", N=48) == -2
+    assert g(L, "mx_linear_fwd", D=(1 << 24) + 32) == -2      # contraction dimension above 2^24
     # a product that splits K demands its workspace
     need = L.mx_linear_workspace_bytes(2, 50432, 768, 768)
     assert need > 0 and need % (768 * 768 * 4) == 0
