@@ -143,6 +143,25 @@ def main():
     dt = time.perf_counter() - t0
     ms_per_step = dt * 1e3 / args.steps
 
+    # Q-EMA weight quantizer (Sec. 5), outside the timed region: the four weights of the block, one
+    # update + quantization each, as a training step with Q-EMA would issue them
+    qema = []
+    for (name, N, D, C), (X, W, dY) in zip(layers, inputs):
+        w32 = W.float()
+        ema = w32.clone()
+        out = (torch.empty((C, D // 2), dtype=torch.uint8, device="cuda"), torch.empty((C, D // 32), dtype=torch.uint8, device="cuda"))
+        for _ in range(3):
+            mx.binding.mx_ema_weight_quant(w32, ema, 0.998, 1, out=out)
+        e0, e1 = ev(), ev()
+        e0.record()
+        for _ in range(20):
+            mx.binding.mx_ema_weight_quant(w32, ema, 0.998, 1, out=out)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / 20 * 1e3
+        qema.append({"layer": name, "shape": [C, D], "us": round(us, 1),
+                     "GB/s": round(C * D * (4 + 4 + 4 + 0.5 + 1.0 / 32) / us / 1e3, 1)})
+
     gemm_ms = sum(a.elapsed_time(b) for a, b in gemm_events) / args.steps      # per step, all 12 products
     quant_ms = sum(a.elapsed_time(b) for a, b in quant_events) / args.steps
     n_gemm = 3 * len(layers)
@@ -195,6 +214,7 @@ def main():
                        "ms_per_step": quant_ms, "bytes_per_step": q_bytes},
         "gemm_ms_per_step": gemm_ms,
         "launches": launches,
+        "qema_weight_quant": qema,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(layers, args.cpu_sample_tokens)
