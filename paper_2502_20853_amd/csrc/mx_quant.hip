@@ -438,12 +438,6 @@ hipError_t launch_quantize_tile(const QuantTileParams& p, hipStream_t st)
     const int64_t tiles = (p.rows / 32) * ((p.cols + 63) / 64);
     if (tiles >= 8192) { a.tiles_per_wave = 2; a.waves_c = 1; }
     else               { a.tiles_per_wave = 1; a.waves_c = 1; }
-    if (const char* ov = getenv("MX_TILE_SHAPE")) {      // "tiles_per_wave,waves_c": tuning aid
-        int t = 0, w = 0;
-        if (sscanf(ov, "%d,%d", &t, &w) == 2 && (t == 1 || t == 2 || t == 4) && (w == 1 || w == 2) && t * w <= 4) {
-            a.tiles_per_wave = t; a.waves_c = w;
-        }
-    }
     const int64_t cols_per_block = 64 * a.tiles_per_wave * a.waves_c, rows_per_block = 256 / a.waves_c;
     dim3 grid((unsigned)((p.cols + cols_per_block - 1) / cols_per_block),
               (unsigned)((p.rows + rows_per_block - 1) / rows_per_block));
