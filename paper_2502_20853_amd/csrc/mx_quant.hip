@@ -14,8 +14,6 @@
 #include "mx_device.hpp"
 #include "mx_launch.hpp"
 
-#include <cstdio>
-#include <cstdlib>
 
 using namespace mxd;
 
