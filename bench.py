@@ -193,6 +193,22 @@ def main():
             launches.append({"layer": name, "op": op, "shape": [m, n, k], "us": round(us, 1),
                              "TFLOP/s": round(fl / us / 1e6, 1), "shape_roofline_TFLOP/s": round(roof, 1)})
 
+    # The quantizers are bound by the vector ALUs: VALU lane-operations per element counted by rocprofv3
+    # (SQ_INSTS_VALU x 64 / elements, profiles/quantizer_valu.json) x elements per step / quantizer time,
+    # against the plain VALU rate 256 CUs x 4 SIMDs x 16 lanes/clk x 2.4 GHz.
+    quant_alu = None
+    vj = os.path.join(ROOT, "profiles", "quantizer_valu.json")
+    if os.path.exists(vj) and args.workload == "vit_base_b256" and args.tokens is None:
+        try:
+            per = json.load(open(vj))["valu_lane_ops_per_element"]
+            ops = sum(per["x_type"] * (N * D + C * D) + per["dy_type"] * N * C for (_, N, D, C) in layers)
+            peak = 256 * 4 * 16 * 2.4e9
+            quant_alu = {"bound": "alu", "achieved": ops / (quant_ms * 1e-3) / 1e12, "peak": peak / 1e12,
+                         "unit": "T lane-ops/s", "frac": ops / (quant_ms * 1e-3) / peak,
+                         "lane_ops_per_element": per}
+        except Exception:
+            quant_alu = None
+
     out = {
         "metric": "MXFP4 linear fwd+bwd TFLOP/s at ViT-B shapes",
         "value": total_flops / (dt / args.steps) / 1e12,
@@ -211,7 +227,7 @@ def main():
                      "traffic": traffic},
         "quantizers": {"bound": "hbm", "achieved": q_bytes / (quant_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
                        "unit": "GB/s", "frac": q_bytes / (quant_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
-                       "ms_per_step": quant_ms, "bytes_per_step": q_bytes},
+                       "ms_per_step": quant_ms, "bytes_per_step": q_bytes, "alu": quant_alu},
         "gemm_ms_per_step": gemm_ms,
         "launches": launches,
         "qema_weight_quant": qema,
