@@ -399,3 +399,50 @@ int orc_num_threads(void)
     return 1;
 #endif
 }
+
+/* ---- Q-Ramping: oscillation detection (Sec. 6.1) and amplification factor (Algorithm 2) ---- */
+
+void orc_oscillation_accumulate(const float* w, int64_t rows, int64_t cols, int64_t ld,
+                  const uint8_t* codes, const uint8_t* scales,
+                  float* w_prev, float* wq_prev, float* dist_w, float* dist_q, int init)
+{
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t c = 0; c < cols; ++c) {
+            const int64_t i = r * cols + c;
+            const uint8_t byte = codes[r * (cols / 2) + c / 2];
+            const int code = (c & 1) ? (byte >> 4) : (byte & 15);
+            const int s = (int)scales[r * (cols / 32) + c / 32] - 127;
+            /* the quantized weight the forward pass uses: P * 2^s, exact in FP32 */
+            const float wq = (float)ldexp(orc_e2m1_value(code), s);
+            const float wc = w[r * ld + c];
+            if (init) {
+                dist_w[i] = 0.0f;
+                dist_q[i] = 0.0f;
+            } else {
+                const float dw = fabsf(wc - w_prev[i]);
+                const float dq = fabsf(wq - wq_prev[i]);
+                dist_w[i] = dist_w[i] + dw;
+                dist_q[i] = dist_q[i] + dq;
+            }
+            w_prev[i] = wc;
+            wq_prev[i] = wq;
+        }
+}
+
+void orc_ramping_factor(const float* dist_w, const float* dist_q, int64_t count,
+                  float k1, int k2, int n_max, int32_t* factor)
+{
+    for (int64_t i = 0; i < count; ++i) {
+        float ratio;
+        if (dist_w[i] == 0.0f) ratio = dist_q[i] == 0.0f ? 0.0f : INFINITY;
+        else                   ratio = dist_q[i] / dist_w[i];
+        const float steps = floorf(ratio / k1);               /* floor(R_w / k1) */
+        /* k2 * steps + 1, capped: compare in floating point first so that +infinity is capped too */
+        int32_t n = n_max;
+        if (steps < (float)n_max) {
+            const int64_t v = (int64_t)k2 * (int64_t)steps + 1;
+            n = v < (int64_t)n_max ? (int32_t)v : n_max;
+        }
+        factor[i] = n;
+    }
+}

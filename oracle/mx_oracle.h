@@ -106,6 +106,24 @@ void orc_ema_weight_quant(const float* w, float* w_ema, float beta, int update_e
                   int64_t rows, int64_t cols, int64_t ld,
                   uint8_t* codes, uint8_t* scales, int scale_mode);
 
+/* Oscillation detection of Q-Ramping (Sec. 6.1 / "Identifying Oscillating Weights"): per weight
+ * element, the lengths of the trajectories of the master weight w and of its quantized value
+ * w_Q = P * 2^s over a window of steps,
+ *     dist_W = sum_t |w^t - w^(t-1)|,   dist_Q = sum_t |w_Q^t - w_Q^(t-1)|.
+ * One call is one step t.  init != 0 opens a window: the previous values are set to the current
+ * ones and both sums to 0.  All arithmetic is FP32, one rounding per operation (difference, then
+ * add), in the order written.  w_prev, wq_prev, dist_w, dist_q are dense [rows x cols]. */
+void orc_oscillation_accumulate(const float* w, int64_t rows, int64_t cols, int64_t ld,
+                  const uint8_t* codes, const uint8_t* scales,
+                  float* w_prev, float* wq_prev, float* dist_w, float* dist_q, int init);
+
+/* Amplification factor of Algorithm 2 (Q-Ramping): R_w = dist_Q / dist_W (FP32 division),
+ * N_w = min(k2 * floor(R_w / k1) + 1, n_max); LR_w = N_w * LR, BS_w = N_w * BS.
+ * dist_W = 0: R_w is taken as 0 when dist_Q = 0 too and as +infinity otherwise (the paper does not
+ * say).  k1 > 0, k2 >= 0, n_max >= 1. */
+void orc_ramping_factor(const float* dist_w, const float* dist_q, int64_t count,
+                  float k1, int k2, int n_max, int32_t* factor);
+
 /* X_i = P_i * 2^s (Sec. 3.1), exact in double. */
 void orc_dequantize(const uint8_t* codes, const uint8_t* scales,
                   int64_t rows, int64_t cols, double* out);

@@ -75,6 +75,10 @@ def lib():
                                            _i64p, _i64p, _i64, _f64p, _f64p]
         L.orc_num_threads.restype = _int
         L.orc_num_threads.argtypes = []
+        L.orc_oscillation_accumulate.restype = None
+        L.orc_oscillation_accumulate.argtypes = [_f32p, _i64, _i64, _i64, _u8p, _u8p, _f32p, _f32p, _f32p, _f32p, _int]
+        L.orc_ramping_factor.restype = None
+        L.orc_ramping_factor.argtypes = [_f32p, _f32p, _i64, ctypes.c_float, _int, _int, ctypes.POINTER(ctypes.c_int32)]
         _lib = L
     return _lib
 
@@ -220,3 +224,29 @@ def gemm_f64_sampled(a_codes, a_scales, b_codes, b_scales, ii, jj):
 
 def num_threads():
     return int(lib().orc_num_threads())
+
+
+def oscillation_accumulate(w, codes, scales, state, init=False):
+    """One step of Q-Ramping's oscillation detection.  state = dict of float32 arrays
+    w_prev, wq_prev, dist_w, dist_q (shape of w), updated in place."""
+    w = _f32(w)
+    codes, scales = _u8(codes), _u8(scales)
+    rows, cols = w.shape
+    for k in ("w_prev", "wq_prev", "dist_w", "dist_q"):
+        a = state[k]
+        assert a.dtype == np.float32 and a.shape == (rows, cols) and a.flags["C_CONTIGUOUS"]
+    lib().orc_oscillation_accumulate(_p(w, _f32p), rows, cols, w.strides[0] // 4, _p(codes, _u8p), _p(scales, _u8p),
+                                     _p(state["w_prev"], _f32p), _p(state["wq_prev"], _f32p),
+                                     _p(state["dist_w"], _f32p), _p(state["dist_q"], _f32p), int(bool(init)))
+    return state
+
+
+def ramping_factor(dist_w, dist_q, k1=16.0, k2=5, n_max=16):
+    """N_w of Algorithm 2 (Q-Ramping) per element, int32."""
+    dw = np.ascontiguousarray(dist_w, np.float32).ravel()
+    dq = np.ascontiguousarray(dist_q, np.float32).ravel()
+    out = np.zeros(dw.shape, np.int32)
+    lib().orc_ramping_factor(_p(dw, _f32p), _p(dq, _f32p), dw.size, float(k1), int(k2), int(n_max),
+                             out.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)))
+    return out.reshape(np.shape(dist_w))
+

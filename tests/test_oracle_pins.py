@@ -535,3 +535,84 @@ def test_layer_gradients_unbiased(orc):
     wT_c, wT_s, _, _ = orc.quantize_transposed(W, round_t=orc.ROUND_RTN, pre_quant=0, want_row=False)
     bias = np.abs(dyq @ orc.dequantize(wT_c, wT_s).T - dX_ref).mean()
     assert bias > 3 * np.abs(dX / trials - dX_ref).mean()
+
+
+# ------------------------------------------------- Q-Ramping: oscillation detection ----
+
+def _osc_state(shape):
+    return {k: np.zeros(shape, np.float32) for k in ("w_prev", "wq_prev", "dist_w", "dist_q")}
+
+
+def test_oscillation_distances_closed_forms(orc):
+    # Sec. 6.1: dist_W = sum |w^t - w^(t-1)|, dist_Q = sum |w_Q^t - w_Q^(t-1)|.
+    # Row 0 drifts by 2^-10 per step (every partial sum exact in FP32): dist_W = T * 2^-10.
+    # Row 1 holds an element whose latent weight w/S hops between -0.76 and -0.74 around the
+    # threshold -0.75 of Sec. 4.1: its quantized value flips between -1 and -0.5 times S on
+    # every step, so each step adds |q1 - q2| * S = 0.5 * S to dist_Q, and 0.02 * S to dist_W.
+    T, S = 12, 0.25
+    base = np.zeros((2, 32), np.float32)
+    base[0, :] = np.linspace(0.5, 1.5, 32, dtype=np.float32)
+    base[1, 0] = 6.0 * S                   # fixes the group's scale: M/S = 6 exactly
+    st = _osc_state(base.shape)
+    for t in range(T + 1):
+        w = base.copy()
+        w[0, :] += np.float32(t * 2.0 ** -10)
+        w[1, 1] = np.float32((-0.76 if t % 2 == 0 else -0.74) * S)
+        codes, scales = orc.quantize(w)
+        assert scales[1, 0] == 127 - 2     # S = 2^-2
+        orc.oscillation_accumulate(w, codes, scales, st, init=(t == 0))
+    assert np.all(st["dist_w"][0] == np.float32(T * 2.0 ** -10))
+    q = orc.dequantize(codes, scales)
+    assert q[1, 1] in (-1.0 * S, -0.5 * S)
+    assert st["dist_q"][1, 1] == np.float32(T * 0.5 * S)
+    assert abs(st["dist_w"][1, 1] - T * 0.02 * S) < 1e-6
+    assert st["dist_q"][1, 0] == 0.0 and st["dist_w"][1, 0] == 0.0          # an element that never moves
+    # the oscillating element has R_w = 25, the drifting ones R_w <= a few
+    R = st["dist_q"][1, 1] / st["dist_w"][1, 1]
+    assert abs(R - 25.0) < 1e-3
+    assert np.all(orc.ramping_factor(st["dist_w"], st["dist_q"], 16.0, 5, 16)[1, 1] == 6)
+
+
+def test_oscillation_window_restart_and_independent_formulation(orc):
+    # the same sums with numpy on dequantized weights (FP32 differences, FP32 running sums)
+    import mx_workloads as wl
+    st = _osc_state((96, 64))
+    prev_w = prev_q = None
+    dw = np.zeros((96, 64), np.float32)
+    dq = np.zeros((96, 64), np.float32)
+    for t, W in enumerate(wl.weight_walk(96, 64, seed=3, steps=6, sigma=2e-3)):
+        codes, scales = orc.quantize(W)
+        q = orc.dequantize(codes, scales).astype(np.float32)
+        restart = t in (0, 4)              # a new detection window at step 4
+        orc.oscillation_accumulate(W, codes, scales, st, init=restart)
+        if restart:
+            dw[:] = 0
+            dq[:] = 0
+        else:
+            dw = (dw + np.abs(W - prev_w)).astype(np.float32)
+            dq = (dq + np.abs(q - prev_q)).astype(np.float32)
+        prev_w, prev_q = W.copy(), q.copy()
+        assert np.array_equal(st["dist_w"], dw) and np.array_equal(st["dist_q"], dq)
+        assert np.array_equal(st["w_prev"], W) and np.array_equal(st["wq_prev"], q)
+    assert dq.max() > 0 and dw.min() > 0
+
+
+def test_ramping_factor_formula(orc):
+    # Algorithm 2 with the paper's defaults k1 = 16, k2 = 5
+    g = PAPER["q_ramping"]
+    for ex in g["factor_examples"]:
+        got = orc.ramping_factor(np.array([[1.0]], np.float32), np.array([[ex["R"]]], np.float32), g["k1"], g["k2"], 64)
+        assert got[0, 0] == ex["N"], ex
+    # cap, and the degenerate trajectories
+    assert orc.ramping_factor(np.array([[1.0]], np.float32), np.array([[1e6]], np.float32), 16, 5, 16)[0, 0] == 16
+    assert orc.ramping_factor(np.array([[0.0]], np.float32), np.array([[0.0]], np.float32), 16, 5, 16)[0, 0] == 1
+    assert orc.ramping_factor(np.array([[0.0]], np.float32), np.array([[0.5]], np.float32), 16, 5, 16)[0, 0] == 16
+    # brute force over a grid of ratios with exact rational arithmetic
+    rng = np.random.default_rng(0)
+    dw = rng.integers(1, 1000, 500).astype(np.float32)
+    dq = rng.integers(0, 100000, 500).astype(np.float32)
+    got = orc.ramping_factor(dw.reshape(1, -1), dq.reshape(1, -1), 16, 5, 40).ravel()
+    for a, b, n in zip(dw, dq, got):
+        r = np.float32(b) / np.float32(a)                    # the FP32 quotient the definition uses
+        want = min(5 * math.floor(Fraction(float(r)) / 16) + 1, 40)
+        assert n == want
