@@ -162,6 +162,31 @@ def main():
         qema.append({"layer": name, "shape": [C, D], "us": round(us, 1),
                      "GB/s": round(C * D * (4 + 4 + 4 + 0.5 + 1.0 / 32) / us / 1e3, 1)})
 
+    # Q-Ramping's oscillation detection (Sec. 6.1) and amplification factor (Algorithm 2), also
+    # outside the timed region: one accumulation step and one factor pass per weight of the block
+    osc = []
+    for (name, N, D, C), (X, W, dY) in zip(layers, inputs):
+        w32 = W.float()
+        codes, scales = mx.binding.mx_quantize(W)
+        st = mx.binding.OscillationState(C, D)
+        mx.binding.mx_oscillation_accumulate(w32, codes, scales, st, init=True)
+        fac = mx.binding.mx_ramping_factor(st.dist_w, st.dist_q)
+        for _ in range(3):
+            mx.binding.mx_oscillation_accumulate(w32, codes, scales, st, init=False)
+        e0, e1, e2 = ev(), ev(), ev()
+        e0.record()
+        for _ in range(20):
+            mx.binding.mx_oscillation_accumulate(w32, codes, scales, st, init=False)
+        e1.record()
+        for _ in range(20):
+            mx.binding.mx_ramping_factor(st.dist_w, st.dist_q, out=fac)
+        e2.record()
+        torch.cuda.synchronize()
+        us_a, us_f = e0.elapsed_time(e1) / 20 * 1e3, e1.elapsed_time(e2) / 20 * 1e3
+        osc.append({"layer": name, "shape": [C, D], "accumulate_us": round(us_a, 1),
+                    "accumulate_GB/s": round(C * D * (4 + 8 + 3 * (0.5 + 1.0 / 32) + 16) / us_a / 1e3, 1),
+                    "factor_us": round(us_f, 1), "factor_GB/s": round(C * D * 12 / us_f / 1e3, 1)})
+
     gemm_ms = sum(a.elapsed_time(b) for a, b in gemm_events) / args.steps      # per step, all 12 products
     quant_ms = sum(a.elapsed_time(b) for a, b in quant_events) / args.steps
     n_gemm = 3 * len(layers)
@@ -231,6 +256,7 @@ def main():
         "gemm_ms_per_step": gemm_ms,
         "launches": launches,
         "qema_weight_quant": qema,
+        "oscillation_detection": osc,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(layers, args.cpu_sample_tokens)

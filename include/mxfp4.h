@@ -148,6 +148,37 @@ int mx_ema_weight_quant(const void* w, int dtype, float* w_ema, float beta, int 
                   int64_t rows, int64_t cols, int64_t ld,
                   uint8_t* codes, uint8_t* scales, int scale_mode, void* stream);
 
+/* ---- next step beyond the layer: Q-Ramping's oscillation detection ---- */
+
+/*
+ * One step of the trajectory lengths of Sec. 6.1 ("Identifying Oscillating Weights"), per weight
+ * element of w[rows x cols]:
+ *     dist_W += |w - w_prev|,     dist_Q += |w_Q - w_Q,prev|,     w_Q = P * 2^s,
+ * FP32 with one rounding per operation, then w_prev <- w and the previous quantized weight <- the
+ * current one.  codes/scales are this step's 1x32 quantization of w (mx_quantize or
+ * mx_ema_weight_quant).
+ *   w                     device, F32 or BF16, row stride ld (alignment as mx_quantize)
+ *   w_prev, dist_w, dist_q   device in/out, FP32, dense [rows x cols], 16-byte aligned
+ *   codes_prev, scales_prev  device in/out, packed like codes/scales: the previous step's w_Q
+ *   init   1 opens a detection window: the sums are zeroed and nothing is added (the previous
+ *          values are not read); 0 accumulates one step.
+ */
+int mx_oscillation_accumulate(const void* w, int dtype, int64_t rows, int64_t cols, int64_t ld,
+                  const uint8_t* codes, const uint8_t* scales,
+                  float* w_prev, uint8_t* codes_prev, uint8_t* scales_prev,
+                  float* dist_w, float* dist_q, int init, void* stream);
+
+/*
+ * Amplification factor of Algorithm 2 (Q-Ramping) per element: with the oscillation ratio
+ * R_w = dist_Q / dist_W (Sec. 6.1),  N_w = min(k2 * floor(R_w / k1) + 1, n_max); the per-element
+ * learning rate and batch size are N_w times the global ones.  The paper's defaults are k1 = 16,
+ * k2 = 5.  dist_W = 0 (not covered by the paper): N_w = 1 if dist_Q = 0 too, else n_max.
+ *   dist_w, dist_q   device, FP32, count elements;  factor  device out, int32, count elements
+ *   k1 > 0, k2 >= 0, n_max >= 1, else MX_ERR_MODE.
+ */
+int mx_ramping_factor(const float* dist_w, const float* dist_q, int64_t count,
+                  float k1, int k2, int n_max, int32_t* factor, void* stream);
+
 /* ---- helpers (not part of the path) ---- */
 
 /* Bytes of workspace the product `which` (MX_GEMM_*) needs for these sizes. */

@@ -26,6 +26,7 @@ GEMM_FWD, GEMM_BWD_DX, GEMM_BWD_DW = 0, 1, 2
 
 EXPORTS = ["mx_quantize", "mx_quantize_transposed", "mx_linear_fwd", "mx_linear_bwd_dx",
            "mx_linear_bwd_dw", "mx_ema_weight_quant", "mx_linear_workspace_bytes",
+           "mx_oscillation_accumulate", "mx_ramping_factor",
            "mx_dequantize", "mx_calibration_copy", "mx_last_hip_error", "mx_version"]
 
 
@@ -65,6 +66,10 @@ def lib():
     L.mx_ema_weight_quant.argtypes = [vp, ci, vp, f32, ci, i64, i64, i64, vp, vp, ci, vp]
     L.mx_linear_workspace_bytes.restype = sz
     L.mx_linear_workspace_bytes.argtypes = [ci, i64, i64, i64]
+    L.mx_oscillation_accumulate.restype = ci
+    L.mx_oscillation_accumulate.argtypes = [vp, ci, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp, ci, vp]
+    L.mx_ramping_factor.restype = ci
+    L.mx_ramping_factor.argtypes = [vp, vp, i64, f32, ci, ci, vp, vp]
     L.mx_dequantize.restype = ci
     L.mx_dequantize.argtypes = [vp, vp, i64, i64, vp, vp]
     L.mx_calibration_copy.restype = ci
@@ -204,6 +209,42 @@ def mx_ema_weight_quant(w, w_ema, beta=0.998, update_ema=1, scale_mode=SCALE_TRU
                                    _ptr(codes), _ptr(scales), scale_mode, _stream(stream))
     _check("mx_ema_weight_quant", rc)
     return codes, scales
+
+
+class OscillationState:
+    """Device buffers of one weight's detection window (Sec. 6.1)."""
+
+    def __init__(self, rows, cols, device="cuda"):
+        f = lambda: torch.empty((rows, cols), dtype=torch.float32, device=device)
+        self.w_prev, self.dist_w, self.dist_q = f(), f(), f()
+        self.codes_prev = _u8((rows, cols // 2), device)
+        self.scales_prev = _u8((rows, cols // 32), device)
+        self.started = False
+
+
+def mx_oscillation_accumulate(w, codes, scales, state, init=None, stream=None):
+    """One step of dist_W / dist_Q; init defaults to True on the state's first use."""
+    rows, cols, ld = _matrix(w)
+    if init is None:
+        init = not state.started
+    rc = lib().mx_oscillation_accumulate(_ptr(w), _src_dtype(w), rows, cols, ld, _ptr(codes), _ptr(scales),
+                                         _ptr(state.w_prev), _ptr(state.codes_prev), _ptr(state.scales_prev),
+                                         _ptr(state.dist_w), _ptr(state.dist_q), int(bool(init)), _stream(stream))
+    _check("mx_oscillation_accumulate", rc)
+    state.started = True
+    return state
+
+
+def mx_ramping_factor(dist_w, dist_q, k1=16.0, k2=5, n_max=16, out=None, stream=None):
+    """N_w of Algorithm 2 per element (int32, shape of dist_w)."""
+    if dist_w.dtype != torch.float32 or dist_q.dtype != torch.float32 or not dist_w.is_contiguous() or not dist_q.is_contiguous():
+        raise ValueError("dist_w and dist_q must be contiguous float32 tensors")
+    if out is None:
+        out = torch.empty(dist_w.shape, dtype=torch.int32, device=dist_w.device)
+    rc = lib().mx_ramping_factor(_ptr(dist_w), _ptr(dist_q), dist_w.numel(), float(k1), int(k2), int(n_max),
+                                 _ptr(out), _stream(stream))
+    _check("mx_ramping_factor", rc)
+    return out
 
 
 def mx_dequantize(codes, scales, stream=None):

@@ -182,6 +182,32 @@ size_t mx_linear_workspace_bytes(int which, int64_t N, int64_t C, int64_t D)
     return split > 1 ? (size_t)split * (size_t)m * (size_t)n * sizeof(float) : 0;
 }
 
+int mx_oscillation_accumulate(const void* w, int dtype, int64_t rows, int64_t cols, int64_t ld,
+                  const uint8_t* codes, const uint8_t* scales,
+                  float* w_prev, uint8_t* codes_prev, uint8_t* scales_prev,
+                  float* dist_w, float* dist_q, int init, void* stream)
+{
+    if (!w_prev || !codes_prev || !scales_prev || !dist_w || !dist_q) return MX_ERR_NULL;
+    int rc = check_rows_call(w, dtype, rows, cols, ld, codes, scales, MX_SCALE_TRUNCFREE);
+    if (rc != MX_OK) return rc;
+    if (init != 0 && init != 1) return MX_ERR_MODE;
+    if (!aligned(w_prev, 16) || !aligned(dist_w, 16) || !aligned(dist_q, 16) || !aligned(codes_prev, 4)) return MX_ERR_ALIGN;
+    mxl::OscillationParams p{};
+    p.w = w; p.bf16 = dtype == MX_DTYPE_BF16; p.rows = rows; p.cols = cols; p.ld = ld;
+    p.codes = codes; p.scales = scales; p.w_prev = w_prev; p.codes_prev = codes_prev; p.scales_prev = scales_prev;
+    p.dist_w = dist_w; p.dist_q = dist_q; p.init = init;
+    return hip_status(mxl::launch_oscillation(p, static_cast<hipStream_t>(stream)));
+}
+
+int mx_ramping_factor(const float* dist_w, const float* dist_q, int64_t count,
+                  float k1, int k2, int n_max, int32_t* factor, void* stream)
+{
+    if (!dist_w || !dist_q || !factor) return MX_ERR_NULL;
+    if (count <= 0 || count > ((int64_t)1 << 40)) return MX_ERR_SHAPE;
+    if (!(k1 > 0.0f) || k2 < 0 || n_max < 1) return MX_ERR_MODE;
+    return hip_status(mxl::launch_ramping_factor(dist_w, dist_q, count, k1, k2, n_max, factor, static_cast<hipStream_t>(stream)));
+}
+
 int mx_dequantize(const uint8_t* codes, const uint8_t* scales, int64_t rows, int64_t cols,
                   float* out, void* stream)
 {

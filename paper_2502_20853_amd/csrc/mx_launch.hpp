@@ -60,6 +60,23 @@ hipError_t launch_quantize_tile(const QuantTileParams& p, hipStream_t st);
 hipError_t launch_dequantize(const uint8_t* codes, const uint8_t* scales, int64_t rows, int64_t cols,
                              float* out, hipStream_t st);
 
+struct OscillationParams {
+    const void* w;
+    bool bf16;
+    int64_t rows, cols, ld;
+    const uint8_t* codes;
+    const uint8_t* scales;
+    float* w_prev;
+    uint8_t* codes_prev;
+    uint8_t* scales_prev;
+    float* dist_w;
+    float* dist_q;
+    int init;
+};
+hipError_t launch_oscillation(const OscillationParams& p, hipStream_t st);
+hipError_t launch_ramping_factor(const float* dist_w, const float* dist_q, int64_t count, float k1, int k2,
+                                 int n_max, int32_t* factor, hipStream_t st);
+
 hipError_t launch_calibration_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
 
 // Number of K-splits the product will use for these sizes (1 = none).

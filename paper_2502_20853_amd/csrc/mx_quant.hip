@@ -342,6 +342,93 @@ __global__ __launch_bounds__(TILE_THREADS, 4) void quantize_tile_kernel(TileArgs
     }
 }
 
+// ---------------------------------------------------------------------------
+// Q-Ramping's oscillation detection (Sec. 6.1): one step of
+//     dist_W += |w - w_prev|,   dist_Q += |w_Q - w_Q,prev|,   w_Q = P * 2^s,
+// per weight element, FP32, one rounding per operation.  The previous quantized weight is kept
+// packed (codes_prev / scales_prev), not as FP32: 0.53 instead of 4 bytes per element of state.
+// One lane owns 8 consecutive elements, as in the quantizers.
+// ---------------------------------------------------------------------------
+struct OscArgs {
+    const void* w;
+    const uint8_t* codes;
+    const uint8_t* scales;
+    float* w_prev;
+    uint8_t* codes_prev;
+    uint8_t* scales_prev;
+    float* dist_w;
+    float* dist_q;
+    int64_t ld;
+    uint32_t cpr;          // 8-element chunks per row
+    uint32_t total;        // rows * cpr
+    int init;
+};
+
+template <typename SrcT>
+__global__ __launch_bounds__(ROWS_THREADS) void oscillation_kernel(OscArgs a)
+{
+    const uint32_t q = blockIdx.x * ROWS_THREADS + threadIdx.x;
+    if (q >= a.total) return;
+    const uint32_t r = q / a.cpr, ch = q - r * a.cpr;
+    const F8 w = load8(static_cast<const SrcT*>(a.w) + (int64_t)r * a.ld + (int64_t)ch * 8);
+    const size_t dense = (size_t)q * 8;                   // state arrays are dense [rows][cols]
+    const uint32_t pk = reinterpret_cast<const uint32_t*>(a.codes)[q];
+    const uint32_t byte = a.scales[(size_t)q >> 2];       // cols/32 groups per row = cpr/4
+    float4* wp = reinterpret_cast<float4*>(a.w_prev + dense);
+    if (!a.init) {
+        const uint32_t pk0 = reinterpret_cast<const uint32_t*>(a.codes_prev)[q];
+        const uint32_t byte0 = a.scales_prev[(size_t)q >> 2];
+        const float4 p0 = wp[0], p1 = wp[1];
+        const float prev[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+        float4* dwp = reinterpret_cast<float4*>(a.dist_w + dense);
+        float4* dqp = reinterpret_cast<float4*>(a.dist_q + dense);
+        const float4 a0 = dwp[0], a1 = dwp[1], b0 = dqp[0], b1 = dqp[1];
+        float dw[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+        float dq[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            const float wq = dequant((pk >> (4 * t)) & 15u, byte);
+            const float wq0 = dequant((pk0 >> (4 * t)) & 15u, byte0);
+            dw[t] = __fadd_rn(dw[t], __builtin_fabsf(__fsub_rn(w.v[t], prev[t])));
+            dq[t] = __fadd_rn(dq[t], __builtin_fabsf(__fsub_rn(wq, wq0)));
+        }
+        dwp[0] = make_float4(dw[0], dw[1], dw[2], dw[3]);
+        dwp[1] = make_float4(dw[4], dw[5], dw[6], dw[7]);
+        dqp[0] = make_float4(dq[0], dq[1], dq[2], dq[3]);
+        dqp[1] = make_float4(dq[4], dq[5], dq[6], dq[7]);
+    } else {
+        const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
+        reinterpret_cast<float4*>(a.dist_w + dense)[0] = z;
+        reinterpret_cast<float4*>(a.dist_w + dense)[1] = z;
+        reinterpret_cast<float4*>(a.dist_q + dense)[0] = z;
+        reinterpret_cast<float4*>(a.dist_q + dense)[1] = z;
+    }
+    wp[0] = make_float4(w.v[0], w.v[1], w.v[2], w.v[3]);
+    wp[1] = make_float4(w.v[4], w.v[5], w.v[6], w.v[7]);
+    reinterpret_cast<uint32_t*>(a.codes_prev)[q] = pk;
+    if ((ch & 3) == 0) a.scales_prev[(size_t)q >> 2] = (uint8_t)byte;
+}
+
+// Amplification factor of Algorithm 2 (Q-Ramping): N_w = min(k2 * floor(R_w / k1) + 1, n_max),
+// R_w = dist_Q / dist_W with IEEE FP32 divisions; dist_W = 0 gives R_w = 0 if dist_Q = 0, else +inf.
+__global__ void ramping_factor_kernel(const float* dist_w, const float* dist_q, int64_t count,
+                                      float k1, int k2, int n_max, int32_t* factor)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= count) return;
+    const float dw = dist_w[i], dq = dist_q[i];
+    float ratio;
+    if (dw == 0.0f) ratio = dq == 0.0f ? 0.0f : __builtin_inff();
+    else            ratio = __fdiv_rn(dq, dw);
+    const float steps = floorf(__fdiv_rn(ratio, k1));
+    int32_t n = n_max;
+    if (steps < (float)n_max) {
+        const int64_t v = (int64_t)k2 * (int64_t)steps + 1;
+        n = v < (int64_t)n_max ? (int32_t)v : n_max;
+    }
+    factor[i] = n;
+}
+
 __global__ void dequantize_kernel(const uint8_t* codes, const uint8_t* scales, int64_t total_bytes,
                                   int64_t cols, float* out)
 {
@@ -459,6 +546,26 @@ hipError_t launch_calibration_copy(void* dst, const void* src, size_t bytes, hip
     if (blocks > 65536) blocks = 65536;
     hipLaunchKernelGGL(calibration_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
                        static_cast<const uint4*>(src), static_cast<uint4*>(dst), n);
+    return hipGetLastError();
+}
+
+hipError_t launch_oscillation(const OscillationParams& p, hipStream_t st)
+{
+    OscArgs a{};
+    a.w = p.w; a.codes = p.codes; a.scales = p.scales; a.w_prev = p.w_prev;
+    a.codes_prev = p.codes_prev; a.scales_prev = p.scales_prev; a.dist_w = p.dist_w; a.dist_q = p.dist_q;
+    a.ld = p.ld; a.cpr = (uint32_t)(p.cols / 8); a.total = (uint32_t)(p.rows * (p.cols / 8)); a.init = p.init;
+    dim3 grid((a.total + ROWS_THREADS - 1) / ROWS_THREADS), block(ROWS_THREADS);
+    if (p.bf16) hipLaunchKernelGGL(oscillation_kernel<uint16_t>, grid, block, 0, st, a);
+    else        hipLaunchKernelGGL(oscillation_kernel<float>, grid, block, 0, st, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_ramping_factor(const float* dist_w, const float* dist_q, int64_t count, float k1, int k2,
+                                 int n_max, int32_t* factor, hipStream_t st)
+{
+    dim3 grid((unsigned)((count + 255) / 256)), block(256);
+    hipLaunchKernelGGL(ramping_factor_kernel, grid, block, 0, st, dist_w, dist_q, count, k1, k2, n_max, factor);
     return hipGetLastError();
 }
 

@@ -128,3 +128,20 @@ def test_calibration_copy_rejects(L):
 def test_dequantize_rejects(L):
     assert L.mx_dequantize(P(0), P(FAKE), 4, 32, P(FAKE), P(0)) == -1
     assert L.mx_dequantize(P(FAKE), P(FAKE), 4, 33, P(FAKE), P(0)) == -2
+
+
+def test_oscillation_and_ramping_rejects(L):
+    def o(w=FAKE, dtype=0, rows=64, cols=64, ld=64, codes=FAKE, scales=FAKE, wp=FAKE, cp=FAKE, sp=FAKE,
+          dw=FAKE, dq=FAKE, init=0):
+        return L.mx_oscillation_accumulate(P(w), dtype, rows, cols, ld, P(codes), P(scales), P(wp), P(cp), P(sp),
+                                           P(dw), P(dq), init, P(0))
+    assert o(w=0) == -1 and o(wp=0) == -1 and o(cp=0) == -1 and o(dq=0) == -1
+    assert o(dtype=5) == -3 and o(cols=40) == -2 and o(ld=32) == -2
+    assert o(init=2) == -4
+    assert o(dw=FAKE + 4) == -5 and o(cp=FAKE + 2) == -5
+
+    def r(dw=FAKE, dq=FAKE, n=64, k1=16.0, k2=5, nmax=16, out=FAKE):
+        return L.mx_ramping_factor(P(dw), P(dq), n, k1, k2, nmax, P(out), P(0))
+    assert r(dw=0) == -1 and r(out=0) == -1
+    assert r(n=0) == -2
+    assert r(k1=0.0) == -4 and r(k1=float("nan")) == -4 and r(k2=-1) == -4 and r(nmax=0) == -4

@@ -487,3 +487,42 @@ def test_full_size_vit_base_qkv_layer(mx, orc):
     sampled(y, (xt[2], xt[3], wt[2], wt[3]), N, C, "Y", True)
     sampled(dx, (dy[2], dy[3], wt[0], wt[1]), N, D, "dX", True)
     sampled(dw, (dy[0], dy[1], xt[0], xt[1]), C, D, "dW", False)
+
+
+# ------------------------------------------------- Q-Ramping: oscillation detection ----
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_oscillation_accumulate_and_ramping_factor(mx, orc, dtype):
+    """dist_W / dist_Q (Sec. 6.1) over a weight walk with a window restart, then N_w of Algorithm 2:
+    every state array bit-exact against the oracle at every step."""
+    import mx_workloads as wl
+    C, D = 544, 320                                    # rows not a multiple of the launch width, 10 groups per row
+    state = mx.OscillationState(C, D)
+    ost = {k: np.zeros((C, D), np.float32) for k in ("w_prev", "wq_prev", "dist_w", "dist_q")}
+    for t, W in enumerate(wl.weight_walk(C, D, seed=9, steps=7, sigma=3e-3)):
+        if dtype == "bf16":
+            W = wl.round_to_bf16(W)
+        if t == 3:
+            W[5, :64] = 0.0                            # all-zero groups: w_Q = 0 with scale byte 98
+        codes, scales = orc.quantize(W)
+        restart = t in (0, 5)
+        orc.oscillation_accumulate(W, codes, scales, ost, init=restart)
+        gq = mx.mx_quantize(dev(W, dtype))
+        assert_same_bytes(gq[0], codes, "codes step %d" % t)
+        mx.mx_oscillation_accumulate(dev(W, dtype), gq[0], gq[1], state, init=restart)
+        assert np.array_equal(host(state.dist_w), ost["dist_w"]), t
+        assert np.array_equal(host(state.dist_q), ost["dist_q"]), t
+        assert np.array_equal(host(state.w_prev), ost["w_prev"]), t
+        assert_same_bytes(state.codes_prev, codes, "previous codes step %d" % t)
+        assert_same_bytes(state.scales_prev, scales, "previous scales step %d" % t)
+    assert ost["dist_q"].max() > 0
+    for k1, k2, nmax in ((16.0, 5, 16), (0.37, 3, 100), (1.0, 1, 7)):
+        want = orc.ramping_factor(ost["dist_w"], ost["dist_q"], k1, k2, nmax)
+        got = host(mx.mx_ramping_factor(state.dist_w, state.dist_q, k1, k2, nmax))
+        assert np.array_equal(got, want), (k1, k2, nmax)
+    # degenerate trajectories: elements that never moved, and quantized jumps without master movement
+    dw = np.array([[0.0, 0.0, 1e-30, 1.0]], np.float32)
+    dq = np.array([[0.0, 0.5, 1.0, 0.0]], np.float32)
+    want = orc.ramping_factor(dw, dq, 16.0, 5, 16)
+    got = host(mx.mx_ramping_factor(dev(dw), dev(dq), 16.0, 5, 16))
+    assert np.array_equal(got, want) and list(want[0]) == [1, 16, 16, 1]
