@@ -1,4 +1,5 @@
-// MXFP4 quantizer kernels for gfx950: streaming, HBM-bound, no matrix cores.
+// MXFP4 quantizer kernels for gfx950: streaming, no matrix cores (the fused
+// tile kernel is bound by the vector ALUs, the others by memory and launch).
 //
 //  quantize_rows_kernel   1x32 groups along the columns (Q1, Q2, Q3 of Eqs. 3-4)
 //  quantize_tile_kernel   32x1 groups stored transposed (Q4, Q5, Q6 of Eqs. 4-5),
@@ -6,6 +7,8 @@
 //                         source (one read of the tensor) and with double
 //                         quantization (Sec. 3.3)
 //  ema_quantize_kernel    Q-EMA (Eq. 8, Algorithm 1)
+//  oscillation_kernel     trajectory lengths dist_W, dist_Q of Q-Ramping (Sec. 6.1)
+//  ramping_factor_kernel  amplification factor N_w of Algorithm 2
 //  dequantize_kernel      test aid
 //
 // Work split: one lane owns 8 consecutive elements of a row (one 16-byte bf16
