@@ -446,3 +446,69 @@ void orc_ramping_factor(const float* dist_w, const float* dist_q, int64_t count,
         factor[i] = n;
     }
 }
+
+/* ----------------------------------------------------------- diagnostics -- */
+
+/* distance from y to the nearest of the 14 rounding thresholds (midpoints of neighbouring signed
+ * E2M1 values) */
+static double nearest_threshold_distance(double y)
+{
+    double best = INFINITY;
+    for (int t = 0; t < 7; ++t) {
+        const double thr = 0.5 * (E2M1_MAG[t] + E2M1_MAG[t + 1]);
+        const double dp = fabs(y - thr), dn = fabs(y + thr);
+        if (dp < best) best = dp;
+        if (dn < best) best = dn;
+    }
+    return best;
+}
+
+/* MaxDist of Sec. 4.2 for the E2M1 value with magnitude index t (the same for both signs): the
+ * cell of the value reaches from the midpoint towards the neighbour below to the midpoint towards
+ * the neighbour above; the cell of 0 is [-0.25, 0.25]; the cell of 6 ends at 6. */
+static double cell_max_distance(int t)
+{
+    if (t == 7) return E2M1_MAG[7] - 0.5 * (E2M1_MAG[6] + E2M1_MAG[7]);
+    const double hi = 0.5 * (E2M1_MAG[t] + E2M1_MAG[t + 1]);
+    const double lo = (t == 0) ? -hi : 0.5 * (E2M1_MAG[t - 1] + E2M1_MAG[t]);
+    return 0.5 * (hi - lo);
+}
+
+void orc_quant_confidence(const float* w, int64_t rows, int64_t cols, int64_t ld, int scale_mode,
+                  float* conf, uint64_t* hist, int bins)
+{
+    int64_t groups = cols / 32;
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t g = 0; g < groups; ++g) {
+            const float* x = w + r * ld + 32 * g;
+            const int s = orc_shared_exponent(group_amax(x, 1), scale_mode);
+            for (int i = 0; i < 32; ++i) {
+                const double y = scale_to_group(x[i], s, scale_mode);
+                const int code = round_rtn_d(y);
+                const float num = (float)nearest_threshold_distance(y);   /* exact */
+                const float den = (float)cell_max_distance(code & 7);     /* exact */
+                const float c = num / den;
+                if (conf) conf[r * cols + 32 * g + i] = c;
+                if (hist) {
+                    int b = (int)floorf(c * (float)bins);
+                    if (b > bins - 1) b = bins - 1;
+                    hist[b] += 1;
+                }
+            }
+        }
+}
+
+double orc_rate_of_change_term(const float* x, int64_t rows, int64_t cols, int64_t ld, float* x_prev)
+{
+    double diff2 = 0.0, prev2 = 0.0;
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t c = 0; c < cols; ++c) {
+            const double cur = (double)x[r * ld + c];
+            const double old = (double)x_prev[r * cols + c];
+            diff2 += (cur - old) * (cur - old);
+            prev2 += old * old;
+            x_prev[r * cols + c] = x[r * ld + c];
+        }
+    if (prev2 == 0.0) return diff2 == 0.0 ? 0.0 : INFINITY;
+    return sqrt(diff2) / sqrt(prev2);
+}

@@ -124,6 +124,27 @@ void orc_oscillation_accumulate(const float* w, int64_t rows, int64_t cols, int6
 void orc_ramping_factor(const float* dist_w, const float* dist_q, int64_t count,
                   float k1, int k2, int n_max, int32_t* factor);
 
+/* Quantization confidence (Sec. 4.2): for a weight element w of a 1x32 group with scale S,
+ * on the latent value y = w / S,
+ *     QuantConf = min_i |y - thrd_i| / MaxDist(y_FP4),
+ * where the thresholds are the 14 midpoints between neighbouring signed E2M1 values, y_FP4 is the
+ * deterministic rounding of y, and MaxDist(v) is the largest distance to the nearest threshold a
+ * latent value rounded to v can have: half the width of v's cell for a cell between two thresholds,
+ * the whole width for the two outermost cells [5, 6] and [-6, -5].  (The ratio is the same in the
+ * unscaled domain: S multiplies numerator and denominator alike.)  Numerator and denominator are
+ * exact in FP32; the quotient is one FP32 division.  conf is dense [rows x cols].
+ * hist, if not NULL, holds `bins` counters and is ADDED to: element with confidence c counts in bin
+ * min(bins - 1, floor(c * bins)), the product taken in FP32. */
+void orc_quant_confidence(const float* w, int64_t rows, int64_t cols, int64_t ld, int scale_mode,
+                  float* conf, uint64_t* hist, int bins);
+
+/* One term of the rate of change of a tensor (Sec. 4.1):
+ *     r(X) = (1/T0) sum_{t=1..T0} ||X^t - X^(t-1)||_F / ||X^(t-1)||_F.
+ * Returns ||x - x_prev||_F / ||x_prev||_F in FP64 (differences of FP32 values are exact in FP64;
+ * the sums of squares run in FP64 in index order), then sets x_prev = x.  x_prev is dense
+ * [rows x cols].  A zero ||x_prev|| gives 0 if the difference is zero too, +infinity otherwise. */
+double orc_rate_of_change_term(const float* x, int64_t rows, int64_t cols, int64_t ld, float* x_prev);
+
 /* X_i = P_i * 2^s (Sec. 3.1), exact in double. */
 void orc_dequantize(const uint8_t* codes, const uint8_t* scales,
                   int64_t rows, int64_t cols, double* out);

@@ -77,6 +77,10 @@ def lib():
         L.orc_num_threads.argtypes = []
         L.orc_oscillation_accumulate.restype = None
         L.orc_oscillation_accumulate.argtypes = [_f32p, _i64, _i64, _i64, _u8p, _u8p, _f32p, _f32p, _f32p, _f32p, _int]
+        L.orc_quant_confidence.restype = None
+        L.orc_quant_confidence.argtypes = [_f32p, _i64, _i64, _i64, _int, _f32p, ctypes.POINTER(ctypes.c_uint64), _int]
+        L.orc_rate_of_change_term.restype = ctypes.c_double
+        L.orc_rate_of_change_term.argtypes = [_f32p, _i64, _i64, _i64, _f32p]
         L.orc_ramping_factor.restype = None
         L.orc_ramping_factor.argtypes = [_f32p, _f32p, _i64, ctypes.c_float, _int, _int, ctypes.POINTER(ctypes.c_int32)]
         _lib = L
@@ -250,3 +254,23 @@ def ramping_factor(dist_w, dist_q, k1=16.0, k2=5, n_max=16):
                              out.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)))
     return out.reshape(np.shape(dist_w))
 
+
+
+def quant_confidence(w, scale_mode=SCALE_TRUNCFREE, bins=0):
+    """QuantConf of Sec. 4.2 per element (float32, shape of w); with bins > 0 also the histogram
+    (uint64[bins]) of the confidences."""
+    w = _f32(w)
+    rows, cols = w.shape
+    conf = np.zeros((rows, cols), np.float32)
+    hist = np.zeros(bins, np.uint64) if bins > 0 else None
+    lib().orc_quant_confidence(_p(w, _f32p), rows, cols, w.strides[0] // 4, int(scale_mode), _p(conf, _f32p),
+                               hist.ctypes.data_as(ctypes.POINTER(ctypes.c_uint64)) if bins > 0 else None, int(bins))
+    return (conf, hist) if bins > 0 else conf
+
+
+def rate_of_change_term(x, x_prev):
+    """||x - x_prev||_F / ||x_prev||_F (Sec. 4.1), FP64; x_prev (float32, dense, shape of x) is then set to x."""
+    x = _f32(x)
+    rows, cols = x.shape
+    assert x_prev.dtype == np.float32 and x_prev.shape == (rows, cols) and x_prev.flags["C_CONTIGUOUS"]
+    return float(lib().orc_rate_of_change_term(_p(x, _f32p), rows, cols, x.strides[0] // 4, _p(x_prev, _f32p)))

@@ -616,3 +616,124 @@ def test_ramping_factor_formula(orc):
         r = np.float32(b) / np.float32(a)                    # the FP32 quotient the definition uses
         want = min(5 * math.floor(Fraction(float(r)) / 16) + 1, 40)
         assert n == want
+
+
+# ------------------------------------------------- oscillation diagnostics ----
+
+def _latent_group(latents, S=0.25):
+    """One 1x32 group whose scale is S (an element at 6*S pins it) holding the given latent values."""
+    assert len(latents) <= 31
+    w = np.zeros((1, 32), np.float32)
+    w[0, 0] = 6.0 * S
+    w[0, 1:1 + len(latents)] = np.asarray(latents, np.float64) * S
+    return w
+
+
+def test_quant_confidence_thresholds_and_cell_centres(orc):
+    # Sec. 4.2: 0 on a threshold (a midpoint of neighbouring FP4 values, e.g. the -0.75 of Sec. 4.1),
+    # 1 where the latent value is as far from every threshold as its FP4 value allows.
+    thr = [(a + b) / 2 for a, b in zip(SIGNED_GRID[:-1], SIGNED_GRID[1:])]
+    assert PAPER["threshold_example"]["thrd"] in thr and len(thr) == 14
+    conf = orc.quant_confidence(_latent_group(thr))
+    assert np.all(conf[0, 1:15] == 0.0)
+    # the furthest points: midway between the two thresholds of a cell; +-6 for the outermost cells
+    far = [0.0, 0.5, -0.5, 1.0, -1.0, 1.5, -1.5, 2.125, -2.125, 3.0, -3.0, 4.25, -4.25, 6.0, -6.0]
+    conf = orc.quant_confidence(_latent_group(far))
+    assert np.all(conf[0, 1:16] == 1.0) and conf[0, 0] == 1.0
+    # values in between, by hand: cell of 2 is [1.75, 2.5], of 4 is [3.5, 5], of 6 is [5, 6], of 0 is [-.25, .25]
+    by_hand = {2.0: 0.25 / 0.375, 4.0: 0.5 / 0.75, -4.0: 0.5 / 0.75, 5.5: 0.5, -5.25: 0.25, 0.125: 0.5,
+               0.375: 0.5, 2.25: 0.25 / 0.375, 3.25: 0.5, 1.125: 0.5}
+    conf = orc.quant_confidence(_latent_group(list(by_hand)))
+    for i, (y, c) in enumerate(by_hand.items()):
+        assert conf[0, 1 + i] == np.float32(c), (y, conf[0, 1 + i], c)
+
+
+def test_quant_confidence_brute_force_definition(orc):
+    # the definition taken literally, in rationals: MaxDist(v) by scanning every latent value on a
+    # 1/64 grid of [-6, 6] (thresholds and cell centres are multiples of 1/8), min over all thresholds
+    thr = [Fraction(a + b) / 2 for a, b in zip(SIGNED_GRID[:-1], SIGNED_GRID[1:])]
+    grid = [Fraction(v) for v in SIGNED_GRID]
+
+    def nearest(y):                      # round_D: ties toward the larger value
+        best = min(abs(y - g) for g in grid)
+        return max(g for g in grid if abs(y - g) == best)
+
+    maxdist = {}
+    for k in range(-6 * 64, 6 * 64 + 1):
+        y = Fraction(k, 64)
+        d = min(abs(y - t) for t in thr)
+        v = nearest(y)
+        maxdist[v] = max(maxdist.get(v, Fraction(0)), d)
+    rng = np.random.default_rng(11)
+    w = (rng.standard_normal((6, 64)) * rng.choice([1e-3, 0.02, 1.0, 30.0], (6, 1))).astype(np.float32)
+    for mode in (orc.SCALE_TRUNCFREE, orc.SCALE_FLOOR):
+        conf = orc.quant_confidence(w, mode)
+        codes, scales = orc.quantize(w, orc.ROUND_RTN, mode)
+        assert conf.min() >= 0.0 and conf.max() <= 1.0
+        for r in range(w.shape[0]):
+            for c in range(w.shape[1]):
+                S = Fraction(2) ** (int(scales[r, c // 32]) - 127)
+                y = Fraction(float(w[r, c])) / S
+                y = max(min(y, Fraction(6)), Fraction(-6))          # Eq. 2's scale can overflow: clipped
+                q = min(abs(y - t) for t in thr) / maxdist[nearest(y)]
+                got = Fraction(float(conf[r, c]))
+                half_ulp = Fraction(float(np.spacing(np.float32(max(float(q), 2.0 ** -126))))) / 2
+                assert abs(got - q) <= half_ulp, (r, c, float(y), float(got), float(q))
+
+
+def test_quant_confidence_invariances_and_histogram(orc):
+    import mx_workloads as wl
+    w = wl.weights(64, 96, seed=21)
+    conf, hist = orc.quant_confidence(w, bins=20)
+    assert np.array_equal(conf, orc.quant_confidence(w))
+    # a power-of-two rescale moves weight and thresholds alike; so does a sign flip
+    assert np.array_equal(conf, orc.quant_confidence(w * np.float32(2.0 ** -7)))
+    assert np.array_equal(conf, orc.quant_confidence(-w))
+    assert hist.sum() == w.size
+    ref = np.bincount(np.minimum(19, np.floor(conf * np.float32(20)).astype(np.int64)).ravel(), minlength=20)
+    assert np.array_equal(hist, ref.astype(np.uint64))
+    # an all-zero group has latent value 0 everywhere: confidence 1
+    z = np.zeros((1, 32), np.float32)
+    assert np.all(orc.quant_confidence(z) == 1.0)
+    # a strided source reads the same values
+    big = np.zeros((64, 128), np.float32)
+    big[:, :96] = w
+    assert np.array_equal(orc.quant_confidence(big[:, :96]), conf)
+
+
+def test_rate_of_change_closed_forms_and_numpy(orc):
+    # Sec. 4.1: one term ||X^t - X^(t-1)||_F / ||X^(t-1)||_F
+    rng = np.random.default_rng(5)
+    prev = (rng.integers(-512, 512, (48, 40)) / 64.0).astype(np.float32)
+    prev[0, 0] = 1.0
+    # X^t = 1.5 X^(t-1): every product exact, ratio exactly 0.5 up to the rounding of the sums
+    xp = prev.copy()
+    r = orc.rate_of_change_term((1.5 * prev).astype(np.float32), xp)
+    assert abs(r - 0.5) < 1e-14
+    assert np.array_equal(xp, (1.5 * prev).astype(np.float32))           # the previous tensor is replaced
+    # no change: 0
+    assert orc.rate_of_change_term(xp.copy(), xp) == 0.0
+    # one element moved by d: ||dX|| = |d|
+    x = prev.copy()
+    x[3, 7] += np.float32(0.25)
+    xp = prev.copy()
+    r = orc.rate_of_change_term(x, xp)
+    assert abs(r - 0.25 / np.linalg.norm(prev.astype(np.float64))) < 1e-15
+    # library norms on random data, strided source
+    a = rng.standard_normal((80, 96)).astype(np.float32)
+    b = (a + 1e-3 * rng.standard_normal((80, 96))).astype(np.float32)
+    big = np.zeros((80, 160), np.float32)
+    big[:, :96] = b
+    xp = a.copy()
+    r = orc.rate_of_change_term(big[:, :96], xp)
+    ref = np.linalg.norm(b.astype(np.float64) - a.astype(np.float64)) / np.linalg.norm(a.astype(np.float64))
+    assert abs(r - ref) <= 1e-13 * ref
+    assert np.array_equal(xp, b)
+    # a zero previous tensor: 0/0 reads 0, d/0 reads infinity
+    z = np.zeros((2, 32), np.float32)
+    assert orc.rate_of_change_term(z.copy(), z.copy()) == 0.0
+    assert orc.rate_of_change_term(np.ones((2, 32), np.float32), z.copy()) == math.inf
+    # the average over a window is r(X): a tensor that doubles every step has r = 1
+    xp = prev.copy()
+    terms = [orc.rate_of_change_term((prev * np.float32(2.0 ** (t + 1))), xp) for t in range(5)]
+    assert abs(sum(terms) / 5 - 1.0) < 1e-14
