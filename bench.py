@@ -187,6 +187,32 @@ def main():
                     "accumulate_GB/s": round(C * D * (4 + 8 + 3 * (0.5 + 1.0 / 32) + 16) / us_a / 1e3, 1),
                     "factor_us": round(us_f, 1), "factor_GB/s": round(C * D * 12 / us_f / 1e3, 1)})
 
+    # oscillation diagnostics of Sec. 4 (quantization confidence with its histogram; one term of
+    # the rate of change), outside the timed region, on each weight of the block
+    diag = []
+    for (name, N, D, C), (X, W, dY) in zip(layers, inputs):
+        hist = torch.zeros(100, dtype=torch.int64, device="cuda")
+        rs = mx.binding.RateOfChangeState(C, D)
+        mx.binding.mx_rate_of_change_step(W, rs)
+        for _ in range(3):
+            mx.binding.mx_quant_confidence(W, conf=False, hist=hist)
+            mx.binding.mx_rate_of_change_step(W, rs)
+        e0, e1, e2 = ev(), ev(), ev()
+        e0.record()
+        for _ in range(20):
+            mx.binding.mx_quant_confidence(W, conf=False, hist=hist)
+        e1.record()
+        for _ in range(20):
+            mx.binding.mx_rate_of_change_step(W, rs)
+        e2.record()
+        torch.cuda.synchronize()
+        us_c, us_r = e0.elapsed_time(e1) / 20 * 1e3, e1.elapsed_time(e2) / 20 * 1e3
+        eb = W.element_size()
+        diag.append({"layer": name, "shape": [C, D], "confidence_hist_us": round(us_c, 1),
+                     "confidence_hist_GB/s": round(C * D * eb / us_c / 1e3, 1),
+                     "rate_of_change_us": round(us_r, 1),
+                     "rate_of_change_GB/s": round(C * D * (eb + 8) / us_r / 1e3, 1)})
+
     gemm_ms = sum(a.elapsed_time(b) for a, b in gemm_events) / args.steps      # per step, all 12 products
     quant_ms = sum(a.elapsed_time(b) for a, b in quant_events) / args.steps
     n_gemm = 3 * len(layers)
@@ -257,6 +283,7 @@ def main():
         "launches": launches,
         "qema_weight_quant": qema,
         "oscillation_detection": osc,
+        "oscillation_diagnostics": diag,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(layers, args.cpu_sample_tokens)

@@ -179,6 +179,44 @@ int mx_oscillation_accumulate(const void* w, int dtype, int64_t rows, int64_t co
 int mx_ramping_factor(const float* dist_w, const float* dist_q, int64_t count,
                   float k1, int k2, int n_max, int32_t* factor, void* stream);
 
+/* ---- oscillation diagnostics (Sec. 4) ---- */
+
+/*
+ * Quantization confidence of Sec. 4.2 for every element of w[rows x cols], on the latent value
+ * y = w / S of its 1x32 group (S as mx_quantize computes it for scale_mode):
+ *     QuantConf = min_i |y - thrd_i| / MaxDist(y_FP4)   in [0, 1],
+ * thresholds = the midpoints of neighbouring E2M1 values; MaxDist = half the width of the rounding
+ * cell of y_FP4 (the whole width for the outermost cells [5, 6] and [-6, -5]).  0 on a threshold,
+ * 1 at the point of the cell furthest from its thresholds.
+ *   w      device, F32 or BF16, row stride ld (alignment as mx_quantize)
+ *   conf   device out, FP32, dense [rows x cols], 16-byte aligned; or NULL
+ *   hist   device in/out, `bins` 64-bit counters, ADDED to (clear them to open a histogram); or
+ *          NULL.  An element with confidence c counts in bin min(bins - 1, floor(c * bins)), the
+ *          product in FP32.  1 <= bins <= 1024, else MX_ERR_MODE.
+ * conf and hist may not both be NULL.
+ */
+int mx_quant_confidence(const void* w, int dtype, int64_t rows, int64_t cols, int64_t ld, int scale_mode,
+                  float* conf, uint64_t* hist, int bins, void* stream);
+
+/*
+ * One term of the rate of change of a tensor (Sec. 4.1),
+ *     r(X) = (1/T0) sum_{t=1..T0} ||X^t - X^(t-1)||_F / ||X^(t-1)||_F:
+ * with x = X^t and x_prev = X^(t-1), computes the term in FP64 (sums of squares in a fixed order:
+ * results repeat bit for bit), then x_prev <- x.
+ *   x        device, F32 or BF16, [rows x cols], row stride ld; cols % 8 == 0
+ *   x_prev   device in/out, FP32, dense [rows x cols], 16-byte aligned
+ *   init     1 opens a window: x_prev <- x, result <- {0, 0, 0}; 0 adds one term
+ *   workspace   device scratch of mx_rate_of_change_workspace_bytes() bytes (MX_ERR_WORKSPACE if
+ *            smaller), not kept between calls
+ *   result   device in/out, 3 doubles: [0] this call's term, [1] the sum of the terms since the
+ *            window opened, [2] their number; r(X) = result[1] / result[2].
+ * ||x_prev|| = 0 gives a term of 0 if x = x_prev, +infinity otherwise.
+ */
+size_t mx_rate_of_change_workspace_bytes(void);
+int mx_rate_of_change_step(const void* x, int dtype, int64_t rows, int64_t cols, int64_t ld,
+                  float* x_prev, int init, void* workspace, size_t workspace_bytes,
+                  double* result, void* stream);
+
 /* ---- helpers (not part of the path) ---- */
 
 /* Bytes of workspace the product `which` (MX_GEMM_*) needs for these sizes. */

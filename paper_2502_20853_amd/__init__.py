@@ -7,5 +7,6 @@ from .binding import (  # noqa: F401
     mx_dequantize, mx_ema_weight_quant, mx_linear_bwd_dw, mx_linear_bwd_dx, mx_linear_fwd,
     mx_linear_workspace_bytes, mx_quantize, mx_quantize_transposed, mx_version,
     OscillationState, mx_oscillation_accumulate, mx_ramping_factor,
+    RateOfChangeState, mx_quant_confidence, mx_rate_of_change_step,
 )
 from .layer import MxLinearStep  # noqa: F401

@@ -27,6 +27,7 @@ GEMM_FWD, GEMM_BWD_DX, GEMM_BWD_DW = 0, 1, 2
 EXPORTS = ["mx_quantize", "mx_quantize_transposed", "mx_linear_fwd", "mx_linear_bwd_dx",
            "mx_linear_bwd_dw", "mx_ema_weight_quant", "mx_linear_workspace_bytes",
            "mx_oscillation_accumulate", "mx_ramping_factor",
+           "mx_quant_confidence", "mx_rate_of_change_workspace_bytes", "mx_rate_of_change_step",
            "mx_dequantize", "mx_calibration_copy", "mx_last_hip_error", "mx_version"]
 
 
@@ -70,6 +71,12 @@ def lib():
     L.mx_oscillation_accumulate.argtypes = [vp, ci, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp, ci, vp]
     L.mx_ramping_factor.restype = ci
     L.mx_ramping_factor.argtypes = [vp, vp, i64, f32, ci, ci, vp, vp]
+    L.mx_quant_confidence.restype = ci
+    L.mx_quant_confidence.argtypes = [vp, ci, i64, i64, i64, ci, vp, vp, ci, vp]
+    L.mx_rate_of_change_workspace_bytes.restype = sz
+    L.mx_rate_of_change_workspace_bytes.argtypes = []
+    L.mx_rate_of_change_step.restype = ci
+    L.mx_rate_of_change_step.argtypes = [vp, ci, i64, i64, i64, vp, ci, vp, sz, vp, vp]
     L.mx_dequantize.restype = ci
     L.mx_dequantize.argtypes = [vp, vp, i64, i64, vp, vp]
     L.mx_calibration_copy.restype = ci
@@ -245,6 +252,56 @@ def mx_ramping_factor(dist_w, dist_q, k1=16.0, k2=5, n_max=16, out=None, stream=
                                  _ptr(out), _stream(stream))
     _check("mx_ramping_factor", rc)
     return out
+
+
+def mx_quant_confidence(w, scale_mode=SCALE_TRUNCFREE, conf=True, hist=None, stream=None):
+    """Quantization confidence of Sec. 4.2.  conf=True returns the per-element confidences
+    (float32, shape of w); hist (int64 tensor of `bins` counters) is added to if given.
+    Returns (conf or None, hist or None)."""
+    rows, cols = w.shape
+    out = torch.empty((rows, cols), dtype=torch.float32, device=w.device) if conf else None
+    bins = 0
+    if hist is not None:
+        if hist.dtype != torch.int64 or not hist.is_contiguous():
+            raise ValueError("hist must be a contiguous int64 tensor")
+        bins = hist.numel()
+    rc = lib().mx_quant_confidence(_ptr(w), _src_dtype(w), rows, cols, w.stride(0), int(scale_mode),
+                                   _ptr(out), _ptr(hist), bins, _stream(stream))
+    _check("mx_quant_confidence", rc)
+    return out, hist
+
+
+class RateOfChangeState:
+    """Device state of the rate of change of one tensor (Sec. 4.1): the previous tensor (FP32),
+    the reduction scratch and the three result doubles (term, sum of terms, number of terms)."""
+
+    def __init__(self, rows, cols, device="cuda"):
+        self.rows, self.cols = rows, cols
+        self.x_prev = torch.empty((rows, cols), dtype=torch.float32, device=device)
+        self.workspace = torch.empty(lib().mx_rate_of_change_workspace_bytes(), dtype=torch.uint8, device=device)
+        self.result = torch.zeros(3, dtype=torch.float64, device=device)
+        self.started = False
+
+    def rate(self):
+        """r(X) over the terms since the window opened (synchronizes)."""
+        _, total, count = self.result.tolist()
+        return total / count if count else 0.0
+
+
+def mx_rate_of_change_step(x, state, init=None, stream=None):
+    """Adds ||x - x_prev||_F / ||x_prev||_F to the state's running sum, then x_prev <- x.
+    init=True (default on first use) opens a window instead."""
+    rows, cols = x.shape
+    if (rows, cols) != (state.rows, state.cols):
+        raise ValueError("state was made for another shape")
+    if init is None:
+        init = not state.started
+    rc = lib().mx_rate_of_change_step(_ptr(x), _src_dtype(x), rows, cols, x.stride(0), _ptr(state.x_prev),
+                                      1 if init else 0, _ptr(state.workspace), state.workspace.numel(),
+                                      _ptr(state.result), _stream(stream))
+    _check("mx_rate_of_change_step", rc)
+    state.started = True
+    return state
 
 
 def mx_dequantize(codes, scales, stream=None):

@@ -208,6 +208,43 @@ int mx_ramping_factor(const float* dist_w, const float* dist_q, int64_t count,
     return hip_status(mxl::launch_ramping_factor(dist_w, dist_q, count, k1, k2, n_max, factor, static_cast<hipStream_t>(stream)));
 }
 
+int mx_quant_confidence(const void* w, int dtype, int64_t rows, int64_t cols, int64_t ld, int scale_mode,
+                  float* conf, uint64_t* hist, int bins, void* stream)
+{
+    if (!w || (!conf && !hist)) return MX_ERR_NULL;
+    if (dtype != MX_DTYPE_F32 && dtype != MX_DTYPE_BF16) return MX_ERR_DTYPE;
+    if (scale_mode != MX_SCALE_TRUNCFREE && scale_mode != MX_SCALE_FLOOR) return MX_ERR_MODE;
+    if (rows <= 0 || cols <= 0 || (cols % 32) != 0 || ld < cols) return MX_ERR_SHAPE;
+    if (rows > MAX_ELEMS / cols) return MX_ERR_SHAPE;
+    if (hist && (bins < 1 || bins > mxl::CONFIDENCE_MAX_BINS)) return MX_ERR_MODE;
+    if (!aligned(w, 16) || (conf && !aligned(conf, 16)) || (hist && !aligned(hist, 8))) return MX_ERR_ALIGN;
+    if (ld % (dtype == MX_DTYPE_BF16 ? 8 : 4) != 0) return MX_ERR_ALIGN;
+    mxl::ConfidenceParams p{};
+    p.w = w; p.bf16 = dtype == MX_DTYPE_BF16; p.rows = rows; p.cols = cols; p.ld = ld;
+    p.floor_mode = scale_mode == MX_SCALE_FLOOR; p.conf = conf; p.hist = hist; p.bins = bins;
+    return hip_status(mxl::launch_confidence(p, static_cast<hipStream_t>(stream)));
+}
+
+size_t mx_rate_of_change_workspace_bytes(void) { return mxl::rate_workspace_bytes(); }
+
+int mx_rate_of_change_step(const void* x, int dtype, int64_t rows, int64_t cols, int64_t ld,
+                  float* x_prev, int init, void* workspace, size_t workspace_bytes,
+                  double* result, void* stream)
+{
+    if (!x || !x_prev || !result) return MX_ERR_NULL;
+    if (dtype != MX_DTYPE_F32 && dtype != MX_DTYPE_BF16) return MX_ERR_DTYPE;
+    if (init != 0 && init != 1) return MX_ERR_MODE;
+    if (rows <= 0 || cols <= 0 || (cols % 8) != 0 || ld < cols) return MX_ERR_SHAPE;
+    if (rows > MAX_ELEMS / cols) return MX_ERR_SHAPE;
+    if (!workspace || workspace_bytes < mxl::rate_workspace_bytes()) return MX_ERR_WORKSPACE;
+    if (!aligned(x, 16) || !aligned(x_prev, 16) || !aligned(workspace, 8) || !aligned(result, 8)) return MX_ERR_ALIGN;
+    if (ld % (dtype == MX_DTYPE_BF16 ? 8 : 4) != 0) return MX_ERR_ALIGN;
+    mxl::RateParams p{};
+    p.x = x; p.bf16 = dtype == MX_DTYPE_BF16; p.rows = rows; p.cols = cols; p.ld = ld;
+    p.x_prev = x_prev; p.init = init; p.partial = static_cast<double*>(workspace); p.result = result;
+    return hip_status(mxl::launch_rate_of_change(p, static_cast<hipStream_t>(stream)));
+}
+
 int mx_dequantize(const uint8_t* codes, const uint8_t* scales, int64_t rows, int64_t cols,
                   float* out, void* stream)
 {

@@ -77,6 +77,30 @@ hipError_t launch_oscillation(const OscillationParams& p, hipStream_t st);
 hipError_t launch_ramping_factor(const float* dist_w, const float* dist_q, int64_t count, float k1, int k2,
                                  int n_max, int32_t* factor, hipStream_t st);
 
+struct ConfidenceParams {
+    const void* w;
+    bool bf16;
+    int64_t rows, cols, ld;
+    int floor_mode;
+    float* conf;            // may be null
+    uint64_t* hist;         // may be null
+    int bins;
+};
+constexpr int CONFIDENCE_MAX_BINS = 1024;
+hipError_t launch_confidence(const ConfidenceParams& p, hipStream_t st);
+
+struct RateParams {
+    const void* x;
+    bool bf16;
+    int64_t rows, cols, ld;
+    float* x_prev;
+    int init;
+    double* partial;        // rate_workspace_bytes() of scratch
+    double* result;         // 3 doubles
+};
+size_t rate_workspace_bytes();
+hipError_t launch_rate_of_change(const RateParams& p, hipStream_t st);
+
 hipError_t launch_calibration_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
 
 // Number of K-splits the product will use for these sizes (1 = none).

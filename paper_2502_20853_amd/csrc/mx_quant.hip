@@ -9,6 +9,9 @@
 //  ema_quantize_kernel    Q-EMA (Eq. 8, Algorithm 1)
 //  oscillation_kernel     trajectory lengths dist_W, dist_Q of Q-Ramping (Sec. 6.1)
 //  ramping_factor_kernel  amplification factor N_w of Algorithm 2
+//  confidence_kernel      quantization confidence per element and its histogram (Sec. 4.2)
+//  rate_partial_kernel,   one term of the rate of change of a tensor (Sec. 4.1): FP64 sums of
+//  rate_finish_kernel     squares, reduced in a fixed order
 //  dequantize_kernel      test aid
 //
 // Work split: one lane owns 8 consecutive elements of a row (one 16-byte bf16
@@ -432,6 +435,174 @@ __global__ void ramping_factor_kernel(const float* dist_w, const float* dist_q, 
     factor[i] = n;
 }
 
+// ---------------------------------------------------------------------------
+// Quantization confidence (Sec. 4.2) on the latent value y = w / S of a 1x32 group:
+//     conf = min_i |y - thrd_i| / MaxDist(y_FP4).
+// The thresholds are the midpoints of neighbouring E2M1 values; the cell of an E2M1 value reaches
+// from the threshold below to the threshold above it (the cell of 0 is [-0.25, 0.25], the cell of
+// 6 is [5, 6]), and MaxDist is half the cell's width, for the outermost cell the whole width.
+// The sign plays no part: everything is taken on a = |y|.  y is exact (a power-of-two scaling),
+// each distance is one FP32 subtraction, the quotient one IEEE division.
+// ---------------------------------------------------------------------------
+struct ConfArgs {
+    const void* w;
+    float* conf;                       // may be null
+    unsigned long long* hist;          // may be null
+    int64_t ld;
+    uint32_t cpr, total;
+    int bins;
+    int floor_mode;
+};
+
+__device__ __forceinline__ float confidence_of(float a)
+{
+    // lower threshold, upper threshold, MaxDist of the cell that holds a
+    float lo, hi, den;
+    if (a < 0.25f)      { lo = -0.25f; hi = 0.25f; den = 0.25f; }
+    else if (a < 0.75f) { lo = 0.25f;  hi = 0.75f; den = 0.25f; }
+    else if (a < 1.25f) { lo = 0.75f;  hi = 1.25f; den = 0.25f; }
+    else if (a < 1.75f) { lo = 1.25f;  hi = 1.75f; den = 0.25f; }
+    else if (a < 2.5f)  { lo = 1.75f;  hi = 2.5f;  den = 0.375f; }
+    else if (a < 3.5f)  { lo = 2.5f;   hi = 3.5f;  den = 0.5f; }
+    else if (a < 5.0f)  { lo = 3.5f;   hi = 5.0f;  den = 0.75f; }
+    else                { lo = 5.0f;   hi = __builtin_inff(); den = 1.0f; }
+    const float below = __fsub_rn(a, lo), above = __fsub_rn(hi, a);
+    return __fdiv_rn(below < above ? below : above, den);
+}
+
+constexpr int CONF_MAX_BINS = mxl::CONFIDENCE_MAX_BINS;
+
+template <typename SrcT>
+__global__ __launch_bounds__(ROWS_THREADS) void confidence_kernel(ConfArgs a)
+{
+    __shared__ uint32_t lh[CONF_MAX_BINS];
+    if (a.hist) {
+        for (int b = threadIdx.x; b < a.bins; b += ROWS_THREADS) lh[b] = 0u;
+        __syncthreads();
+    }
+    // a.total is a multiple of 4 and a quad of lanes (one 1x32 group) starts at a multiple of 4:
+    // the lanes of a group pass or fail the loop test together
+    for (uint32_t q = blockIdx.x * ROWS_THREADS + threadIdx.x; q < a.total; q += gridDim.x * ROWS_THREADS) {
+        const uint32_t r = q / a.cpr, ch = q - r * a.cpr;
+        const F8 w = load8(static_cast<const SrcT*>(a.w) + (int64_t)r * a.ld + (int64_t)ch * 8);
+        const uint32_t byte = scale_byte(quad_max(amax_bits8(w)), a.floor_mode);
+        const float inv = inv_scale(byte);
+        float c[8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            float y = __builtin_fabsf(__fmul_rn(w.v[t], inv));
+            y = y > 6.0f ? 6.0f : y;                       // Eq. 2's scale truncates to Q_p
+            c[t] = confidence_of(y);
+        }
+        if (a.conf) {
+            float4* out = reinterpret_cast<float4*>(a.conf + (size_t)q * 8);
+            out[0] = make_float4(c[0], c[1], c[2], c[3]);
+            out[1] = make_float4(c[4], c[5], c[6], c[7]);
+        }
+        if (a.hist) {
+            const float nb = (float)a.bins;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                int b = (int)floorf(__fmul_rn(c[t], nb));
+                b = b > a.bins - 1 ? a.bins - 1 : b;
+                atomicAdd(&lh[b], 1u);
+            }
+        }
+    }
+    if (a.hist) {
+        __syncthreads();
+        for (int b = threadIdx.x; b < a.bins; b += ROWS_THREADS)
+            if (lh[b]) atomicAdd(&a.hist[b], (unsigned long long)lh[b]);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// One term of the rate of change (Sec. 4.1): ||x - x_prev||_F / ||x_prev||_F, then x_prev = x.
+// Differences of FP32 values and their squares' sums are taken in FP64.  The order of the sums is
+// fixed by the launch shape (RATE_BLOCKS x ROWS_THREADS lanes, grid-stride over 8-element chunks,
+// then a tree within the block, then the blocks in index order), so a call repeats bit for bit.
+// ---------------------------------------------------------------------------
+constexpr int RATE_BLOCKS = 1024;
+
+struct RateArgs {
+    const void* x;
+    float* x_prev;
+    double* partial;                   // [RATE_BLOCKS][2]
+    int64_t ld;
+    uint32_t cpr, total;
+    int init;
+};
+
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+    return v;
+}
+
+template <typename SrcT>
+__global__ __launch_bounds__(ROWS_THREADS) void rate_partial_kernel(RateArgs a)
+{
+    __shared__ double red[2][ROWS_THREADS / 64];
+    double diff2 = 0.0, prev2 = 0.0;
+    for (uint32_t q = blockIdx.x * ROWS_THREADS + threadIdx.x; q < a.total; q += RATE_BLOCKS * ROWS_THREADS) {
+        const uint32_t r = q / a.cpr, ch = q - r * a.cpr;
+        const F8 x = load8(static_cast<const SrcT*>(a.x) + (int64_t)r * a.ld + (int64_t)ch * 8);
+        float4* pp = reinterpret_cast<float4*>(a.x_prev + (size_t)q * 8);
+        if (!a.init) {
+            const float4 p0 = pp[0], p1 = pp[1];
+            const float old[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const double o = (double)old[t], d = (double)x.v[t] - o;
+                diff2 = fma(d, d, diff2);
+                prev2 = fma(o, o, prev2);
+            }
+        }
+        pp[0] = make_float4(x.v[0], x.v[1], x.v[2], x.v[3]);
+        pp[1] = make_float4(x.v[4], x.v[5], x.v[6], x.v[7]);
+    }
+    diff2 = wave_sum(diff2);
+    prev2 = wave_sum(prev2);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) { red[0][wave] = diff2; red[1][wave] = prev2; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double d = 0.0, p = 0.0;
+        for (int i = 0; i < ROWS_THREADS / 64; ++i) { d += red[0][i]; p += red[1][i]; }
+        a.partial[2 * blockIdx.x] = d;
+        a.partial[2 * blockIdx.x + 1] = p;
+    }
+}
+
+// result[0] = this step's term, result[1] = sum of the terms since the window opened,
+// result[2] = their number.  One workgroup.
+__global__ __launch_bounds__(ROWS_THREADS) void rate_finish_kernel(const double* partial, int init, double* result)
+{
+    __shared__ double red[2][ROWS_THREADS / 64];
+    double d = 0.0, p = 0.0;
+    for (int b = threadIdx.x; b < RATE_BLOCKS; b += ROWS_THREADS) { d += partial[2 * b]; p += partial[2 * b + 1]; }
+    d = wave_sum(d);
+    p = wave_sum(p);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) { red[0][wave] = d; red[1][wave] = p; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        if (init) {
+            result[0] = 0.0; result[1] = 0.0; result[2] = 0.0;
+        } else {
+            double dd = 0.0, pp = 0.0;
+            for (int i = 0; i < ROWS_THREADS / 64; ++i) { dd += red[0][i]; pp += red[1][i]; }
+            double term;
+            if (pp == 0.0) term = dd == 0.0 ? 0.0 : (double)__builtin_inff();
+            else           term = sqrt(dd) / sqrt(pp);
+            result[0] = term;
+            result[1] = result[1] + term;
+            result[2] = result[2] + 1.0;
+        }
+    }
+}
+
 __global__ void dequantize_kernel(const uint8_t* codes, const uint8_t* scales, int64_t total_bytes,
                                   int64_t cols, float* out)
 {
@@ -561,6 +732,36 @@ hipError_t launch_oscillation(const OscillationParams& p, hipStream_t st)
     dim3 grid((a.total + ROWS_THREADS - 1) / ROWS_THREADS), block(ROWS_THREADS);
     if (p.bf16) hipLaunchKernelGGL(oscillation_kernel<uint16_t>, grid, block, 0, st, a);
     else        hipLaunchKernelGGL(oscillation_kernel<float>, grid, block, 0, st, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_confidence(const ConfidenceParams& p, hipStream_t st)
+{
+    ConfArgs a{};
+    a.w = p.w; a.conf = p.conf; a.hist = reinterpret_cast<unsigned long long*>(p.hist); a.ld = p.ld;
+    a.cpr = (uint32_t)(p.cols / 8); a.total = (uint32_t)(p.rows * (p.cols / 8));
+    a.bins = p.hist ? p.bins : 0; a.floor_mode = p.floor_mode;
+    // at most one workgroup per compute unit: each one flushes its histogram to memory once
+    uint32_t blocks = (a.total + ROWS_THREADS - 1) / ROWS_THREADS;
+    dim3 grid(blocks < 256u ? blocks : 256u), block(ROWS_THREADS);
+    if (p.bf16) hipLaunchKernelGGL(confidence_kernel<uint16_t>, grid, block, 0, st, a);
+    else        hipLaunchKernelGGL(confidence_kernel<float>, grid, block, 0, st, a);
+    return hipGetLastError();
+}
+
+size_t rate_workspace_bytes() { return (size_t)RATE_BLOCKS * 2 * sizeof(double); }
+
+hipError_t launch_rate_of_change(const RateParams& p, hipStream_t st)
+{
+    RateArgs a{};
+    a.x = p.x; a.x_prev = p.x_prev; a.partial = p.partial; a.ld = p.ld;
+    a.cpr = (uint32_t)(p.cols / 8); a.total = (uint32_t)(p.rows * (p.cols / 8)); a.init = p.init;
+    dim3 grid(RATE_BLOCKS), block(ROWS_THREADS);
+    if (p.bf16) hipLaunchKernelGGL(rate_partial_kernel<uint16_t>, grid, block, 0, st, a);
+    else        hipLaunchKernelGGL(rate_partial_kernel<float>, grid, block, 0, st, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(rate_finish_kernel, dim3(1), block, 0, st, p.partial, p.init, p.result);
     return hipGetLastError();
 }
 

@@ -145,3 +145,25 @@ def test_oscillation_and_ramping_rejects(L):
     assert r(dw=0) == -1 and r(out=0) == -1
     assert r(n=0) == -2
     assert r(k1=0.0) == -4 and r(k1=float("nan")) == -4 and r(k2=-1) == -4 and r(nmax=0) == -4
+
+
+def test_diagnostics_rejects(L):
+    def c(w=FAKE, dtype=0, rows=64, cols=64, ld=64, mode=0, conf=FAKE, hist=FAKE, bins=16):
+        return L.mx_quant_confidence(P(w), dtype, rows, cols, ld, mode, P(conf), P(hist), bins, P(0))
+    assert c(w=0) == -1 and c(conf=0, hist=0) == -1
+    assert c(dtype=7) == -3 and c(mode=2) == -4
+    assert c(cols=48) == -2 and c(ld=32) == -2 and c(rows=0) == -2
+    assert c(bins=0) == -4 and c(bins=1025) == -4
+    assert c(conf=FAKE + 8) == -5 and c(hist=FAKE + 4) == -5 and c(w=FAKE + 4) == -5
+
+    need = L.mx_rate_of_change_workspace_bytes()
+    assert need > 0
+
+    def r(x=FAKE, dtype=0, rows=64, cols=64, ld=64, xp=FAKE, init=0, ws=FAKE, wsb=None, res=FAKE):
+        return L.mx_rate_of_change_step(P(x), dtype, rows, cols, ld, P(xp), init, P(ws),
+                                        need if wsb is None else wsb, P(res), P(0))
+    assert r(x=0) == -1 and r(xp=0) == -1 and r(res=0) == -1
+    assert r(dtype=3) == -3 and r(init=-1) == -4
+    assert r(cols=60) == -2 and r(ld=56) == -2
+    assert r(ws=0) == -6 and r(wsb=need - 1) == -6
+    assert r(xp=FAKE + 4) == -5 and r(res=FAKE + 4) == -5

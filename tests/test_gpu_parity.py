@@ -526,3 +526,87 @@ def test_oscillation_accumulate_and_ramping_factor(mx, orc, dtype):
     want = orc.ramping_factor(dw, dq, 16.0, 5, 16)
     got = host(mx.mx_ramping_factor(dev(dw), dev(dq), 16.0, 5, 16))
     assert np.array_equal(got, want) and list(want[0]) == [1, 16, 16, 1]
+
+
+# ------------------------------------------------- oscillation diagnostics (Sec. 4) ----
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("scale_mode", [0, 1])
+def test_quant_confidence_bit_exact(mx, orc, dtype, scale_mode):
+    """QuantConf of Sec. 4.2 per element and its histogram, bit-exact: weights of the layer's
+    distribution, plus latent values planted on every threshold and cell centre, an all-zero group,
+    tiny and huge groups, and a strided source."""
+    import mx_workloads as wl
+    C, D = 200, 352                                    # ragged against the 256-lane launch, 11 groups per row
+    W = wl.weights(C, D, seed=31)
+    planted = [0.25, -0.75, 1.25, -1.75, 2.5, -3.5, 5.0, 0.0, 0.5, -1.0, 1.5, 2.125, -3.0, 4.25, -6.0, 6.0, 5.999, 0.2499]
+    W[0, :32] = 0.0
+    W[0, 0] = 6.0 * 0.125
+    W[0, 1:1 + len(planted)] = np.asarray(planted) * 0.125
+    W[1, :32] = 0.0                                    # all-zero group
+    W[2, 32:64] *= 1e-30                               # groups near the bottom and the top of FP32's range
+    W[3, 32:64] *= 1e30
+    W[4, 5] = 0.9                                      # an outlier that Eq. 2's scale truncates
+    if dtype == "bf16":
+        W = wl.round_to_bf16(W)
+    want, want_hist = orc.quant_confidence(W, scale_mode, bins=50)
+    hist = torch.zeros(50, dtype=torch.int64, device="cuda")
+    got, _ = mx.mx_quant_confidence(dev(W, dtype), scale_mode, hist=hist)
+    assert np.array_equal(host(got).view(np.uint32), want.view(np.uint32))
+    assert np.array_equal(host(hist).astype(np.uint64), want_hist)
+    if scale_mode == 0:
+        assert np.all(want[0, 1:8] == 0.0) and np.all(want[0, 8:17] == 1.0)
+    # histogram only, added to the counters already there; strided source
+    big = np.zeros((C, D + 64), np.float32)
+    big[:, :D] = W
+    view = dev(big, dtype)[:, :D]
+    _, h2 = mx.mx_quant_confidence(view, scale_mode, conf=False, hist=hist)
+    assert np.array_equal(host(h2).astype(np.uint64), 2 * want_hist)
+    got2, _ = mx.mx_quant_confidence(view, scale_mode)
+    assert np.array_equal(host(got2), want)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_rate_of_change_matches_oracle(mx, orc, dtype):
+    """Terms of r(X) (Sec. 4.1) over a weight walk: each term within 1e-12 relative of the oracle's
+    FP64 value (only the order of the FP64 sums differs: n * 2^-53 bounds it far below that), the
+    previous tensor bit-exact, the window sum and count kept on the device, reruns bit-identical."""
+    import mx_workloads as wl
+    C, D = 300, 328                                    # cols a multiple of 8 only
+    state = mx.RateOfChangeState(C, D)
+    xp = np.zeros((C, D), np.float32)
+    terms = []
+    for t, W in enumerate(wl.weight_walk(C, 352, seed=13, steps=6, sigma=2e-3)):
+        W = np.ascontiguousarray(W[:, :D])
+        if dtype == "bf16":
+            W = wl.round_to_bf16(W)
+        restart = t in (0, 4)
+        if restart:
+            xp[...] = W
+            terms = []
+        else:
+            terms.append(orc.rate_of_change_term(W, xp))
+        mx.mx_rate_of_change_step(dev(W, dtype), state, init=restart)
+        res = host(state.result)
+        assert np.array_equal(host(state.x_prev), xp), t
+        assert res[2] == len(terms)
+        if terms:
+            assert abs(res[0] - terms[-1]) <= 1e-12 * terms[-1], (t, res[0], terms[-1])
+            assert abs(res[1] - sum(terms)) <= 1e-12 * sum(terms)
+            assert abs(state.rate() - sum(terms) / len(terms)) <= 1e-12
+    assert terms and terms[-1] > 0
+    # the same step from the same state gives the same bits
+    a = mx.RateOfChangeState(C, D)
+    b = mx.RateOfChangeState(C, D)
+    W0, W1 = list(wl.weight_walk(C, 352, seed=14, steps=1, sigma=1e-2))[:2]
+    for st in (a, b):
+        mx.mx_rate_of_change_step(dev(np.ascontiguousarray(W0[:, :D])), st)
+        mx.mx_rate_of_change_step(dev(np.ascontiguousarray(W1[:, :D])), st)
+    assert host(a.result).tobytes() == host(b.result).tobytes()
+    # an unchanged tensor: 0; a zero previous tensor: +infinity
+    z = mx.RateOfChangeState(8, 32)
+    mx.mx_rate_of_change_step(dev(np.zeros((8, 32), np.float32)), z)
+    mx.mx_rate_of_change_step(dev(np.zeros((8, 32), np.float32)), z)
+    assert host(z.result)[0] == 0.0
+    mx.mx_rate_of_change_step(dev(np.ones((8, 32), np.float32)), z)
+    assert host(z.result)[0] == np.inf
