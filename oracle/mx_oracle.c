@@ -512,3 +512,30 @@ double orc_rate_of_change_term(const float* x, int64_t rows, int64_t cols, int64
     if (prev2 == 0.0) return diff2 == 0.0 ? 0.0 : INFINITY;
     return sqrt(diff2) / sqrt(prev2);
 }
+
+/* --------------------------------------------------- Q-Ramping's optimizer -- */
+
+void orc_ramping_adamw_step(double* w, const double* grad, int64_t count,
+                  double* m, double* v, double* g_acc,
+                  const int32_t* factor, int32_t* acc_steps, int32_t* updates,
+                  double lr, double beta1, double beta2, double eps, double weight_decay)
+{
+    for (int64_t i = 0; i < count; ++i) {
+        const int32_t n_w = factor ? factor[i] : 1;
+        g_acc[i] += grad[i];
+        acc_steps[i] += 1;
+        if (acc_steps[i] < n_w) continue;              /* this element's batch is not full yet */
+        const double g = g_acc[i] / (double)acc_steps[i];
+        const double lr_w = (double)n_w * lr;
+        updates[i] += 1;
+        const double u = (double)updates[i];
+        w[i] = w[i] * (1.0 - lr_w * weight_decay);
+        m[i] = beta1 * m[i] + (1.0 - beta1) * g;
+        v[i] = beta2 * v[i] + (1.0 - beta2) * g * g;
+        const double bc1 = 1.0 - pow(beta1, u);
+        const double bc2 = 1.0 - pow(beta2, u);
+        w[i] = w[i] - (lr_w / bc1) * m[i] / (sqrt(v[i]) / sqrt(bc2) + eps);
+        g_acc[i] = 0.0;
+        acc_steps[i] = 0;
+    }
+}

@@ -124,6 +124,24 @@ void orc_oscillation_accumulate(const float* w, int64_t rows, int64_t cols, int6
 void orc_ramping_factor(const float* dist_w, const float* dist_q, int64_t count,
                   float k1, int k2, int n_max, int32_t* factor);
 
+/* One optimizer step of Q-Ramping's customised AdamW (Algorithm 2, "update w according to LR_w and
+ * BS_w"; Sec. 6.2: the batch size of an oscillating weight is N_w times the global one, realised by
+ * accumulating its gradient, and its learning rate grows in proportion).  Per element, FP64:
+ *     g_acc += grad;  acc_steps += 1;
+ *     if acc_steps >= N_w:                       (N_w = factor, 1 everywhere if factor is NULL)
+ *         g = g_acc / acc_steps;  lr_w = N_w * lr;  u = ++updates;
+ *         w = w * (1 - lr_w * weight_decay)                              (decoupled decay)
+ *         m = beta1 * m + (1 - beta1) * g;   v = beta2 * v + (1 - beta2) * g * g;
+ *         w = w - (lr_w / (1 - beta1^u)) * m / (sqrt(v) / sqrt(1 - beta2^u) + eps);
+ *         g_acc = 0;  acc_steps = 0;
+ * so that an element with factor N follows exactly AdamW at learning rate N * lr on the means of N
+ * consecutive gradients, its bias correction counting its own updates.  The paper gives no formula
+ * for the update; this is the reading taken. */
+void orc_ramping_adamw_step(double* w, const double* grad, int64_t count,
+                  double* m, double* v, double* g_acc,
+                  const int32_t* factor, int32_t* acc_steps, int32_t* updates,
+                  double lr, double beta1, double beta2, double eps, double weight_decay);
+
 /* Quantization confidence (Sec. 4.2): for a weight element w of a 1x32 group with scale S,
  * on the latent value y = w / S,
  *     QuantConf = min_i |y - thrd_i| / MaxDist(y_FP4),

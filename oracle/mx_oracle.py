@@ -35,6 +35,7 @@ _lib = None
 _u8p = ctypes.POINTER(ctypes.c_uint8)
 _f32p = ctypes.POINTER(ctypes.c_float)
 _f64p = ctypes.POINTER(ctypes.c_double)
+_i32p = ctypes.POINTER(ctypes.c_int32)
 _i64p = ctypes.POINTER(ctypes.c_int64)
 _u32p = ctypes.POINTER(ctypes.c_uint32)
 _i64, _u64, _u32, _int = ctypes.c_int64, ctypes.c_uint64, ctypes.c_uint32, ctypes.c_int
@@ -81,6 +82,10 @@ def lib():
         L.orc_quant_confidence.argtypes = [_f32p, _i64, _i64, _i64, _int, _f32p, ctypes.POINTER(ctypes.c_uint64), _int]
         L.orc_rate_of_change_term.restype = ctypes.c_double
         L.orc_rate_of_change_term.argtypes = [_f32p, _i64, _i64, _i64, _f32p]
+        L.orc_ramping_adamw_step.restype = None
+        L.orc_ramping_adamw_step.argtypes = [_f64p, _f64p, _i64, _f64p, _f64p, _f64p, _i32p, _i32p, _i32p,
+                                             ctypes.c_double, ctypes.c_double, ctypes.c_double, ctypes.c_double,
+                                             ctypes.c_double]
         L.orc_ramping_factor.restype = None
         L.orc_ramping_factor.argtypes = [_f32p, _f32p, _i64, ctypes.c_float, _int, _int, ctypes.POINTER(ctypes.c_int32)]
         _lib = L
@@ -274,3 +279,27 @@ def rate_of_change_term(x, x_prev):
     rows, cols = x.shape
     assert x_prev.dtype == np.float32 and x_prev.shape == (rows, cols) and x_prev.flags["C_CONTIGUOUS"]
     return float(lib().orc_rate_of_change_term(_p(x, _f32p), rows, cols, x.strides[0] // 4, _p(x_prev, _f32p)))
+
+
+def ramping_adamw_state(w):
+    """Fresh optimizer state for weights w: dict of float64 w, m, v, g_acc and int32 acc_steps, updates."""
+    w = np.array(w, np.float64).ravel()
+    z = lambda t: np.zeros(w.shape, t)
+    return {"w": w, "m": z(np.float64), "v": z(np.float64), "g_acc": z(np.float64),
+            "acc_steps": z(np.int32), "updates": z(np.int32)}
+
+
+def ramping_adamw_step(state, grad, factor=None, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01):
+    """One step of Q-Ramping's customised AdamW (Algorithm 2) on the state, in place."""
+    g = np.ascontiguousarray(np.asarray(grad, np.float64).ravel())
+    n = state["w"].size
+    assert g.size == n
+    f = None
+    if factor is not None:
+        f = np.ascontiguousarray(np.asarray(factor, np.int32).ravel())
+        assert f.size == n
+    lib().orc_ramping_adamw_step(_p(state["w"], _f64p), _p(g, _f64p), n, _p(state["m"], _f64p), _p(state["v"], _f64p),
+                                 _p(state["g_acc"], _f64p), _p(f, _i32p), _p(state["acc_steps"], _i32p),
+                                 _p(state["updates"], _i32p), float(lr), float(beta1), float(beta2), float(eps),
+                                 float(weight_decay))
+    return state

@@ -737,3 +737,90 @@ def test_rate_of_change_closed_forms_and_numpy(orc):
     xp = prev.copy()
     terms = [orc.rate_of_change_term((prev * np.float32(2.0 ** (t + 1))), xp) for t in range(5)]
     assert abs(sum(terms) / 5 - 1.0) < 1e-14
+
+
+# ------------------------------------------------- Q-Ramping's customised AdamW ----
+
+def _torch_adamw_run(w0, grads, lr, betas, eps, wd):
+    """torch.optim.AdamW (CPU, FP64, plain single-tensor path) over a list of gradients."""
+    import torch
+    p = torch.nn.Parameter(torch.tensor(np.asarray(w0, np.float64)))
+    opt = torch.optim.AdamW([p], lr=lr, betas=betas, eps=eps, weight_decay=wd, foreach=False)
+    out = []
+    for g in grads:
+        p.grad = torch.tensor(np.asarray(g, np.float64))
+        opt.step()
+        out.append(p.detach().numpy().copy())
+    return out
+
+
+def test_ramping_adamw_factor_one_is_adamw(orc):
+    # Algorithm 2 with N_w = 1 everywhere is "normal AdamW": the library's, step for step
+    rng = np.random.default_rng(3)
+    w0 = rng.standard_normal(257) * 0.05
+    grads = [rng.standard_normal(257) * 10.0 ** rng.uniform(-4, 0) for _ in range(12)]
+    hp = dict(lr=2e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.05)
+    ref = _torch_adamw_run(w0, grads, hp["lr"], (hp["beta1"], hp["beta2"]), hp["eps"], hp["weight_decay"])
+    for factor in (None, np.ones(257, np.int32)):
+        st = orc.ramping_adamw_state(w0)
+        for t, g in enumerate(grads):
+            orc.ramping_adamw_step(st, g, factor, **hp)
+            assert np.allclose(st["w"], ref[t], rtol=1e-12, atol=1e-15), t
+            assert np.all(st["updates"] == t + 1) and np.all(st["acc_steps"] == 0) and np.all(st["g_acc"] == 0)
+
+
+def test_ramping_adamw_element_follows_large_batch_adamw(orc):
+    # Sec. 6.2: an element with factor N has N times the batch size (its gradients are accumulated
+    # over N steps) and N times the learning rate.  So it must follow AdamW at lr * N on the means
+    # of N consecutive gradients, and stand still in between; elements are independent.
+    rng = np.random.default_rng(4)
+    n, T = 60, 24
+    w0 = rng.standard_normal(n) * 0.05
+    grads = [rng.standard_normal(n) * 0.01 for _ in range(T)]
+    factor = np.array([1, 2, 3, 4, 6, 16] * 10, np.int32)
+    hp = dict(lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+    st = orc.ramping_adamw_state(w0)
+    traj = []
+    for g in grads:
+        orc.ramping_adamw_step(st, g, factor, **hp)
+        traj.append(st["w"].copy())
+    for N in (1, 2, 3, 4, 6, 16):
+        sel = factor == N
+        means = [np.mean(grads[k * N:(k + 1) * N], axis=0)[sel] for k in range(T // N)]
+        ref = _torch_adamw_run(w0[sel], means, hp["lr"] * N, (hp["beta1"], hp["beta2"]), hp["eps"], hp["weight_decay"])
+        for t in range(T):
+            done = (t + 1) // N                       # updates made after step t (0-based)
+            want = w0[sel] if done == 0 else ref[done - 1]
+            assert np.allclose(traj[t][sel], want, rtol=1e-12, atol=1e-15), (N, t)
+        assert np.all(st["updates"][sel] == T // N)
+        assert np.all(st["acc_steps"][sel] == T % N)
+
+
+def test_ramping_adamw_first_update_closed_form_and_refactor(orc):
+    # First AdamW update without decay: m_hat = g, v_hat = g^2, so w moves by lr_w * g / (|g| + eps):
+    # N * lr in the direction opposite to the mean gradient.
+    w0 = np.array([1.0, -2.0, 0.5, 0.25])
+    factor = np.array([1, 4, 4, 2], np.int32)
+    g = np.array([0.3, -0.2, 0.1, 0.0])
+    st = orc.ramping_adamw_state(w0)
+    for t in range(4):
+        orc.ramping_adamw_step(st, g, factor, lr=1e-2, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0)
+        if t == 0:
+            assert abs(st["w"][0] - (1.0 - 1e-2)) < 1e-9
+            assert st["w"][1] == -2.0 and st["w"][2] == 0.5       # their batches are not full
+            assert np.all(st["m"][1:] == 0) and np.all(st["v"][1:] == 0)
+            assert list(st["acc_steps"]) == [0, 1, 1, 1]
+    assert abs(st["w"][1] - (-2.0 + 4e-2)) < 1e-8                  # one update of 4 * lr against the sign of g
+    assert abs(st["w"][2] - (0.5 - 4e-2)) < 1e-8
+    assert st["w"][3] == 0.25                                      # zero gradient: 0 / (0 + eps) = 0
+    assert list(st["updates"]) == [4, 1, 1, 2]
+    # a new detection lowers an element's factor below what it has accumulated: it updates at once,
+    # with the mean of what it holds
+    st = orc.ramping_adamw_state([0.0])
+    for gval in (1.0, 2.0, 3.0):
+        orc.ramping_adamw_step(st, [gval], np.array([8], np.int32), lr=1e-2, weight_decay=0.0)
+    assert st["updates"][0] == 0 and st["g_acc"][0] == 6.0
+    orc.ramping_adamw_step(st, [6.0], np.array([2], np.int32), lr=1e-2, weight_decay=0.0)
+    assert st["updates"][0] == 1 and st["acc_steps"][0] == 0
+    assert abs(st["m"][0] - 0.1 * 3.0) < 1e-15                     # mean of 1, 2, 3, 6
+    assert abs(st["w"][0] - (-2e-2)) < 1e-9                        # lr_w = 2 * lr
