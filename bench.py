@@ -213,6 +213,33 @@ def main():
                      "rate_of_change_us": round(us_r, 1),
                      "rate_of_change_GB/s": round(C * D * (eb + 8) / us_r / 1e3, 1)})
 
+    # Q-Ramping's customised AdamW (Algorithm 2), outside the timed region: one optimizer step over
+    # all quantized-layer weights of a 12-block model of these shapes (one flat launch), with factors
+    # from a synthetic oscillating minority, and the same without factors (plain AdamW)
+    n_par = 12 * sum(C * D for (_, _, D, C) in layers)
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    w_all = torch.randn(n_par, device="cuda", generator=gen) * 0.02
+    g_all = torch.randn(n_par, device="cuda", generator=gen) * 1e-3
+    fac_all = torch.where(torch.rand(n_par, device="cuda", generator=gen) < 0.02,
+                          torch.full((n_par,), 6, dtype=torch.int32, device="cuda"),
+                          torch.ones(n_par, dtype=torch.int32, device="cuda"))
+    opt = []
+    for label, fac, bytes_per in (("ramping", fac_all, 56), ("plain_adamw", None, 36)):
+        ost = mx.binding.RampingAdamwState((n_par,), ramping=fac is not None)
+        for _ in range(2):
+            mx.binding.mx_ramping_adamw_step(w_all, g_all, ost, fac)
+        e0, e1 = ev(), ev()
+        e0.record()
+        for _ in range(10):
+            mx.binding.mx_ramping_adamw_step(w_all, g_all, ost, fac)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / 10 * 1e3
+        opt.append({"mode": label, "elements": n_par, "us": round(us, 1), "bytes_per_element": bytes_per,
+                    "GB/s": round(n_par * bytes_per / us / 1e3, 1),
+                    "hbm_frac": round(n_par * bytes_per / us / 1e3 / PEAK_HBM_GBS, 3)})
+    del w_all, g_all, fac_all, ost
+
     gemm_ms = sum(a.elapsed_time(b) for a, b in gemm_events) / args.steps      # per step, all 12 products
     quant_ms = sum(a.elapsed_time(b) for a, b in quant_events) / args.steps
     n_gemm = 3 * len(layers)
@@ -284,6 +311,7 @@ def main():
         "qema_weight_quant": qema,
         "oscillation_detection": osc,
         "oscillation_diagnostics": diag,
+        "ramping_adamw": opt,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(layers, args.cpu_sample_tokens)

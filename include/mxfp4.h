@@ -179,6 +179,35 @@ int mx_oscillation_accumulate(const void* w, int dtype, int64_t rows, int64_t co
 int mx_ramping_factor(const float* dist_w, const float* dist_q, int64_t count,
                   float k1, int k2, int n_max, int32_t* factor, void* stream);
 
+/*
+ * One optimizer step of Q-Ramping's customised AdamW (Algorithm 2, "update w according to LR_w and
+ * BS_w"; Sec. 6.2) on `count` weight elements.  An element with amplification factor N_w accumulates
+ * its gradient over N_w steps (N_w times the batch size) and then takes one AdamW update at N_w
+ * times the learning rate.  Per element:
+ *     g_acc += grad;  acc_steps += 1;
+ *     if acc_steps >= N_w:
+ *         g = g_acc / acc_steps;  lr_w = N_w * lr;  u = ++updates;
+ *         w = w * (1 - lr_w * weight_decay);
+ *         m = beta1 * m + (1 - beta1) * g;   v = beta2 * v + (1 - beta2) * g * g;
+ *         w = w - (lr_w / (1 - beta1^u)) * m / (sqrt(v) / sqrt(1 - beta2^u) + eps);
+ *         g_acc = 0;  acc_steps = 0;
+ * (the paper prints no formula for the update: this is AdamW with decoupled decay, the bias
+ * correction counting the element's own updates, so that factor 1 is exactly AdamW).  FP32.
+ *   w, m, v      device in/out, FP32, count elements (the master weight and AdamW's two moments)
+ *   grad         device, F32 or BF16, count elements (e.g. the dW of mx_linear_bwd_dw)
+ *   updates      device in/out, int32: updates each element has made; all zero at the start
+ *   factor       device, int32: N_w >= 1 per element (mx_ramping_factor's output), or NULL for 1
+ *                everywhere (plain AdamW; g_acc and acc_steps are then not used and may be NULL)
+ *   g_acc, acc_steps   device in/out, FP32 / int32: the gradient sum an element holds and the number
+ *                of steps in it; all zero at the start
+ *   count % 4 == 0; every array 16-byte aligned (grad in BF16: 8).
+ *   lr >= 0, 0 < beta1, beta2 < 1, eps >= 0, weight_decay >= 0, else MX_ERR_MODE.
+ */
+int mx_ramping_adamw_step(float* w, const void* grad, int grad_dtype, int64_t count,
+                  float* m, float* v, int32_t* updates,
+                  const int32_t* factor, float* g_acc, int32_t* acc_steps,
+                  float lr, float beta1, float beta2, float eps, float weight_decay, void* stream);
+
 /* ---- oscillation diagnostics (Sec. 4) ---- */
 
 /*

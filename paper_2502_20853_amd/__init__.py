@@ -8,5 +8,6 @@ from .binding import (  # noqa: F401
     mx_linear_workspace_bytes, mx_quantize, mx_quantize_transposed, mx_version,
     OscillationState, mx_oscillation_accumulate, mx_ramping_factor,
     RateOfChangeState, mx_quant_confidence, mx_rate_of_change_step,
+    RampingAdamwState, mx_ramping_adamw_step,
 )
 from .layer import MxLinearStep  # noqa: F401

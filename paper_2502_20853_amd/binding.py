@@ -27,7 +27,7 @@ GEMM_FWD, GEMM_BWD_DX, GEMM_BWD_DW = 0, 1, 2
 EXPORTS = ["mx_quantize", "mx_quantize_transposed", "mx_linear_fwd", "mx_linear_bwd_dx",
            "mx_linear_bwd_dw", "mx_ema_weight_quant", "mx_linear_workspace_bytes",
            "mx_oscillation_accumulate", "mx_ramping_factor",
-           "mx_quant_confidence", "mx_rate_of_change_workspace_bytes", "mx_rate_of_change_step",
+           "mx_ramping_adamw_step", "mx_quant_confidence", "mx_rate_of_change_workspace_bytes", "mx_rate_of_change_step",
            "mx_dequantize", "mx_calibration_copy", "mx_last_hip_error", "mx_version"]
 
 
@@ -71,6 +71,8 @@ def lib():
     L.mx_oscillation_accumulate.argtypes = [vp, ci, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp, ci, vp]
     L.mx_ramping_factor.restype = ci
     L.mx_ramping_factor.argtypes = [vp, vp, i64, f32, ci, ci, vp, vp]
+    L.mx_ramping_adamw_step.restype = ci
+    L.mx_ramping_adamw_step.argtypes = [vp, vp, ci, i64, vp, vp, vp, vp, vp, vp, f32, f32, f32, f32, f32, vp]
     L.mx_quant_confidence.restype = ci
     L.mx_quant_confidence.argtypes = [vp, ci, i64, i64, i64, ci, vp, vp, ci, vp]
     L.mx_rate_of_change_workspace_bytes.restype = sz
@@ -252,6 +254,41 @@ def mx_ramping_factor(dist_w, dist_q, k1=16.0, k2=5, n_max=16, out=None, stream=
                                  _ptr(out), _stream(stream))
     _check("mx_ramping_factor", rc)
     return out
+
+
+class RampingAdamwState:
+    """Device state of Q-Ramping's customised AdamW for one weight: the two moments, the per-element
+    update counts, and (ramping=True) the per-element gradient sums and their step counts."""
+
+    def __init__(self, shape, device="cuda", ramping=True):
+        self.shape = tuple(shape)
+        z = lambda dt: torch.zeros(self.shape, dtype=dt, device=device)
+        self.m, self.v, self.updates = z(torch.float32), z(torch.float32), z(torch.int32)
+        self.g_acc = z(torch.float32) if ramping else None
+        self.acc_steps = z(torch.int32) if ramping else None
+
+
+def mx_ramping_adamw_step(w, grad, state, factor=None, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8,
+                          weight_decay=0.01, stream=None):
+    """One step of Algorithm 2's optimizer on the master weight w (float32, contiguous, in place).
+    factor: int32 tensor from mx_ramping_factor, or None for plain AdamW."""
+    if w.dtype != torch.float32 or not w.is_contiguous() or not grad.is_contiguous():
+        raise ValueError("w must be contiguous float32, grad contiguous")
+    if tuple(w.shape) != state.shape or grad.shape != w.shape:
+        raise ValueError("shape mismatch")
+    if factor is not None:
+        if state.g_acc is None:
+            raise ValueError("state was made without ramping")
+        if factor.dtype != torch.int32 or not factor.is_contiguous() or factor.shape != w.shape:
+            raise ValueError("factor must be a contiguous int32 tensor of w's shape")
+    rc = lib().mx_ramping_adamw_step(_ptr(w), _ptr(grad), _src_dtype(grad), w.numel(), _ptr(state.m), _ptr(state.v),
+                                     _ptr(state.updates), _ptr(factor),
+                                     _ptr(state.g_acc if factor is not None else None),
+                                     _ptr(state.acc_steps if factor is not None else None),
+                                     float(lr), float(beta1), float(beta2), float(eps), float(weight_decay),
+                                     _stream(stream))
+    _check("mx_ramping_adamw_step", rc)
+    return w
 
 
 def mx_quant_confidence(w, scale_mode=SCALE_TRUNCFREE, conf=True, hist=None, stream=None):

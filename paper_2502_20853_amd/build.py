@@ -6,7 +6,7 @@ import sys
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libmxfp4_hip.so")
-SOURCES = ["mx_api.hip", "mx_quant.hip", "mx_gemm.hip"]
+SOURCES = ["mx_api.hip", "mx_quant.hip", "mx_gemm.hip", "mx_optim.hip"]
 HEADERS = ["mx_device.hpp", "mx_launch.hpp", os.path.join("..", "..", "include", "mxfp4.h")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

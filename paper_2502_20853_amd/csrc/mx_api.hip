@@ -208,6 +208,28 @@ int mx_ramping_factor(const float* dist_w, const float* dist_q, int64_t count,
     return hip_status(mxl::launch_ramping_factor(dist_w, dist_q, count, k1, k2, n_max, factor, static_cast<hipStream_t>(stream)));
 }
 
+int mx_ramping_adamw_step(float* w, const void* grad, int grad_dtype, int64_t count,
+                  float* m, float* v, int32_t* updates,
+                  const int32_t* factor, float* g_acc, int32_t* acc_steps,
+                  float lr, float beta1, float beta2, float eps, float weight_decay, void* stream)
+{
+    if (!w || !grad || !m || !v || !updates) return MX_ERR_NULL;
+    if (factor && (!g_acc || !acc_steps)) return MX_ERR_NULL;
+    if (grad_dtype != MX_DTYPE_F32 && grad_dtype != MX_DTYPE_BF16) return MX_ERR_DTYPE;
+    if (count <= 0 || (count % 4) != 0 || count > ((int64_t)1 << 40)) return MX_ERR_SHAPE;
+    // betas in (0, 1) so that 1 - beta^u > 0 for every u >= 1; written so that NaN fails
+    if (!(lr >= 0.0f) || !(beta1 > 0.0f && beta1 < 1.0f) || !(beta2 > 0.0f && beta2 < 1.0f) ||
+        !(eps >= 0.0f) || !(weight_decay >= 0.0f)) return MX_ERR_MODE;
+    if (!aligned(w, 16) || !aligned(m, 16) || !aligned(v, 16) || !aligned(updates, 16) ||
+        !aligned(grad, grad_dtype == MX_DTYPE_BF16 ? 8 : 16)) return MX_ERR_ALIGN;
+    if (factor && (!aligned(factor, 16) || !aligned(g_acc, 16) || !aligned(acc_steps, 16))) return MX_ERR_ALIGN;
+    mxl::RampingAdamwParams p{};
+    p.w = w; p.grad = grad; p.grad_bf16 = grad_dtype == MX_DTYPE_BF16; p.count = count; p.m = m; p.v = v;
+    p.updates = updates; p.factor = factor; p.g_acc = factor ? g_acc : nullptr; p.acc_steps = factor ? acc_steps : nullptr;
+    p.lr = lr; p.beta1 = beta1; p.beta2 = beta2; p.eps = eps; p.weight_decay = weight_decay;
+    return hip_status(mxl::launch_ramping_adamw(p, static_cast<hipStream_t>(stream)));
+}
+
 int mx_quant_confidence(const void* w, int dtype, int64_t rows, int64_t cols, int64_t ld, int scale_mode,
                   float* conf, uint64_t* hist, int bins, void* stream)
 {

@@ -101,6 +101,21 @@ struct RateParams {
 size_t rate_workspace_bytes();
 hipError_t launch_rate_of_change(const RateParams& p, hipStream_t st);
 
+struct RampingAdamwParams {
+    float* w;
+    const void* grad;
+    bool grad_bf16;
+    int64_t count;          // multiple of 4
+    float* m;
+    float* v;
+    float* g_acc;           // null iff factor is null
+    const int32_t* factor;  // null: plain AdamW
+    int32_t* acc_steps;     // null iff factor is null
+    int32_t* updates;
+    float lr, beta1, beta2, eps, weight_decay;
+};
+hipError_t launch_ramping_adamw(const RampingAdamwParams& p, hipStream_t st);
+
 hipError_t launch_calibration_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
 
 // Number of K-splits the product will use for these sizes (1 = none).

@@ -167,3 +167,20 @@ def test_diagnostics_rejects(L):
     assert r(cols=60) == -2 and r(ld=56) == -2
     assert r(ws=0) == -6 and r(wsb=need - 1) == -6
     assert r(xp=FAKE + 4) == -5 and r(res=FAKE + 4) == -5
+
+
+def test_ramping_adamw_rejects(L):
+    import ctypes
+    f = ctypes.c_float
+
+    def a(w=FAKE, g=FAKE, gd=0, n=64, m=FAKE, v=FAKE, u=FAKE, fac=FAKE, acc=FAKE, st=FAKE,
+          lr=1e-3, b1=0.9, b2=0.999, eps=1e-8, wd=0.01):
+        return L.mx_ramping_adamw_step(P(w), P(g), gd, n, P(m), P(v), P(u), P(fac), P(acc), P(st),
+                                       f(lr), f(b1), f(b2), f(eps), f(wd), P(0))
+    assert a(w=0) == -1 and a(g=0) == -1 and a(m=0) == -1 and a(u=0) == -1
+    assert a(acc=0) == -1 and a(st=0) == -1            # a factor needs its accumulators
+    assert a(gd=2) == -3
+    assert a(n=0) == -2 and a(n=66) == -2
+    assert a(b1=1.0) == -4 and a(b2=0.0) == -4 and a(lr=-1.0) == -4 and a(eps=float("nan")) == -4 and a(wd=-0.1) == -4
+    assert a(w=FAKE + 4) == -5 and a(u=FAKE + 8) == -5 and a(fac=FAKE + 4) == -5 and a(g=FAKE + 8) == -5
+    assert a(g=FAKE + 8, gd=1) != -5                   # BF16 gradients need 8-byte alignment only

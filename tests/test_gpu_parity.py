@@ -610,3 +610,61 @@ def test_rate_of_change_matches_oracle(mx, orc, dtype):
     assert host(z.result)[0] == 0.0
     mx.mx_rate_of_change_step(dev(np.ones((8, 32), np.float32)), z)
     assert host(z.result)[0] == np.inf
+
+
+# ------------------------------------------------- Q-Ramping's customised AdamW (Algorithm 2) ----
+
+@pytest.mark.parametrize("grad_dtype", ["f32", "bf16"])
+def test_ramping_adamw_matches_oracle(mx, orc, grad_dtype):
+    """T steps of the optimizer from the same start, GPU (FP32) against the oracle (FP64), each on its
+    own state.  The integer state (steps held, updates made) must be identical; w, m, v agree within
+    the FP32 rounding of the ~10 operations of an update, which adds per step at most about
+    2^-23 |w| (the stored weight) + 2e-6 lr N_max (the update term) to |w_gpu - w_oracle|."""
+    import mx_workloads as wl
+    C, D, T = 96, 200, 14                               # 19200 elements: 18.75 workgroups of 1024
+    lr, b1, b2, eps, wd = (float(np.float32(x)) for x in (2e-3, 0.9, 0.999, 1e-8, 0.05))
+    rng = np.random.default_rng(77)
+    W0 = wl.weights(C, 224, seed=41)[:, :D].copy()
+    factor = np.ones((C, D), np.int32)
+    osc = rng.random((C, D)) < 0.15                     # the paper's oscillating minority, here 15 %
+    factor[osc] = rng.choice([2, 3, 6, 11, 16], int(osc.sum()))
+    ost = orc.ramping_adamw_state(W0)
+    w = dev(W0)
+    st = mx.RampingAdamwState((C, D))
+    fac = dev(factor)
+    gmax = 0.0
+    for t in range(T):
+        g = (rng.standard_normal((C, D)) * 3e-3 * 10.0 ** rng.uniform(-1, 1)).astype(np.float32)
+        if t == 5:
+            g[:, :8] = 0.0
+        if grad_dtype == "bf16":
+            g = wl.round_to_bf16(g)
+        if t == 9:                                      # a new detection: factors change under held gradients
+            factor = np.where(rng.random((C, D)) < 0.5, factor, np.maximum(1, factor // 2)).astype(np.int32)
+            fac = dev(factor)
+        gmax = max(gmax, float(np.abs(g).max()))
+        orc.ramping_adamw_step(ost, g, factor, lr, b1, b2, eps, wd)
+        mx.mx_ramping_adamw_step(w, dev(g, grad_dtype), st, fac, lr, b1, b2, eps, wd)
+        assert np.array_equal(host(st.acc_steps).ravel(), ost["acc_steps"]), t
+        assert np.array_equal(host(st.updates).ravel(), ost["updates"]), t
+        n = t + 1
+        tol_w = n * (2.0 ** -23 * np.abs(W0).max() + 2e-6 * lr * 16)
+        err_w = np.abs(host(w).ravel().astype(np.float64) - ost["w"]).max()
+        assert err_w <= tol_w, (t, err_w, tol_w)
+        err_m = np.abs(host(st.m).ravel().astype(np.float64) - ost["m"]).max()
+        assert err_m <= n * 3e-7 * gmax, (t, err_m)
+        err_v = np.abs(host(st.v).ravel().astype(np.float64) - ost["v"]).max()
+        assert err_v <= n * 3e-7 * gmax ** 2, (t, err_v)
+        err_a = np.abs(host(st.g_acc).ravel().astype(np.float64) - ost["g_acc"]).max()
+        assert err_a <= 16 * 2.0 ** -23 * gmax, (t, err_a)
+    assert ost["updates"].min() < ost["updates"].max()
+    # plain AdamW (no factor): same bar, and the ramping state is not needed
+    ost = orc.ramping_adamw_state(W0)
+    w = dev(W0)
+    st = mx.RampingAdamwState((C, D), ramping=False)
+    for t in range(4):
+        g = (rng.standard_normal((C, D)) * 3e-3).astype(np.float32)
+        orc.ramping_adamw_step(ost, g, None, lr, b1, b2, eps, wd)
+        mx.mx_ramping_adamw_step(w, dev(g), st, None, lr, b1, b2, eps, wd)
+    assert np.all(host(st.updates) == 4)
+    assert np.abs(host(w).ravel().astype(np.float64) - ost["w"]).max() <= 4 * (2.0 ** -23 * np.abs(W0).max() + 2e-6 * lr)
