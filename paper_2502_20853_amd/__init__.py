@@ -11,3 +11,4 @@ from .binding import (  # noqa: F401
     RampingAdamwState, mx_ramping_adamw_step,
 )
 from .layer import MxLinearStep  # noqa: F401
+from .module import MxLinear  # noqa: F401
