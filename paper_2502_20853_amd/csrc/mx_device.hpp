@@ -263,14 +263,21 @@ __device__ __forceinline__ F8 zero8()
     return r;
 }
 
+// max(|a|, |b|, m) on FP32 bit patterns in one instruction: for finite values the order of the
+// magnitudes is the order of their bit patterns, and the source modifiers take the absolute values
+// (the separate AND and the two-operand maximum cost more issue cycles than this one instruction).
+__device__ __forceinline__ uint32_t absmax3_bits(float a, float b, uint32_t m)
+{
+    float r;
+    asm("v_max3_f32 %0, |%1|, |%2|, %3" : "=v"(r) : "v"(a), "v"(b), "v"(__uint_as_float(m)));
+    return __float_as_uint(r);
+}
+
 __device__ __forceinline__ uint32_t amax_bits8(const F8& x)
 {
     uint32_t m = 0;
 #pragma unroll
-    for (int t = 0; t < 8; ++t) {
-        uint32_t b = __float_as_uint(x.v[t]) & 0x7FFFFFFFu;
-        m = b > m ? b : m;
-    }
+    for (int t = 0; t < 8; t += 2) m = absmax3_bits(x.v[t], x.v[t + 1], m);
     return m;
 }
 

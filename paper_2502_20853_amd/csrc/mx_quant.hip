@@ -283,12 +283,8 @@ __global__ __launch_bounds__(TILE_THREADS, 4) void quantize_tile_kernel(TileArgs
         uint32_t sb[8];
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
-            uint32_t m = 0;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                uint32_t b = __float_as_uint(x[j].v[t]) & 0x7FFFFFFFu;
-                m = b > m ? b : m;
-            }
+            uint32_t m = absmax3_bits(x[0].v[t], x[1].v[t], 0u);
+            m = absmax3_bits(x[2].v[t], x[3].v[t], m);
             m = xor_lane_max(m, 8);
             m = xor_lane_max(m, 16);
             m = xor_lane_max(m, 32);
