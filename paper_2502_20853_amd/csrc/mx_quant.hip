@@ -193,6 +193,49 @@ __device__ __forceinline__ uint32_t xor_lane_max(uint32_t v, int mask)
     return v > o ? v : o;
 }
 
+// Copies one staged result of a macro tile to memory: `lines` staged lines (rows of row codes, or
+// columns of transposed codes), each `pieces` 16-byte pieces of codes (ST_PITCH apart in LDS,
+// `code_pitch` bytes apart in memory) and `pieces` scale bytes (8 apart in LDS, `scale_pitch` apart
+// in memory); pieces <= 8.  A lane keeps its piece and steps over the lines, so the loop has no
+// index arithmetic beyond two additions; when a line's scale bytes form an aligned 8- or 4-byte
+// word they leave as one store.
+__device__ __forceinline__ void write_staged(const uint8_t* codes_st, const uint8_t* scales_st,
+                                             uint32_t lines, uint32_t pieces,
+                                             uint8_t* codes, size_t code_pitch,
+                                             uint8_t* scales, size_t scale_pitch, uint32_t tid)
+{
+    if ((pieces & (pieces - 1u)) == 0u) {
+        const uint32_t sh = (uint32_t)__builtin_ctz(pieces);
+        const uint32_t lstep = (uint32_t)TILE_THREADS >> sh;
+        uint32_t l = tid >> sh;
+        const uint32_t pc = tid & (pieces - 1u);
+        const uint8_t* s = codes_st + l * ST_PITCH + pc * 16;
+        uint8_t* d = codes + (size_t)l * code_pitch + pc * 16;
+        const size_t dstep = (size_t)lstep * code_pitch;
+        for (; l < lines; l += lstep, s += lstep * ST_PITCH, d += dstep)
+            *reinterpret_cast<uint4*>(d) = *reinterpret_cast<const uint4*>(s);
+    } else {
+        for (uint32_t q = tid; q < lines * pieces; q += TILE_THREADS) {
+            const uint32_t l = q / pieces, pc = q - l * pieces;
+            *reinterpret_cast<uint4*>(codes + (size_t)l * code_pitch + pc * 16) =
+                *reinterpret_cast<const uint4*>(codes_st + l * ST_PITCH + pc * 16);
+        }
+    }
+    const bool word_ok = ((reinterpret_cast<uintptr_t>(scales) | scale_pitch) & (pieces - 1u)) == 0u;
+    if (pieces == 8u && word_ok) {
+        for (uint32_t l = tid; l < lines; l += TILE_THREADS)
+            *reinterpret_cast<uint2*>(scales + (size_t)l * scale_pitch) = *reinterpret_cast<const uint2*>(scales_st + l * 8);
+    } else if (pieces == 4u && word_ok) {
+        for (uint32_t l = tid; l < lines; l += TILE_THREADS)
+            *reinterpret_cast<uint32_t*>(scales + (size_t)l * scale_pitch) = *reinterpret_cast<const uint32_t*>(scales_st + l * 8);
+    } else {
+        for (uint32_t q = tid; q < lines * 8u; q += TILE_THREADS) {
+            const uint32_t l = q >> 3, pc = q & 7u;
+            if (pc < pieces) scales[(size_t)l * scale_pitch + pc] = scales_st[l * 8 + pc];
+        }
+    }
+}
+
 // SRC: 0 = FP32 source, 1 = bf16 source, 2 = packed row result given
 template <int SRC, bool ROW_SR, bool T_SR, bool FLOOR>
 __global__ __launch_bounds__(TILE_THREADS, 4) void quantize_tile_kernel(TileArgs a)
@@ -316,32 +359,13 @@ __global__ __launch_bounds__(TILE_THREADS, 4) void quantize_tile_kernel(TileArgs
     // ---- write the staged macro tile out: 16 bytes per lane, whole 128-byte lines ----
     const uint32_t ncols_here = min(macro_cols, a.cols - mcol0);    // multiples of 32
     const uint32_t nrows_here = min(macro_rows, a.rows - mrow0);    // multiples of 32
-    if (want_row) {
-        // row codes: nrows_here rows x ncols_here/2 bytes, in 16-byte pieces (32 columns each)
-        const uint32_t pieces = ncols_here >> 5;
-        for (uint32_t q = tid; q < nrows_here * pieces; q += TILE_THREADS) {
-            uint32_t r = q / pieces, pc = q - r * pieces;
-            uint4 v = *reinterpret_cast<const uint4*>(st + ST_ROW_OFF + r * ST_PITCH + pc * 16);
-            *reinterpret_cast<uint4*>(a.codes_row + (size_t)(mrow0 + r) * half_cols + (mcol0 >> 1) + pc * 16) = v;
-        }
-        for (uint32_t q = tid; q < nrows_here * pieces; q += TILE_THREADS) {
-            uint32_t r = q / pieces, pc = q - r * pieces;
-            a.scales_row[(size_t)(mrow0 + r) * grp_cols + (mcol0 >> 5) + pc] = st[ST_SROW_OFF + r * 8 + pc];
-        }
-    }
-    {
-        // transposed codes: ncols_here columns x nrows_here/2 bytes, in 16-byte pieces (32 rows each)
-        const uint32_t pieces = nrows_here >> 5;
-        for (uint32_t q = tid; q < ncols_here * pieces; q += TILE_THREADS) {
-            uint32_t cl = q / pieces, pc = q - cl * pieces;
-            uint4 v = *reinterpret_cast<const uint4*>(st + ST_COL_OFF + cl * ST_PITCH + pc * 16);
-            *reinterpret_cast<uint4*>(a.codes_t + (size_t)(mcol0 + cl) * half_rows + (mrow0 >> 1) + pc * 16) = v;
-        }
-        for (uint32_t q = tid; q < ncols_here * pieces; q += TILE_THREADS) {
-            uint32_t cl = q / pieces, pc = q - cl * pieces;
-            a.scales_t[(size_t)(mcol0 + cl) * grp_rows + (mrow0 >> 5) + pc] = st[ST_SCOL_OFF + cl * 8 + pc];
-        }
-    }
+    if (want_row)
+        write_staged(st + ST_ROW_OFF, st + ST_SROW_OFF, nrows_here, ncols_here >> 5,
+                     a.codes_row + (size_t)mrow0 * half_cols + (mcol0 >> 1), half_cols,
+                     a.scales_row + (size_t)mrow0 * grp_cols + (mcol0 >> 5), grp_cols, tid);
+    write_staged(st + ST_COL_OFF, st + ST_SCOL_OFF, ncols_here, nrows_here >> 5,
+                 a.codes_t + (size_t)mcol0 * half_rows + (mrow0 >> 1), half_rows,
+                 a.scales_t + (size_t)mcol0 * grp_rows + (mrow0 >> 5), grp_rows, tid);
 }
 
 // ---------------------------------------------------------------------------
