@@ -86,17 +86,23 @@ __device__ __forceinline__ uint32_t sr_code(float x, int e, uint32_t rinv)
     return ((mag + rinv) >> 22) | ((__float_as_uint(x) >> 28) & 8u);
 }
 
-// round_D that also hands back the rounded magnitude on the grid's bit layout, i.e.
-// (code & 7) << 22 = m * 2^-126, for the double quantization that follows.
+// round_D that also hands back the rounded value on the grid's bit layout with its sign,
+// i.e. sign | (code & 7) << 22 = +-m * 2^-126, for the double quantization that follows.
+// The sum keeps the sign in bit 31 (the magnitude stays below 2^25, so nothing carries into it, and
+// the -1 of a negative value only borrows from the low bits), which saves taking |v| apart first;
+// bits 30..25 of the sum are zero, so sum >> 28 is the sign nibble as it stands.
 template <bool FLOOR>
 __device__ __forceinline__ uint32_t rtn_code_keep(float x, int e, uint32_t& grid_bits)
 {
     uint32_t vb = __float_as_uint(__builtin_ldexpf(x, e));
-    uint32_t mag = vb & 0x7FFFFFFFu;
-    if (FLOOR) mag = mag > GRID_MAX_BITS ? GRID_MAX_BITS : mag;
-    uint32_t t = mag + 0x200000u + (uint32_t)((int32_t)vb >> 31);
+    if (FLOOR) {
+        uint32_t mag = vb & 0x7FFFFFFFu;
+        mag = mag > GRID_MAX_BITS ? GRID_MAX_BITS : mag;
+        vb = mag | (vb & 0x80000000u);
+    }
+    uint32_t t = vb + 0x200000u + (uint32_t)((int32_t)vb >> 31);
     grid_bits = t & 0xFFC00000u;
-    return (t >> 22) | ((vb >> 28) & 8u);
+    return ((t >> 22) & 7u) | (t >> 28);
 }
 
 template <bool FLOOR>
@@ -206,15 +212,25 @@ __device__ __forceinline__ uint32_t sr_field(const U4& r, int t)
 // The eight rounding addends ((65535 - r16) << 6) | 63 of an 8-element block, for sr_code().
 struct U8 { uint32_t w[8]; };
 
+// (16-bit field of w) * 64 + 63 in one instruction; HIGH selects the upper field.
+template <bool HIGH>
+__device__ __forceinline__ uint32_t field16_times64_plus63(uint32_t w)
+{
+    uint32_t r;
+    if (HIGH) asm("v_mad_u32_u16 %0, %1, 64, 63 op_sel:[1,0,0,0]" : "=v"(r) : "v"(w));
+    else      asm("v_mad_u32_u16 %0, %1, 64, 63" : "=v"(r) : "v"(w));
+    return r;
+}
+
 __device__ __forceinline__ U8 sr_addends(uint64_t blk, uint32_t tensor_id, uint32_t k0, uint32_t k1)
 {
     U4 r = sr_block(blk, tensor_id, k0, k1);
     U8 a;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        uint32_t inv = ~r.w[i];
-        a.w[2 * i] = ((inv & 0xFFFFu) << 6) | 63u;
-        a.w[2 * i + 1] = ((inv >> 16) << 6) | 63u;
+        uint32_t inv = ~r.w[i];                       // both 16-bit fields become 65535 - r16
+        a.w[2 * i] = field16_times64_plus63<false>(inv);
+        a.w[2 * i + 1] = field16_times64_plus63<true>(inv);
     }
     return a;
 }

@@ -306,11 +306,15 @@ __global__ __launch_bounds__(TILE_THREADS, 4) void quantize_tile_kernel(TileArgs
 #pragma unroll
                         for (int t = 0; t < 8; ++t) {
                             uint32_t gb;
-                            uint32_t code = ROW_SR ? sr_code_keep<FLOOR>(x[j].v[t], e, rnd.w[t], gb)
-                                                   : rtn_code_keep<FLOOR>(x[j].v[t], e, gb);
-                            pk |= code << (4 * t);
-                            float mag = __builtin_ldexpf(__uint_as_float(gb), (int)byte - 1);      // m * 2^s, exact
-                            x[j].v[t] = __builtin_copysignf(mag, x[j].v[t]);
+                            if (ROW_SR) {
+                                uint32_t code = sr_code_keep<FLOOR>(x[j].v[t], e, rnd.w[t], gb);
+                                pk |= code << (4 * t);
+                                float mag = __builtin_ldexpf(__uint_as_float(gb), (int)byte - 1);  // m * 2^s, exact
+                                x[j].v[t] = __builtin_copysignf(mag, x[j].v[t]);
+                            } else {
+                                pk |= rtn_code_keep<FLOOR>(x[j].v[t], e, gb) << (4 * t);           // gb carries the sign
+                                x[j].v[t] = __builtin_ldexpf(__uint_as_float(gb), (int)byte - 1);  // +-m * 2^s, exact
+                            }
                         }
                     } else {
                         pk = encode8<ROW_SR, FLOOR>(x[j], e, rnd);
