@@ -281,13 +281,22 @@ __global__ __launch_bounds__(TILE_THREADS, 4) void quantize_tile_kernel(TileArgs
                 }
             }
         } else {
+            if (mcol0 + tcol0 + 64 <= a.cols) {           // whole tile inside the matrix (uniform): no masking, no zero fill
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                x[j] = zero8();
-                if (ok) {
+                for (int j = 0; j < 4; ++j) {
                     int64_t off = (int64_t)(row0 + j) * a.ld + c;
                     if (SRC == 1) x[j] = load8(static_cast<const uint16_t*>(a.src) + off);
                     else          x[j] = load8(static_cast<const float*>(a.src) + off);
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    x[j] = zero8();
+                    if (ok) {
+                        int64_t off = (int64_t)(row0 + j) * a.ld + c;
+                        if (SRC == 1) x[j] = load8(static_cast<const uint16_t*>(a.src) + off);
+                        else          x[j] = load8(static_cast<const float*>(a.src) + off);
+                    }
                 }
             }
             // ---- 1x32 quantizer of the same elements ---------------------------
