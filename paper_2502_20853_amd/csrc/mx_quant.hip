@@ -152,8 +152,9 @@ __global__ __launch_bounds__(ROWS_THREADS) void ema_quantize_kernel(RowsArgs a)
 // ---------------------------------------------------------------------------
 // Transposed / fused quantizer.
 //
-// A workgroup of 8 waves owns a 256 x 256 macro tile of the source (256 x 64 for small
-// tensors); wave w owns rows [32w, 32w+32) of it and walks over its 32 x 64 tiles.
+// A workgroup of 8 waves owns a 256 x 128 macro tile of the source (256 x 64 for small tensors
+// and for the tiles of a sparsely filled last round); wave w owns rows [32w, 32w+32) of it and
+// walks over its 32 x 64 tiles.  The grid is one-dimensional over the macro tiles in row-major order.
 // Inside a tile, lane l holds rows 4*(l/8)+j (j = 0..3) x columns 8*(l%8)+t (t = 0..7):
 //   - each load instruction reads 8 full rows of 64 elements,
 //   - a 1x32 row group is 4 neighbouring lanes (DPP quad reduction),
@@ -181,8 +182,10 @@ struct TileArgs {
     int64_t ld;
     uint32_t rows, cols;
     int pre_quant;
-    int tiles_per_wave;    // 32 x 64 tiles a wave walks along the columns
-    int waves_c;           // waves of the workgroup side by side along the columns (1 or 2); 8 / waves_c along the rows
+    // 1-D grid over macro tiles in row-major order: the first n_wide workgroups own 256 x 128 tiles
+    // (two 32 x 64 tiles per wave), the rest own the two 256 x 64 halves of the tiles after those
+    uint32_t n_wide;
+    uint32_t wide_per_row; // 256 x 128 tiles per block of 256 rows = ceil(cols / 128)
     uint32_t k0, k1, tensor_id_t, tensor_id_row;
     uint64_t index_base;
 };
@@ -248,11 +251,17 @@ __global__ __launch_bounds__(TILE_THREADS, 4) void quantize_tile_kernel(TileArgs
     if (!SWITCH_MODES) set_round_mode_for<(ROW_SR || T_SR)>();
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int cc = lane & 7, rg = lane >> 3;
-    const int wr = a.waves_c == 2 ? wave >> 1 : wave;     // wave position inside the macro tile
-    const int wc = a.waves_c == 2 ? wave & 1 : 0;
-    const uint32_t macro_rows = 256u / a.waves_c, macro_cols = 64u * a.waves_c * a.tiles_per_wave;
-    const uint32_t mrow0 = blockIdx.y * macro_rows;       // macro tile origin
-    const uint32_t mcol0 = blockIdx.x * macro_cols;
+    const int wr = wave;                                  // wave position inside the macro tile
+    // macro tile of this workgroup (uniform): a wide one, or one half of a wide one
+    const bool wide = blockIdx.x < a.n_wide;
+    const uint32_t narrow = wide ? 0u : blockIdx.x - a.n_wide;
+    const uint32_t wide_index = wide ? blockIdx.x : a.n_wide + (narrow >> 1);
+    const uint32_t row_block = wide_index / a.wide_per_row;
+    const int tiles_per_wave = wide ? 2 : 1;
+    const uint32_t macro_rows = 256u, macro_cols = 64u * tiles_per_wave;
+    const uint32_t mrow0 = row_block * macro_rows;        // macro tile origin
+    const uint32_t mcol0 = (wide_index - row_block * a.wide_per_row) * 128u + (wide ? 0u : (narrow & 1u) * 64u);
+    if (mcol0 >= a.cols) return;                          // second half of a tile that is only 64 columns wide
     const bool wave_has_rows = mrow0 + wr * 32 < a.rows;
     const uint32_t lrow0 = wr * 32 + 4 * rg;              // first of this lane's 4 rows inside the macro tile
     const uint32_t row0 = mrow0 + lrow0;
@@ -260,8 +269,8 @@ __global__ __launch_bounds__(TILE_THREADS, 4) void quantize_tile_kernel(TileArgs
     const uint32_t half_rows = a.rows >> 1, grp_rows = a.rows >> 5;
     const uint32_t half_cols = a.cols >> 1, grp_cols = a.cols >> 5;
 
-    for (int ci = 0; ci < a.tiles_per_wave && wave_has_rows; ++ci) {
-        const uint32_t tcol0 = (wc * a.tiles_per_wave + ci) * 64;
+    for (int ci = 0; ci < tiles_per_wave && wave_has_rows; ++ci) {
+        const uint32_t tcol0 = ci * 64;
         const uint32_t lcol0 = tcol0 + cc * 8;            // first of this lane's 8 columns inside the macro tile
         const uint32_t c = mcol0 + lcol0;
         if (mcol0 + tcol0 >= a.cols) break;               // uniform over the wave
@@ -725,14 +734,20 @@ hipError_t launch_quantize_tile(const QuantTileParams& p, hipStream_t st)
     a.tensor_id_t = p.tensor_id_t; a.tensor_id_row = p.tensor_id_row; a.index_base = p.index_base;
     // Macro tile of a workgroup (8 waves): 256 rows x 128 columns (whole 128-byte lines of the
     // transposed codes, 64-byte pieces of the row codes; measured a few percent faster than
-    // 256 x 256, whose fewer, longer waves leave more slots idle in the last round), 256 x 64 for
-    // small tensors such as weights.
-    const int64_t tiles = (p.rows / 32) * ((p.cols + 63) / 64);
-    if (tiles >= 8192) { a.tiles_per_wave = 2; a.waves_c = 1; }
-    else               { a.tiles_per_wave = 1; a.waves_c = 1; }
-    const int64_t cols_per_block = 64 * a.tiles_per_wave * a.waves_c, rows_per_block = 256 / a.waves_c;
-    dim3 grid((unsigned)((p.cols + cols_per_block - 1) / cols_per_block),
-              (unsigned)((p.rows + rows_per_block - 1) / rows_per_block));
+    // 256 x 256), 256 x 64 for small tensors such as weights, where latency counts.
+    // Two workgroups fit a compute unit (LDS), so 512 run at a time and a launch proceeds in rounds
+    // of 512 equal tiles.  When the last round would be less than half full, its tiles are issued as
+    // their 256 x 64 halves: twice the workgroups, half the time, and the round ends earlier.
+    const uint32_t wide_per_row = (uint32_t)((p.cols + 127) / 128);
+    const uint32_t n_tiles = (uint32_t)((p.rows + 255) / 256) * wide_per_row;
+    const int64_t tiles32 = (p.rows / 32) * ((p.cols + 63) / 64);
+    uint32_t n_wide = 0;
+    if (tiles32 >= 8192) {
+        const uint32_t rem = n_tiles % 512u;
+        n_wide = (rem > 0u && rem <= 256u) ? n_tiles - rem : n_tiles;
+    }
+    a.n_wide = n_wide; a.wide_per_row = wide_per_row;
+    dim3 grid(n_wide + 2u * (n_tiles - n_wide));
     const bool row_sr = p.row_codes_in ? false : p.sr_row;
     if (p.floor_mode) {
         if (p.row_codes_in)  launch_tile_src<2, true>(a, row_sr, p.sr_t, grid, st);
