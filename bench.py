@@ -30,6 +30,11 @@ def parse():
     ap.add_argument("--cpu-sample-tokens", type=int, default=16384)
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "gemm_traffic.json"),
                     help="HBM bytes per GEMM launch measured with rocprofv3 --pmc, if present")
+    ap.add_argument("--event-every", type=int, default=5,
+                    help="record the per-kernel HIP events on every n-th timed step (an event between two "
+                         "launches costs about 3 us of idle chip, 5 %% of a step if every step carries them)")
+    ap.add_argument("--streams", type=int, default=1, choices=(1, 2),
+                    help="2: issue the weight / gradient quantizers and the dW product on a second HIP stream")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference dispatch for scaling rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters)")
@@ -100,30 +105,73 @@ def main():
     gemm_events, quant_events = [], []
     per_launch = {}                        # (layer index, op) -> list of (start, end) events
 
-    def run_step(seed, record):
-        for st, (X, W, dY) in zip(steps_obj, inputs):
-            B = mx.binding
+    side_stream = torch.cuda.Stream()                                # default priority
+    dw_ws = [torch.empty_like(st.workspace) for st in steps_obj]     # the dW product's own K-split workspace
+
+    def run_step(seed, record, side=None):
+        """One step.  With one stream every launch follows the previous one.  With two, the main
+        stream carries quant X -> fwd -> dX and the second one quant W -> quant dY -> dW of the same
+        layer; events express the data dependencies (fwd needs the weight codes, dX the gradient
+        codes, dW the transposed activation codes), so the tail of one kernel overlaps the next."""
+        B = mx.binding
+        main = torch.cuda.current_stream()
+        for li, (st, (X, W, dY)) in enumerate(zip(steps_obj, inputs)):
+            e = [ev() for _ in range(12)] if record else None
+            if side is None:
+                if record: e[0].record()
+                B.mx_quantize_transposed(X, B.ROUND_SR, 6, 1, True, B.ROUND_RTN, 1, seed=seed, out=(st.xtq, st.xts, st.xq, st.xs))
+                if record: e[1].record()
+                st.quantize_weight(W, seed)
+                if record: e[2].record()
+                B.mx_linear_fwd(st.xq, st.xs, st.wq, st.ws, out=st.y, workspace=st.workspace)
+                if record: e[3].record()
+                B.mx_quantize_transposed(dY, B.ROUND_SR, 5, 0, True, B.ROUND_SR, 3, seed=seed, out=(st.dytq, st.dyts, st.dyq, st.dys))
+                if record: e[4].record()
+                B.mx_linear_bwd_dx(st.dyq, st.dys, st.wtq, st.wts, out=st.dx, workspace=st.workspace)
+                if record: e[5].record()
+                B.mx_linear_bwd_dw(st.dytq, st.dyts, st.xtq, st.xts, out=st.dw, workspace=st.workspace)
+                if record: e[6].record()
+                spans = {"quant X": (0, 1), "quant W": (1, 2), "fwd": (2, 3), "quant dY": (3, 4), "dX": (4, 5), "dW": (5, 6)}
+            else:
+                fork, w_done, dy_done, x_done = torch.cuda.Event(), torch.cuda.Event(), torch.cuda.Event(), torch.cuda.Event()
+                fork.record(main)
+                side.wait_event(fork)                  # the layer's inputs are ready on the main stream
+                with torch.cuda.stream(side):
+                    if record: e[0].record()
+                    st.quantize_weight(W, seed)
+                    if record: e[1].record()
+                    w_done.record()
+                    if record: e[2].record()
+                    B.mx_quantize_transposed(dY, B.ROUND_SR, 5, 0, True, B.ROUND_SR, 3, seed=seed, out=(st.dytq, st.dyts, st.dyq, st.dys))
+                    if record: e[3].record()
+                    dy_done.record()
+                if record: e[4].record()
+                B.mx_quantize_transposed(X, B.ROUND_SR, 6, 1, True, B.ROUND_RTN, 1, seed=seed, out=(st.xtq, st.xts, st.xq, st.xs))
+                if record: e[5].record()
+                x_done.record(main)
+                main.wait_event(w_done)
+                if record: e[6].record()
+                B.mx_linear_fwd(st.xq, st.xs, st.wq, st.ws, out=st.y, workspace=st.workspace)
+                if record: e[7].record()
+                main.wait_event(dy_done)
+                if record: e[8].record()
+                B.mx_linear_bwd_dx(st.dyq, st.dys, st.wtq, st.wts, out=st.dx, workspace=st.workspace)
+                if record: e[9].record()
+                with torch.cuda.stream(side):
+                    side.wait_event(x_done)
+                    if record: e[10].record()
+                    B.mx_linear_bwd_dw(st.dytq, st.dyts, st.xtq, st.xts, out=st.dw, workspace=dw_ws[li])
+                    if record: e[11].record()
+                spans = {"quant W": (0, 1), "quant dY": (2, 3), "quant X": (4, 5), "fwd": (6, 7), "dX": (8, 9), "dW": (10, 11)}
             if record:
-                e = [ev() for _ in range(12)]
-                e[0].record()
-            B.mx_quantize_transposed(X, B.ROUND_SR, 6, 1, True, B.ROUND_RTN, 1, seed=seed, out=(st.xtq, st.xts, st.xq, st.xs))
-            if record: e[1].record()
-            st.quantize_weight(W, seed)
-            if record: e[2].record()
-            B.mx_linear_fwd(st.xq, st.xs, st.wq, st.ws, out=st.y, workspace=st.workspace)
-            if record: e[3].record()
-            B.mx_quantize_transposed(dY, B.ROUND_SR, 5, 0, True, B.ROUND_SR, 3, seed=seed, out=(st.dytq, st.dyts, st.dyq, st.dys))
-            if record: e[4].record()
-            B.mx_linear_bwd_dx(st.dyq, st.dys, st.wtq, st.wts, out=st.dx, workspace=st.workspace)
-            if record: e[5].record()
-            B.mx_linear_bwd_dw(st.dytq, st.dyts, st.xtq, st.xts, out=st.dw, workspace=st.workspace)
-            if record:
-                e[6].record()
-                quant_events.extend([(e[0], e[1]), (e[1], e[2]), (e[3], e[4])])
-                gemm_events.extend([(e[2], e[3]), (e[4], e[5]), (e[5], e[6])])
-                li = steps_obj.index(st)
-                for op, k in (("quant X", 0), ("quant W", 1), ("fwd", 2), ("quant dY", 3), ("dX", 4), ("dW", 5)):
-                    per_launch.setdefault((li, op), []).append((e[k], e[k + 1]))
+                quant_events.extend([(e[a], e[b]) for k, (a, b) in spans.items() if k.startswith("quant")])
+                gemm_events.extend([(e[a], e[b]) for k, (a, b) in spans.items() if not k.startswith("quant")])
+                for op, (a, b) in spans.items():
+                    per_launch.setdefault((li, op), []).append((e[a], e[b]))
+        if side is not None:
+            join = torch.cuda.Event()
+            join.record(side)
+            main.wait_event(join)                      # the step ends when both streams have ended
 
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")      # 1 GiB read, 1 GiB written
@@ -133,15 +181,32 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    timed_side = side_stream if args.streams == 2 else None
     for w in range(args.warmup):
-        run_step(w, False)
+        run_step(w, False, timed_side)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    n_recorded = 0
     for s in range(args.steps):
-        run_step(1000 + s, True)           # events are recorded on the launch stream (torch's current stream)
+        rec = s % max(1, args.event_every) == 0
+        n_recorded += rec
+        run_step(1000 + s, rec, timed_side)    # events are recorded on the stream each kernel is launched on
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt * 1e3 / args.steps
+
+    # the same steps under the other schedule, after the timed region, for comparison: with two
+    # streams the tails of the products overlap the next kernels, but a kernel's event-to-event time
+    # then includes the time it shares the chip, so the per-kernel figures come from one stream
+    other_side = None if args.streams == 2 else side_stream
+    for w in range(2):
+        run_step(w, False, other_side)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for s in range(args.steps):
+        run_step(2000 + s, False, other_side)
+    torch.cuda.synchronize()
+    other_ms = (time.perf_counter() - t1) * 1e3 / args.steps
 
     # Q-EMA weight quantizer (Sec. 5), outside the timed region: the four weights of the block, one
     # update + quantization each, as a training step with Q-EMA would issue them
@@ -240,8 +305,8 @@ def main():
                     "hbm_frac": round(n_par * bytes_per / us / 1e3 / PEAK_HBM_GBS, 3)})
     del w_all, g_all, fac_all, ost
 
-    gemm_ms = sum(a.elapsed_time(b) for a, b in gemm_events) / args.steps      # per step, all 12 products
-    quant_ms = sum(a.elapsed_time(b) for a, b in quant_events) / args.steps
+    gemm_ms = sum(a.elapsed_time(b) for a, b in gemm_events) / n_recorded      # per step, all 12 products
+    quant_ms = sum(a.elapsed_time(b) for a, b in quant_events) / n_recorded
     n_gemm = 3 * len(layers)
     achieved = total_flops / (gemm_ms * 1e-3) / 1e12
     traffic = None
@@ -297,7 +362,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": "%s: N=%d tokens, layers %s, Y/dX bf16, dW f32" % (
             args.workload, layers[0][1], ",".join("%s %d->%d" % (n, d, c) for (n, _, d, c) in layers)),
-            "quantizers": "Q1,Q2 RTN; Q3..Q6 stochastic (Philox4x32-10); truncation-free scale; double quantization"},
+            "quantizers": "Q1,Q2 RTN; Q3..Q6 stochastic (Philox4x32-10); truncation-free scale; double quantization",
+            "streams": args.streams, "steps_with_kernel_events": n_recorded},
         "roofline": {"bound": "mfma", "kernel": "mx_gemm_pingpong_kernel (12 launches per step)",
                      "achieved": achieved, "peak": PEAK_FP4_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_FP4_TFLOPS,
@@ -310,6 +376,8 @@ def main():
         "launches": launches,
         "qema_weight_quant": qema,
         "oscillation_detection": osc,
+        "other_schedule": {"streams": 3 - args.streams, "ms_per_step": other_ms,
+                           "value": total_flops / (other_ms * 1e-3) / 1e12, "unit": "TFLOP/s"},
         "oscillation_diagnostics": diag,
         "ramping_adamw": opt,
     }
