@@ -33,6 +33,9 @@ def parse():
     ap.add_argument("--event-every", type=int, default=5,
                     help="record the per-kernel HIP events on every n-th timed step (an event between two "
                          "launches costs about 3 us of idle chip, 5 %% of a step if every step carries them)")
+    ap.add_argument("--no-other-schedule", action="store_true",
+                    help="skip the comparison pass under the other stream schedule (for profiler runs: its "
+                         "overlapped kernels would mix into the per-kernel statistics)")
     ap.add_argument("--streams", type=int, default=1, choices=(1, 2),
                     help="2: issue the weight / gradient quantizers and the dW product on a second HIP stream")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -198,15 +201,17 @@ def main():
     # the same steps under the other schedule, after the timed region, for comparison: with two
     # streams the tails of the products overlap the next kernels, but a kernel's event-to-event time
     # then includes the time it shares the chip, so the per-kernel figures come from one stream
-    other_side = None if args.streams == 2 else side_stream
-    for w in range(2):
-        run_step(w, False, other_side)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    for s in range(args.steps):
-        run_step(2000 + s, False, other_side)
-    torch.cuda.synchronize()
-    other_ms = (time.perf_counter() - t1) * 1e3 / args.steps
+    other_ms = None
+    if not args.no_other_schedule:
+        other_side = None if args.streams == 2 else side_stream
+        for w in range(2):
+            run_step(w, False, other_side)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for s in range(args.steps):
+            run_step(2000 + s, False, other_side)
+        torch.cuda.synchronize()
+        other_ms = (time.perf_counter() - t1) * 1e3 / args.steps
 
     # Q-EMA weight quantizer (Sec. 5), outside the timed region: the four weights of the block, one
     # update + quantization each, as a training step with Q-EMA would issue them
@@ -376,8 +381,9 @@ def main():
         "launches": launches,
         "qema_weight_quant": qema,
         "oscillation_detection": osc,
-        "other_schedule": {"streams": 3 - args.streams, "ms_per_step": other_ms,
-                           "value": total_flops / (other_ms * 1e-3) / 1e12, "unit": "TFLOP/s"},
+        "other_schedule": None if other_ms is None else {
+            "streams": 3 - args.streams, "ms_per_step": other_ms,
+            "value": total_flops / (other_ms * 1e-3) / 1e12, "unit": "TFLOP/s"},
         "oscillation_diagnostics": diag,
         "ramping_adamw": opt,
     }
