@@ -122,9 +122,7 @@ def main():
             e = [ev() for _ in range(12)] if record else None
             if side is None:
                 if record: e[0].record()
-                B.mx_quantize_transposed(X, B.ROUND_SR, 6, 1, True, B.ROUND_RTN, 1, seed=seed, out=(st.xtq, st.xts, st.xq, st.xs))
-                if record: e[1].record()
-                st.quantize_weight(W, seed)
+                st.quantize_inputs(X, W, seed)         # Q1/Q6 of X and Q2/Q4 of W in one launch
                 if record: e[2].record()
                 B.mx_linear_fwd(st.xq, st.xs, st.wq, st.ws, out=st.y, workspace=st.workspace)
                 if record: e[3].record()
@@ -134,7 +132,7 @@ def main():
                 if record: e[5].record()
                 B.mx_linear_bwd_dw(st.dytq, st.dyts, st.xtq, st.xts, out=st.dw, workspace=st.workspace)
                 if record: e[6].record()
-                spans = {"quant X": (0, 1), "quant W": (1, 2), "fwd": (2, 3), "quant dY": (3, 4), "dX": (4, 5), "dW": (5, 6)}
+                spans = {"quant X+W": (0, 2), "fwd": (2, 3), "quant dY": (3, 4), "dX": (4, 5), "dW": (5, 6)}
             else:
                 fork, w_done, dy_done, x_done = torch.cuda.Event(), torch.cuda.Event(), torch.cuda.Event(), torch.cuda.Event()
                 fork.record(main)
@@ -330,9 +328,10 @@ def main():
         name, N, D, C = layers[li]
         us = sum(a.elapsed_time(b) for a, b in evs) / len(evs) * 1e3
         if op.startswith("quant"):
-            r, c = {"quant X": (N, D), "quant W": (C, D), "quant dY": (N, C)}[op]
-            launches.append({"layer": name, "op": op, "shape": [r, c], "us": round(us, 1),
-                             "GB/s": round(quant_bytes(r, c, sb) / us / 1e3, 1)})
+            shapes = {"quant X": [(N, D)], "quant W": [(C, D)], "quant X+W": [(N, D), (C, D)], "quant dY": [(N, C)]}[op]
+            qb = sum(quant_bytes(r, c, sb) for r, c in shapes)
+            launches.append({"layer": name, "op": op, "shape": [list(x) for x in shapes] if len(shapes) > 1 else list(shapes[0]),
+                             "us": round(us, 1), "GB/s": round(qb / us / 1e3, 1)})
         else:
             m, n, k, ob = {"fwd": (N, C, D, 2), "dX": (N, D, C, 2), "dW": (C, D, N, 4)}[op]
             fl = 2.0 * m * n * k

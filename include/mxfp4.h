@@ -105,6 +105,38 @@ int mx_quantize_transposed(const void* src, int dtype, int64_t rows, int64_t col
                 void* stream);
 
 /*
+ * Several mx_quantize_transposed requests in one launch (Sec. 3.3 runs two of them back to back in
+ * the forward pass: the activation and the weight).  One kernel serves the whole batch, so the small
+ * tensor costs no launch of its own and its workgroups fill the last, partly empty round of the
+ * large one's.  Results are those of the separate calls, byte for byte.
+ *   jobs    HOST array of `count` requests, 1 <= count <= MX_TRANSPOSED_BATCH_MAX; every field has the
+ *           meaning, layout and alignment of the argument of the same name of mx_quantize_transposed
+ *   round_t, round_row, scale_mode   shared by all jobs
+ * All jobs must read the same kind of source: all F32, all BF16 (else MX_ERR_DTYPE), or all from
+ * row_codes_in (else MX_ERR_MODE).  Any error of a single job is returned as that call would return
+ * it, and nothing is launched.
+ */
+#define MX_TRANSPOSED_BATCH_MAX 4
+typedef struct mx_transposed_job {
+    const void* src;
+    int dtype;
+    int64_t rows, cols, ld;
+    uint8_t* codes_t;
+    uint8_t* scales_t;
+    uint32_t tensor_id_t;
+    int pre_quant;
+    uint8_t* codes_row;
+    uint8_t* scales_row;
+    uint32_t tensor_id_row;
+    const uint8_t* row_codes_in;
+    const uint8_t* row_scales_in;
+    uint64_t seed;
+    uint64_t index_base;
+} mx_transposed_job;
+int mx_quantize_transposed_batch(const mx_transposed_job* jobs, int count,
+                int round_t, int round_row, int scale_mode, void* stream);
+
+/*
  * The three products (Sec. 3.3, Eqs. 3-5), FP32 accumulation on the
  * block-scaled FP4 matrix cores.  X[N x D], W[C x D], Y[N x C].  Every operand
  * is packed along the product's contraction dimension, which must be a

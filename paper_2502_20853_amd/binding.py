@@ -24,11 +24,21 @@ ROUND_RTN, ROUND_SR = 0, 1
 SCALE_TRUNCFREE, SCALE_FLOOR = 0, 1
 GEMM_FWD, GEMM_BWD_DX, GEMM_BWD_DW = 0, 1, 2
 
-EXPORTS = ["mx_quantize", "mx_quantize_transposed", "mx_linear_fwd", "mx_linear_bwd_dx",
+EXPORTS = ["mx_quantize", "mx_quantize_transposed", "mx_quantize_transposed_batch", "mx_linear_fwd", "mx_linear_bwd_dx",
            "mx_linear_bwd_dw", "mx_ema_weight_quant", "mx_linear_workspace_bytes",
            "mx_oscillation_accumulate", "mx_ramping_factor",
            "mx_ramping_adamw_step", "mx_quant_confidence", "mx_rate_of_change_workspace_bytes", "mx_rate_of_change_step",
            "mx_dequantize", "mx_calibration_copy", "mx_last_hip_error", "mx_version"]
+
+
+class _TransposedJob(ctypes.Structure):
+    """mx_transposed_job of include/mxfp4.h."""
+    _fields_ = [("src", ctypes.c_void_p), ("dtype", ctypes.c_int), ("rows", ctypes.c_int64), ("cols", ctypes.c_int64),
+                ("ld", ctypes.c_int64), ("codes_t", ctypes.c_void_p), ("scales_t", ctypes.c_void_p),
+                ("tensor_id_t", ctypes.c_uint32), ("pre_quant", ctypes.c_int), ("codes_row", ctypes.c_void_p),
+                ("scales_row", ctypes.c_void_p), ("tensor_id_row", ctypes.c_uint32),
+                ("row_codes_in", ctypes.c_void_p), ("row_scales_in", ctypes.c_void_p),
+                ("seed", ctypes.c_uint64), ("index_base", ctypes.c_uint64)]
 
 
 class MxError(RuntimeError):
@@ -169,6 +179,26 @@ def mx_quantize_transposed(src, round_t=ROUND_SR, tensor_id_t=0, pre_quant=1, wa
                                       scale_mode, seed, index_base, _stream(stream))
     _check("mx_quantize_transposed", rc)
     return codes_t, scales_t, codes_row, scales_row
+
+
+def mx_quantize_transposed_batch(jobs, round_t=ROUND_SR, round_row=ROUND_RTN, scale_mode=SCALE_TRUNCFREE, stream=None):
+    """Several transposed quantizations in one launch.  jobs: list of dicts with the keys
+    src, out=(codes_t, scales_t, codes_row, scales_row) and optionally tensor_id_t, tensor_id_row,
+    pre_quant (1), seed (0), index_base (0); the roundings and the scale rule are shared."""
+    arr = (_TransposedJob * len(jobs))()
+    for j, job in zip(arr, jobs):
+        src = job["src"]
+        rows, cols, ld = _matrix(src)
+        codes_t, scales_t, codes_row, scales_row = job["out"]
+        j.src, j.dtype, j.rows, j.cols, j.ld = src.data_ptr(), _src_dtype(src), rows, cols, ld
+        j.codes_t, j.scales_t = codes_t.data_ptr(), scales_t.data_ptr()
+        j.codes_row = codes_row.data_ptr() if codes_row is not None else None
+        j.scales_row = scales_row.data_ptr() if scales_row is not None else None
+        j.tensor_id_t, j.tensor_id_row = job.get("tensor_id_t", 0), job.get("tensor_id_row", 0)
+        j.pre_quant, j.seed, j.index_base = job.get("pre_quant", 1), job.get("seed", 0), job.get("index_base", 0)
+        j.row_codes_in = j.row_scales_in = None
+    rc = lib().mx_quantize_transposed_batch(arr, len(jobs), round_t, round_row, scale_mode, _stream(stream))
+    _check("mx_quantize_transposed_batch", rc)
 
 
 def mx_linear_workspace_bytes(which, N, C, D):

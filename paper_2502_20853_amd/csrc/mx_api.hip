@@ -88,12 +88,13 @@ int mx_quantize(const void* src, int dtype, int64_t rows, int64_t cols, int64_t 
     return hip_status(mxl::launch_quantize_rows(p, static_cast<hipStream_t>(stream)));
 }
 
-int mx_quantize_transposed(const void* src, int dtype, int64_t rows, int64_t cols, int64_t ld,
+// Checks one transposed-quantizer request and fills the launcher's parameters.
+static int make_transposed_job(const void* src, int dtype, int64_t rows, int64_t cols, int64_t ld,
                 uint8_t* codes_t, uint8_t* scales_t, int round_t, uint32_t tensor_id_t,
                 int pre_quant, uint8_t* codes_row, uint8_t* scales_row,
                 int round_row, uint32_t tensor_id_row,
                 const uint8_t* row_codes_in, const uint8_t* row_scales_in,
-                int scale_mode, uint64_t seed, uint64_t index_base, void* stream)
+                int scale_mode, uint64_t seed, uint64_t index_base, mxl::QuantTileParams& p)
 {
     if (!codes_t || !scales_t) return MX_ERR_NULL;
     if ((codes_row == nullptr) != (scales_row == nullptr)) return MX_ERR_NULL;
@@ -118,14 +119,48 @@ int mx_quantize_transposed(const void* src, int dtype, int64_t rows, int64_t col
     }
     const bool any_sr = round_t == MX_ROUND_SR || (!given && round_row == MX_ROUND_SR && (pre_quant || codes_row));
     if (any_sr && (index_base & 7u) != 0) return MX_ERR_ALIGN;
-    mxl::QuantTileParams p{};
-    p.src = src; p.bf16 = dtype == MX_DTYPE_BF16; p.rows = rows; p.cols = cols; p.ld = ld;
+    p = mxl::QuantTileParams{};
+    p.src = src; p.bf16 = !given && dtype == MX_DTYPE_BF16; p.rows = rows; p.cols = cols; p.ld = ld;
     p.codes_t = codes_t; p.scales_t = scales_t; p.sr_t = round_t == MX_ROUND_SR; p.tensor_id_t = tensor_id_t;
     p.pre_quant = pre_quant == 1; p.codes_row = codes_row; p.scales_row = scales_row;
     p.sr_row = round_row == MX_ROUND_SR; p.tensor_id_row = tensor_id_row;
     p.row_codes_in = row_codes_in; p.row_scales_in = row_scales_in;
     p.floor_mode = scale_mode == MX_SCALE_FLOOR; p.seed = seed; p.index_base = index_base;
+    return MX_OK;
+}
+
+int mx_quantize_transposed(const void* src, int dtype, int64_t rows, int64_t cols, int64_t ld,
+                uint8_t* codes_t, uint8_t* scales_t, int round_t, uint32_t tensor_id_t,
+                int pre_quant, uint8_t* codes_row, uint8_t* scales_row,
+                int round_row, uint32_t tensor_id_row,
+                const uint8_t* row_codes_in, const uint8_t* row_scales_in,
+                int scale_mode, uint64_t seed, uint64_t index_base, void* stream)
+{
+    mxl::QuantTileParams p;
+    int rc = make_transposed_job(src, dtype, rows, cols, ld, codes_t, scales_t, round_t, tensor_id_t, pre_quant,
+                                 codes_row, scales_row, round_row, tensor_id_row, row_codes_in, row_scales_in,
+                                 scale_mode, seed, index_base, p);
+    if (rc != MX_OK) return rc;
     return hip_status(mxl::launch_quantize_tile(p, static_cast<hipStream_t>(stream)));
+}
+
+int mx_quantize_transposed_batch(const mx_transposed_job* jobs, int count,
+                int round_t, int round_row, int scale_mode, void* stream)
+{
+    if (!jobs) return MX_ERR_NULL;
+    if (count < 1 || count > MX_TRANSPOSED_BATCH_MAX) return MX_ERR_SHAPE;
+    mxl::QuantTileParams p[MX_TRANSPOSED_BATCH_MAX];
+    for (int j = 0; j < count; ++j) {
+        const mx_transposed_job& q = jobs[j];
+        int rc = make_transposed_job(q.src, q.dtype, q.rows, q.cols, q.ld, q.codes_t, q.scales_t, round_t, q.tensor_id_t,
+                                     q.pre_quant, q.codes_row, q.scales_row, round_row, q.tensor_id_row,
+                                     q.row_codes_in, q.row_scales_in, scale_mode, q.seed, q.index_base, p[j]);
+        if (rc != MX_OK) return rc;
+        // one kernel serves the launch: the jobs must read the same kind of source
+        if ((p[j].row_codes_in != nullptr) != (p[0].row_codes_in != nullptr)) return MX_ERR_MODE;
+        if (p[j].bf16 != p[0].bf16) return MX_ERR_DTYPE;
+    }
+    return hip_status(mxl::launch_quantize_tile_batch(p, count, static_cast<hipStream_t>(stream)));
 }
 
 int mx_linear_fwd(const uint8_t* xq, const uint8_t* xs, const uint8_t* wq, const uint8_t* ws,

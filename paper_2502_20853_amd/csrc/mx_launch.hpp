@@ -57,6 +57,8 @@ struct GemmParams {
 hipError_t launch_quantize_rows(const QuantRowsParams& p, hipStream_t st);
 hipError_t launch_ema_quantize(const QuantRowsParams& p, float* ema, float beta, int update_ema, hipStream_t st);
 hipError_t launch_quantize_tile(const QuantTileParams& p, hipStream_t st);
+// Up to 4 tensors in one launch; they must share source kind, roundings and scale rule.
+hipError_t launch_quantize_tile_batch(const QuantTileParams* jobs, int count, hipStream_t st);
 hipError_t launch_dequantize(const uint8_t* codes, const uint8_t* scales, int64_t rows, int64_t cols,
                              float* out, hipStream_t st);
 

@@ -239,10 +239,24 @@ __device__ __forceinline__ void write_staged(const uint8_t* codes_st, const uint
     }
 }
 
+// Up to TILE_BATCH_MAX tensors per launch (e.g. the activation and the weight of a layer: one launch,
+// and the small tensor's workgroups fill the last round of the large one's).  first[j] is the first
+// workgroup of job j (0xFFFFFFFF for unused slots); all jobs share the template parameters.
+constexpr int TILE_BATCH_MAX = 4;
+struct TileBatch {
+    TileArgs job[TILE_BATCH_MAX];
+    uint32_t first[TILE_BATCH_MAX];
+};
+
 // SRC: 0 = FP32 source, 1 = bf16 source, 2 = packed row result given
 template <int SRC, bool ROW_SR, bool T_SR, bool FLOOR>
-__global__ __launch_bounds__(TILE_THREADS, 4) void quantize_tile_kernel(TileArgs a)
+__global__ __launch_bounds__(TILE_THREADS, 4) void quantize_tile_kernel(TileBatch batch)
 {
+    uint32_t job = 0;
+#pragma unroll
+    for (int i = 1; i < TILE_BATCH_MAX; ++i) job += blockIdx.x >= batch.first[i] ? 1u : 0u;
+    const TileArgs a = batch.job[job];
+    const uint32_t block = blockIdx.x - batch.first[job];
     __shared__ __attribute__((aligned(16))) uint8_t st[ST_BYTES];
     // FP32 sources need the rounding mode of each rule (switched per phase when they differ).
     // bf16 and packed sources scale exactly wherever a round_D threshold is near (8 significant
@@ -253,9 +267,9 @@ __global__ __launch_bounds__(TILE_THREADS, 4) void quantize_tile_kernel(TileArgs
     const int cc = lane & 7, rg = lane >> 3;
     const int wr = wave;                                  // wave position inside the macro tile
     // macro tile of this workgroup (uniform): a wide one, or one half of a wide one
-    const bool wide = blockIdx.x < a.n_wide;
-    const uint32_t narrow = wide ? 0u : blockIdx.x - a.n_wide;
-    const uint32_t wide_index = wide ? blockIdx.x : a.n_wide + (narrow >> 1);
+    const bool wide = block < a.n_wide;
+    const uint32_t narrow = wide ? 0u : block - a.n_wide;
+    const uint32_t wide_index = wide ? block : a.n_wide + (narrow >> 1);
     const uint32_t row_block = wide_index / a.wide_per_row;
     const int tiles_per_wave = wide ? 2 : 1;
     const uint32_t macro_rows = 256u, macro_cols = 64u * tiles_per_wave;
@@ -711,7 +725,7 @@ hipError_t launch_ema_quantize(const QuantRowsParams& p, float* ema, float beta,
 }
 
 template <int SRC, bool FL>
-static void launch_tile_src(const TileArgs& a, bool row_sr, bool t_sr, dim3 grid, hipStream_t st)
+static void launch_tile_src(const TileBatch& a, bool row_sr, bool t_sr, dim3 grid, hipStream_t st)
 {
     dim3 block(TILE_THREADS);
     if (row_sr) {
@@ -723,9 +737,10 @@ static void launch_tile_src(const TileArgs& a, bool row_sr, bool t_sr, dim3 grid
     }
 }
 
-hipError_t launch_quantize_tile(const QuantTileParams& p, hipStream_t st)
+// Fills the kernel arguments of one tensor; returns its number of workgroups.
+static uint32_t make_tile_args(const QuantTileParams& p, TileArgs& a)
 {
-    TileArgs a{};
+    a = TileArgs{};
     a.src = p.src; a.row_codes_in = p.row_codes_in; a.row_scales_in = p.row_scales_in;
     a.codes_t = p.codes_t; a.scales_t = p.scales_t; a.codes_row = p.codes_row; a.scales_row = p.scales_row;
     a.ld = p.ld; a.rows = (uint32_t)p.rows; a.cols = (uint32_t)p.cols;
@@ -747,18 +762,43 @@ hipError_t launch_quantize_tile(const QuantTileParams& p, hipStream_t st)
         n_wide = (rem > 0u && rem <= 256u) ? n_tiles - rem : n_tiles;
     }
     a.n_wide = n_wide; a.wide_per_row = wide_per_row;
-    dim3 grid(n_wide + 2u * (n_tiles - n_wide));
+    return n_wide + 2u * (n_tiles - n_wide);
+}
+
+hipError_t launch_quantize_tile_batch(const QuantTileParams* jobs, int count, hipStream_t st)
+{
+    if (count < 1 || count > TILE_BATCH_MAX) return hipErrorInvalidValue;
+    const QuantTileParams& p = jobs[0];
     const bool row_sr = p.row_codes_in ? false : p.sr_row;
+    TileBatch b{};
+    uint32_t blocks = 0;
+    for (int j = 0; j < TILE_BATCH_MAX; ++j) {
+        b.first[j] = 0xFFFFFFFFu;
+        if (j >= count) continue;
+        const QuantTileParams& q = jobs[j];
+        // one kernel instance serves the launch: source kind, roundings and scale rule are shared
+        if ((q.row_codes_in != nullptr) != (p.row_codes_in != nullptr) || q.bf16 != p.bf16 || q.sr_t != p.sr_t ||
+            (q.row_codes_in ? false : q.sr_row) != row_sr || q.floor_mode != p.floor_mode)
+            return hipErrorInvalidValue;
+        b.first[j] = blocks;
+        blocks += make_tile_args(q, b.job[j]);
+    }
+    dim3 grid(blocks);
     if (p.floor_mode) {
-        if (p.row_codes_in)  launch_tile_src<2, true>(a, row_sr, p.sr_t, grid, st);
-        else if (p.bf16)     launch_tile_src<1, true>(a, row_sr, p.sr_t, grid, st);
-        else                 launch_tile_src<0, true>(a, row_sr, p.sr_t, grid, st);
+        if (p.row_codes_in)  launch_tile_src<2, true>(b, row_sr, p.sr_t, grid, st);
+        else if (p.bf16)     launch_tile_src<1, true>(b, row_sr, p.sr_t, grid, st);
+        else                 launch_tile_src<0, true>(b, row_sr, p.sr_t, grid, st);
     } else {
-        if (p.row_codes_in)  launch_tile_src<2, false>(a, row_sr, p.sr_t, grid, st);
-        else if (p.bf16)     launch_tile_src<1, false>(a, row_sr, p.sr_t, grid, st);
-        else                 launch_tile_src<0, false>(a, row_sr, p.sr_t, grid, st);
+        if (p.row_codes_in)  launch_tile_src<2, false>(b, row_sr, p.sr_t, grid, st);
+        else if (p.bf16)     launch_tile_src<1, false>(b, row_sr, p.sr_t, grid, st);
+        else                 launch_tile_src<0, false>(b, row_sr, p.sr_t, grid, st);
     }
     return hipGetLastError();
+}
+
+hipError_t launch_quantize_tile(const QuantTileParams& p, hipStream_t st)
+{
+    return launch_quantize_tile_batch(&p, 1, st);
 }
 
 hipError_t launch_calibration_copy(void* dst, const void* src, size_t bytes, hipStream_t st)

@@ -48,10 +48,20 @@ class MxLinearStep:
             B.mx_quantize_transposed(W, B.ROUND_SR, Q4, 1, True, B.ROUND_RTN, Q2, scale_mode=self.scale_mode,
                                      seed=seed, out=(self.wtq, self.wts, self.wq, self.ws))
 
+    def quantize_inputs(self, X, W, seed):
+        """Q1/Q6 of X and Q2/Q4 of W: one launch when both are the same kind of source, else two."""
+        if not self.qema and X.dtype == W.dtype:
+            B.mx_quantize_transposed_batch(
+                [{"src": X, "out": (self.xtq, self.xts, self.xq, self.xs), "tensor_id_t": Q6, "tensor_id_row": Q1, "seed": seed},
+                 {"src": W, "out": (self.wtq, self.wts, self.wq, self.ws), "tensor_id_t": Q4, "tensor_id_row": Q2, "seed": seed}],
+                B.ROUND_SR, B.ROUND_RTN, self.scale_mode)
+        else:
+            B.mx_quantize_transposed(X, B.ROUND_SR, Q6, 1, True, B.ROUND_RTN, Q1, scale_mode=self.scale_mode,
+                                     seed=seed, out=(self.xtq, self.xts, self.xq, self.xs))
+            self.quantize_weight(W, seed)
+
     def forward(self, X, W, seed):
-        B.mx_quantize_transposed(X, B.ROUND_SR, Q6, 1, True, B.ROUND_RTN, Q1, scale_mode=self.scale_mode,
-                                 seed=seed, out=(self.xtq, self.xts, self.xq, self.xs))
-        self.quantize_weight(W, seed)
+        self.quantize_inputs(X, W, seed)
         return B.mx_linear_fwd(self.xq, self.xs, self.wq, self.ws, out=self.y, workspace=self.workspace)
 
     def backward(self, dY, seed):

@@ -184,3 +184,33 @@ def test_ramping_adamw_rejects(L):
     assert a(b1=1.0) == -4 and a(b2=0.0) == -4 and a(lr=-1.0) == -4 and a(eps=float("nan")) == -4 and a(wd=-0.1) == -4
     assert a(w=FAKE + 4) == -5 and a(u=FAKE + 8) == -5 and a(fac=FAKE + 4) == -5 and a(g=FAKE + 8) == -5
     assert a(g=FAKE + 8, gd=1) != -5                   # BF16 gradients need 8-byte alignment only
+
+
+def test_transposed_batch_rejects(L):
+    import ctypes
+    from paper_2502_20853_amd.binding import _TransposedJob
+
+    def job(**kw):
+        j = _TransposedJob()
+        j.src, j.dtype, j.rows, j.cols, j.ld = FAKE, 0, 64, 64, 64
+        j.codes_t, j.scales_t, j.codes_row, j.scales_row = FAKE, FAKE, FAKE, FAKE
+        j.tensor_id_t, j.tensor_id_row, j.pre_quant = 6, 1, 1
+        j.row_codes_in = j.row_scales_in = None
+        j.seed, j.index_base = 0, 0
+        for k, v in kw.items():
+            setattr(j, k, v)
+        return j
+
+    def call(jobs, round_t=1, round_row=0, mode=0):
+        arr = (_TransposedJob * max(1, len(jobs)))(*jobs)
+        return L.mx_quantize_transposed_batch(arr, len(jobs), round_t, round_row, mode, P(0))
+    assert L.mx_quantize_transposed_batch(None, 1, 1, 0, 0, P(0)) == -1
+    assert call([]) == -2 and call([job()] * 5) == -2
+    assert call([job(), job(codes_t=None)]) == -1                  # a job's own error comes back as is
+    assert call([job(), job(rows=48)]) == -2
+    assert call([job(), job(src=FAKE + 4)]) == -5
+    assert call([job()], round_t=7) == -4 and call([job()], mode=3) == -4
+    assert call([job(), job(dtype=1, ld=64)]) == -3                # F32 and BF16 sources do not mix
+    given = job(src=None, codes_row=None, scales_row=None, row_codes_in=FAKE, row_scales_in=FAKE)
+    assert call([job(), given]) == -4                              # nor a source with a given row result
+    assert call([job(index_base=4)]) == -5                         # stochastic streams start on a block of 8

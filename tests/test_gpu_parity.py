@@ -668,3 +668,30 @@ def test_ramping_adamw_matches_oracle(mx, orc, grad_dtype):
         mx.mx_ramping_adamw_step(w, dev(g), st, None, lr, b1, b2, eps, wd)
     assert np.all(host(st.updates) == 4)
     assert np.abs(host(w).ravel().astype(np.float64) - ost["w"]).max() <= 4 * (2.0 ** -23 * np.abs(W0).max() + 2e-6 * lr)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_transposed_batch_equals_separate_calls(mx, orc, dtype):
+    """mx_quantize_transposed_batch on (activation, weight, a third ragged tensor): every output byte
+    equals the separate calls' and the oracle's; the tensors differ in size class (wide tiles with a
+    split last round, half tiles only), ids and seeds."""
+    import mx_workloads as wl
+    shapes = [(8192 + 96, 320), (96, 320), (160, 96)]
+    srcs = [wl.activations(shapes[0][0], shapes[0][1], seed=3, outliers=3), wl.weights(shapes[1][0], shapes[1][1], seed=4),
+            wl.weights(shapes[2][0], shapes[2][1], seed=5) * 50]
+    if dtype == "bf16":
+        srcs = [wl.round_to_bf16(a) for a in srcs]
+    ids = [(6, 1, 11), (4, 2, 12), (9, 8, 13)]                      # (transposed id, row id, seed)
+    devs = [dev(a, dtype) for a in srcs]
+    jobs, outs = [], []
+    for t, (r, c), (idt, idr, seed) in zip(devs, shapes, ids):
+        out = tuple(torch.zeros(s, dtype=torch.uint8, device="cuda") for s in ((c, r // 2), (c, r // 32), (r, c // 2), (r, c // 32)))
+        outs.append(out)
+        jobs.append({"src": t, "out": out, "tensor_id_t": idt, "tensor_id_row": idr, "seed": seed})
+    mx.mx_quantize_transposed_batch(jobs, mx.ROUND_SR, mx.ROUND_RTN)
+    for a, t, out, (idt, idr, seed) in zip(srcs, devs, outs, ids):
+        sep = mx.mx_quantize_transposed(t, mx.ROUND_SR, idt, 1, True, mx.ROUND_RTN, idr, seed=seed)
+        want = orc.quantize_transposed(a, round_t=1, tensor_id_t=idt, pre_quant=1, round_row=0, tensor_id_row=idr, seed=seed)
+        for got, s, w, nm in zip(out, sep, want, ("codes_t", "scales_t", "codes_row", "scales_row")):
+            assert torch.equal(got, s), nm
+            assert_same_bytes(got, w, "%s of tensor %s" % (nm, a.shape))
