@@ -29,9 +29,19 @@ class _MxLinearFn(torch.autograd.Function):
         tetra = mod.flow == TETRAJET
         rnd_t = B.ROUND_SR if tetra else B.ROUND_RTN           # Eqs. 4-5 vs Eqs. 6-7
         pre = 1 if tetra else 0
-        xtq, xts, xq, xs = B.mx_quantize_transposed(x2d, rnd_t, Q6, pre, True, B.ROUND_RTN, Q1,
-                                                    scale_mode=mod.scale_mode, seed=seed)
-        wq, ws, wtq, wts = mod._quantize_weight(weight, rnd_t, pre, seed)
+        if not mod.qema and x2d.dtype == weight.dtype:
+            # activation and weight in one launch
+            u8 = lambda *shape: torch.empty(shape, dtype=torch.uint8, device=x2d.device)
+            xtq, xts, xq, xs = u8(D, Np // 2), u8(D, Np // 32), u8(Np, D // 2), u8(Np, D // 32)
+            wtq, wts, wq, ws = u8(D, C // 2), u8(D, C // 32), u8(C, D // 2), u8(C, D // 32)
+            B.mx_quantize_transposed_batch(
+                [{"src": x2d, "out": (xtq, xts, xq, xs), "tensor_id_t": Q6, "tensor_id_row": Q1, "pre_quant": pre, "seed": seed},
+                 {"src": weight.detach(), "out": (wtq, wts, wq, ws), "tensor_id_t": Q4, "tensor_id_row": Q2, "pre_quant": pre,
+                  "seed": seed}], rnd_t, B.ROUND_RTN, mod.scale_mode)
+        else:
+            xtq, xts, xq, xs = B.mx_quantize_transposed(x2d, rnd_t, Q6, pre, True, B.ROUND_RTN, Q1,
+                                                        scale_mode=mod.scale_mode, seed=seed)
+            wq, ws, wtq, wts = mod._quantize_weight(weight, rnd_t, pre, seed)
         y = B.mx_linear_fwd(xq, xs, wq, ws, out_dtype=x2d.dtype, workspace=mod._workspace(B.GEMM_FWD, Np, C, D))
         ctx.save_for_backward(xtq, xts, wtq, wts)
         ctx.mod, ctx.seed, ctx.N, ctx.x_dtype, ctx.w_dtype = mod, seed, N, x2d.dtype, weight.dtype
