@@ -22,9 +22,9 @@ __device__ __forceinline__ uint32_t scale_byte(uint32_t amax_bits, bool floor_mo
 {
     // adding 0x3FFFFF carries into the exponent field exactly when the mantissa exceeds 0x400000
     uint32_t field = (amax_bits + (floor_mode ? 0u : 0x3FFFFFu)) >> 23;
-    int b = (int)field - 2;
-    b = b < 0 ? 0 : b;
-    return amax_bits == 0u ? 98u : (uint32_t)b;
+    uint32_t b;
+    asm("v_sub_u32_e64 %0, %1, 2 clamp" : "=v"(b) : "v"(field));     // max(field - 2, 0) in one instruction
+    return amax_bits == 0u ? 98u : b;
 }
 
 // 2^-s as FP32 for scale byte b = s + 127 (s in [-127, 126]: always normal).
