@@ -695,3 +695,20 @@ def test_transposed_batch_equals_separate_calls(mx, orc, dtype):
         for got, s, w, nm in zip(out, sep, want, ("codes_t", "scales_t", "codes_row", "scales_row")):
             assert torch.equal(got, s), nm
             assert_same_bytes(got, w, "%s of tensor %s" % (nm, a.shape))
+
+
+@pytest.mark.parametrize("rows,cols", [(16384, 1056), (16416, 1088)])
+def test_transposed_wide_tiles_with_ragged_columns(mx, orc, rows, cols):
+    """Tensors large enough for 256 x 128 macro tiles whose width is not a multiple of 128 (a last
+    tile of 32 or 64 columns), with a last round issued as half tiles, and rows that are not a
+    multiple of 256: every output byte against the oracle."""
+    import mx_workloads as wl
+    X = wl.round_to_bf16(wl.activations(rows, cols, seed=rows % 97, outliers=5))
+    want = orc.quantize_transposed(X, round_t=1, tensor_id_t=6, pre_quant=1, round_row=0, tensor_id_row=1, seed=9)
+    got = mx.mx_quantize_transposed(dev(X, "bf16"), mx.ROUND_SR, 6, 1, True, mx.ROUND_RTN, 1, seed=9)
+    for g, w, nm in zip(got, want, ("codes_t", "scales_t", "codes_row", "scales_row")):
+        assert_same_bytes(g, w, nm)
+    want = orc.quantize_transposed(X, round_t=1, tensor_id_t=5, pre_quant=0, round_row=1, tensor_id_row=3, seed=9)
+    got = mx.mx_quantize_transposed(dev(X, "bf16"), mx.ROUND_SR, 5, 0, True, mx.ROUND_SR, 3, seed=9)
+    for g, w, nm in zip(got, want, ("codes_t", "scales_t", "codes_row", "scales_row")):
+        assert_same_bytes(g, w, nm + " (both stochastic)")
