@@ -211,6 +211,30 @@ def main():
         torch.cuda.synchronize()
         other_ms = (time.perf_counter() - t1) * 1e3 / args.steps
 
+    # the same step recorded once into a HIP graph and replayed: the seed lives in device memory and
+    # is advanced inside the graph, so every replay rounds with new numbers (one stream, no events)
+    graph_ms = None
+    if not args.no_other_schedule:
+        try:
+            seed_t = torch.full((1,), 3000, dtype=torch.int64, device="cuda")
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                for st, (X, W, dY) in zip(steps_obj, inputs):
+                    st.forward(X, W, seed_t)
+                    st.backward(dY, seed_t)
+                seed_t.add_(1)
+            for w in range(2):
+                graph.replay()
+            torch.cuda.synchronize()
+            t2 = time.perf_counter()
+            for s in range(args.steps):
+                graph.replay()
+            torch.cuda.synchronize()
+            graph_ms = (time.perf_counter() - t2) * 1e3 / args.steps
+            del graph
+        except Exception as exc:                           # reported, never fatal to the measurement above
+            graph_ms = "failed: %s" % (exc,)
+
     # Q-EMA weight quantizer (Sec. 5), outside the timed region: the four weights of the block, one
     # update + quantization each, as a training step with Q-EMA would issue them
     qema = []
@@ -383,6 +407,9 @@ def main():
         "other_schedule": None if other_ms is None else {
             "streams": 3 - args.streams, "ms_per_step": other_ms,
             "value": total_flops / (other_ms * 1e-3) / 1e12, "unit": "TFLOP/s"},
+        "graph_replay": None if graph_ms is None else (
+            {"error": graph_ms} if isinstance(graph_ms, str) else
+            {"ms_per_step": graph_ms, "value": total_flops / (graph_ms * 1e-3) / 1e12, "unit": "TFLOP/s"}),
         "oscillation_diagnostics": diag,
         "ramping_adamw": opt,
     }

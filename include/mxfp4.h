@@ -112,6 +112,11 @@ int mx_quantize_transposed(const void* src, int dtype, int64_t rows, int64_t col
  *   jobs    HOST array of `count` requests, 1 <= count <= MX_TRANSPOSED_BATCH_MAX; every field has the
  *           meaning, layout and alignment of the argument of the same name of mx_quantize_transposed
  *   round_t, round_row, scale_mode   shared by all jobs
+ *   seed_dev   NULL, or a DEVICE pointer (8-byte aligned, else MX_ERR_ALIGN) to a 64-bit word that the
+ *           kernel reads when it runs and uses in place of `seed`.  A launch recorded into a HIP graph
+ *           keeps its arguments, so a host-side seed would repeat the same draws on every replay;
+ *           with seed_dev the caller changes the word between replays (by a kernel or a copy on the
+ *           same stream) and every replay rounds with fresh numbers.  The word is only read.
  * All jobs must read the same kind of source: all F32, all BF16 (else MX_ERR_DTYPE), or all from
  * row_codes_in (else MX_ERR_MODE).  Any error of a single job is returned as that call would return
  * it, and nothing is launched.
@@ -132,6 +137,7 @@ typedef struct mx_transposed_job {
     const uint8_t* row_scales_in;
     uint64_t seed;
     uint64_t index_base;
+    const uint64_t* seed_dev;
 } mx_transposed_job;
 int mx_quantize_transposed_batch(const mx_transposed_job* jobs, int count,
                 int round_t, int round_row, int scale_mode, void* stream);

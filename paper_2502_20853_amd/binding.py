@@ -38,7 +38,7 @@ class _TransposedJob(ctypes.Structure):
                 ("tensor_id_t", ctypes.c_uint32), ("pre_quant", ctypes.c_int), ("codes_row", ctypes.c_void_p),
                 ("scales_row", ctypes.c_void_p), ("tensor_id_row", ctypes.c_uint32),
                 ("row_codes_in", ctypes.c_void_p), ("row_scales_in", ctypes.c_void_p),
-                ("seed", ctypes.c_uint64), ("index_base", ctypes.c_uint64)]
+                ("seed", ctypes.c_uint64), ("index_base", ctypes.c_uint64), ("seed_dev", ctypes.c_void_p)]
 
 
 class MxError(RuntimeError):
@@ -184,19 +184,34 @@ def mx_quantize_transposed(src, round_t=ROUND_SR, tensor_id_t=0, pre_quant=1, wa
 def mx_quantize_transposed_batch(jobs, round_t=ROUND_SR, round_row=ROUND_RTN, scale_mode=SCALE_TRUNCFREE, stream=None):
     """Several transposed quantizations in one launch.  jobs: list of dicts with the keys
     src, out=(codes_t, scales_t, codes_row, scales_row) and optionally tensor_id_t, tensor_id_row,
-    pre_quant (1), seed (0), index_base (0); the roundings and the scale rule are shared."""
+    pre_quant (1), seed (0), index_base (0); the roundings and the scale rule are shared.
+    Instead of src a job may give row_in=(codes, scales) and shape=(rows, cols).  seed may be a
+    one-element int64 device tensor: the kernel then reads the seed from it when it runs
+    (seed_dev of the C ABI), which is what a launch recorded into a graph needs."""
     arr = (_TransposedJob * len(jobs))()
     for j, job in zip(arr, jobs):
-        src = job["src"]
-        rows, cols, ld = _matrix(src)
+        src = job.get("src")
         codes_t, scales_t, codes_row, scales_row = job["out"]
-        j.src, j.dtype, j.rows, j.cols, j.ld = src.data_ptr(), _src_dtype(src), rows, cols, ld
+        if src is not None:
+            rows, cols, ld = _matrix(src)
+            j.src, j.dtype, j.rows, j.cols, j.ld = src.data_ptr(), _src_dtype(src), rows, cols, ld
+            j.row_codes_in = j.row_scales_in = None
+        else:
+            rows, cols = job["shape"]
+            j.src, j.dtype, j.rows, j.cols, j.ld = None, DTYPE_F32, rows, cols, cols
+            j.row_codes_in, j.row_scales_in = job["row_in"][0].data_ptr(), job["row_in"][1].data_ptr()
         j.codes_t, j.scales_t = codes_t.data_ptr(), scales_t.data_ptr()
         j.codes_row = codes_row.data_ptr() if codes_row is not None else None
         j.scales_row = scales_row.data_ptr() if scales_row is not None else None
         j.tensor_id_t, j.tensor_id_row = job.get("tensor_id_t", 0), job.get("tensor_id_row", 0)
-        j.pre_quant, j.seed, j.index_base = job.get("pre_quant", 1), job.get("seed", 0), job.get("index_base", 0)
-        j.row_codes_in = j.row_scales_in = None
+        j.pre_quant, j.index_base = job.get("pre_quant", 1), job.get("index_base", 0)
+        seed = job.get("seed", 0)
+        if torch.is_tensor(seed):
+            if seed.dtype != torch.int64 or seed.numel() != 1 or not seed.is_cuda:
+                raise ValueError("a device seed is a one-element int64 tensor on the GPU")
+            j.seed, j.seed_dev = 0, seed.data_ptr()
+        else:
+            j.seed, j.seed_dev = seed, None
     rc = lib().mx_quantize_transposed_batch(arr, len(jobs), round_t, round_row, scale_mode, _stream(stream))
     _check("mx_quantize_transposed_batch", rc)
 

@@ -156,6 +156,8 @@ int mx_quantize_transposed_batch(const mx_transposed_job* jobs, int count,
                                      q.pre_quant, q.codes_row, q.scales_row, round_row, q.tensor_id_row,
                                      q.row_codes_in, q.row_scales_in, scale_mode, q.seed, q.index_base, p[j]);
         if (rc != MX_OK) return rc;
+        if (q.seed_dev && !aligned(q.seed_dev, 8)) return MX_ERR_ALIGN;
+        p[j].seed_dev = q.seed_dev;
         // one kernel serves the launch: the jobs must read the same kind of source
         if ((p[j].row_codes_in != nullptr) != (p[0].row_codes_in != nullptr)) return MX_ERR_MODE;
         if (p[j].bf16 != p[0].bf16) return MX_ERR_DTYPE;

@@ -38,6 +38,7 @@ struct QuantTileParams {
     bool floor_mode;
     uint64_t seed;
     uint64_t index_base;
+    const uint64_t* seed_dev = nullptr;   // device word that replaces `seed` when set
 };
 
 // C[m x n] = A[m x k] . B[n x k]^T, operands packed MXFP4 along k.

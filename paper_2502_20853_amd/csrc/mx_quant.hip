@@ -188,6 +188,7 @@ struct TileArgs {
     uint32_t wide_per_row; // 256 x 128 tiles per block of 256 rows = ceil(cols / 128)
     uint32_t k0, k1, tensor_id_t, tensor_id_row;
     uint64_t index_base;
+    const uint32_t* seed_dev;  // when set: the two key words are read from here instead of k0, k1
 };
 
 __device__ __forceinline__ uint32_t xor_lane_max(uint32_t v, int mask)
@@ -257,6 +258,13 @@ __global__ __launch_bounds__(TILE_THREADS, 4) void quantize_tile_kernel(TileBatc
     for (int i = 1; i < TILE_BATCH_MAX; ++i) job += blockIdx.x >= batch.first[i] ? 1u : 0u;
     const TileArgs a = batch.job[job];
     const uint32_t block = blockIdx.x - batch.first[job];
+    // Philox key: the seed argument, or the 64-bit word in device memory that the caller names (a
+    // captured graph then draws new numbers on every replay).  Kept in scalar registers either way.
+    uint32_t k0 = a.k0, k1 = a.k1;
+    if ((ROW_SR || T_SR) && a.seed_dev) {
+        k0 = __builtin_amdgcn_readfirstlane(a.seed_dev[0]);
+        k1 = __builtin_amdgcn_readfirstlane(a.seed_dev[1]);
+    }
     __shared__ __attribute__((aligned(16))) uint8_t st[ST_BYTES];
     // FP32 sources need the rounding mode of each rule (switched per phase when they differ).
     // bf16 and packed sources scale exactly wherever a round_D threshold is near (8 significant
@@ -331,7 +339,7 @@ __global__ __launch_bounds__(TILE_THREADS, 4) void quantize_tile_kernel(TileBatc
                     uint32_t byte = scale_byte(quad_max(amax_bits8(x[j])), FLOOR);
                     const int e = grid_exponent(byte);
                     U8 rnd;
-                    if (ROW_SR) rnd = sr_addends((a.index_base + (uint64_t)r * a.cols + c) >> 3, a.tensor_id_row, a.k0, a.k1);
+                    if (ROW_SR) rnd = sr_addends((a.index_base + (uint64_t)r * a.cols + c) >> 3, a.tensor_id_row, k0, k1);
                     uint32_t pk = 0;
                     if (a.pre_quant) {
                         // keep sign in the value: the next quantizer takes |x| and the sign from it
@@ -376,7 +384,7 @@ __global__ __launch_bounds__(TILE_THREADS, 4) void quantize_tile_kernel(TileBatc
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             U8 rnd;
-            if (T_SR) rnd = sr_addends((a.index_base + (uint64_t)(row0 + j) * a.cols + c) >> 3, a.tensor_id_t, a.k0, a.k1);
+            if (T_SR) rnd = sr_addends((a.index_base + (uint64_t)(row0 + j) * a.cols + c) >> 3, a.tensor_id_t, k0, k1);
 #pragma unroll
             for (int t = 0; t < 8; ++t) {
                 int e = grid_exponent(sb[t]);
@@ -746,6 +754,7 @@ static uint32_t make_tile_args(const QuantTileParams& p, TileArgs& a)
     a.ld = p.ld; a.rows = (uint32_t)p.rows; a.cols = (uint32_t)p.cols;
     a.pre_quant = p.pre_quant;
     a.k0 = (uint32_t)p.seed; a.k1 = (uint32_t)(p.seed >> 32);
+    a.seed_dev = reinterpret_cast<const uint32_t*>(p.seed_dev);
     a.tensor_id_t = p.tensor_id_t; a.tensor_id_row = p.tensor_id_row; a.index_base = p.index_base;
     // Macro tile of a workgroup (8 waves): 256 rows x 128 columns (whole 128-byte lines of the
     // transposed codes, 64-byte pieces of the row codes; measured a few percent faster than

@@ -196,7 +196,7 @@ def test_transposed_batch_rejects(L):
         j.codes_t, j.scales_t, j.codes_row, j.scales_row = FAKE, FAKE, FAKE, FAKE
         j.tensor_id_t, j.tensor_id_row, j.pre_quant = 6, 1, 1
         j.row_codes_in = j.row_scales_in = None
-        j.seed, j.index_base = 0, 0
+        j.seed, j.index_base, j.seed_dev = 0, 0, None
         for k, v in kw.items():
             setattr(j, k, v)
         return j
@@ -214,3 +214,4 @@ def test_transposed_batch_rejects(L):
     given = job(src=None, codes_row=None, scales_row=None, row_codes_in=FAKE, row_scales_in=FAKE)
     assert call([job(), given]) == -4                              # nor a source with a given row result
     assert call([job(index_base=4)]) == -5                         # stochastic streams start on a block of 8
+    assert call([job(seed_dev=FAKE + 4)]) == -5                    # a device seed is a 64-bit word, 8-byte aligned

@@ -456,6 +456,52 @@ def test_config_vit_large_qema_layer(mx, orc):
     _check_layer(mx, orc, step, xt, wt, dy, y, dx, dw, N, D, C, True, True, "vit_large proj q-ema")
 
 
+# ------------------------------------------------- seed in device memory, graph replay ----
+
+def test_device_seed_equals_host_seed(mx, orc):
+    """A seed read from device memory by the kernel gives the bytes of the same seed passed by value."""
+    x = mixed_matrix(288, 320, seed=71, dtype="bf16")
+    X = dev(x, "bf16")
+    for seed in (5, (0x7ABCDEF1 << 32) + 0x92345678, -3):
+        want = orc.quantize_transposed(x, round_t=1, tensor_id_t=5, pre_quant=0, round_row=1, tensor_id_row=3,
+                                       seed=seed & 0xFFFFFFFFFFFFFFFF)
+        out = tuple(torch.empty(w.shape, dtype=torch.uint8, device="cuda") for w in want)
+        seed_t = torch.tensor([seed], dtype=torch.int64, device="cuda")
+        mx.mx_quantize_transposed_batch([{"src": X, "out": out, "tensor_id_t": 5, "tensor_id_row": 3, "pre_quant": 0,
+                                          "seed": seed_t}], 1, 1, 0)
+        for g, w, nm in zip(out, want, ("codes_t", "scales_t", "codes_row", "scales_row")):
+            assert_same_bytes(g, w, "%s seed %d" % (nm, seed))
+
+
+@pytest.mark.parametrize("qema", [False, True])
+def test_layer_pass_recorded_into_a_graph(mx, orc, qema):
+    """Forward + backward recorded once into a HIP graph with the seed in device memory, replayed with
+    three seeds (eager work and synchronization between the replays): every replay's packed bytes and
+    products equal the oracle's for the seed the word held at that replay."""
+    import mx_workloads as wl
+    N, D, C = 544, 256, 384
+    X, W, dY = wl.linear_layer(N, D, C, seed=5, dtype="bf16", outliers=3)
+    Xd, Wd, dYd = dev(X, "bf16"), dev(W, "bf16"), dev(dY, "bf16")
+    step = mx.MxLinearStep(N, D, C, out_dtype=torch.float32, qema=qema, beta=0.0)
+    seed_t = torch.zeros(1, dtype=torch.int64, device="cuda")
+    step.forward(Xd, Wd, seed_t)                         # one eager pass first: code objects loaded and the
+    step.backward(dYd, seed_t)                           # EMA state allocated before the recording starts
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step.forward(Xd, Wd, seed_t)
+        step.backward(dYd, seed_t)
+    for seed in (11, (9 << 32) + 4, 12):
+        seed_t.fill_(seed)
+        step.y.zero_(); step.dx.zero_(); step.dw.zero_(); step.dytq.zero_(); step.xtq.zero_(); step.wtq.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        xt, wt, dy = oracle_layer(orc, X, W, dY, seed=seed)
+        _check_layer(mx, orc, step, xt, wt, dy, step.y, step.dx, step.dw, N, D, C, False, False,
+                     "replay with seed %d" % seed)
+
+
 # ------------------------------------------------- full size, bench launch configuration ----
 
 def test_full_size_vit_base_qkv_layer(mx, orc):
