@@ -12,3 +12,4 @@ from .binding import (  # noqa: F401
 )
 from .layer import MxLinearStep  # noqa: F401
 from .module import MxLinear  # noqa: F401
+from .optim import QRampingAdamW  # noqa: F401
