@@ -76,6 +76,21 @@ class QRampingAdamW(torch.optim.Optimizer):
         """{parameter: N_w tensor in use} for the quantized weights (all ones before the first window closes)."""
         return {p: self.state[p]["factor"] for g in self.param_groups if g["quantized"] for p in g["params"] if self.state[p]}
 
+    def load_state_dict(self, state_dict):
+        """torch's loader converts every state tensor to its parameter's dtype; the integer arrays (update
+        and step counts, factors, packed codes) are taken out before and put back unchanged after."""
+        slim = {"state": {k: dict(v) for k, v in state_dict["state"].items()}, "param_groups": state_dict["param_groups"]}
+        held = {k: {n: v.pop(n) for n in list(v) if torch.is_tensor(v[n]) and not v[n].is_floating_point()}
+                for k, v in slim["state"].items()}
+        super().load_state_dict(slim)
+        params = [p for g in self.param_groups for p in g["params"]]
+        for p in params:                                   # the kernels write in place: share nothing with the source
+            for n, t in self.state[p].items():
+                self.state[p][n] = t.clone()
+        for k, tensors in held.items():
+            for n, t in tensors.items():
+                self.state[params[k]][n] = t.to(params[k].device).clone()
+
     @torch.no_grad()
     def step(self, closure=None):
         loss = None
