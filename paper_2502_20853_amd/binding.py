@@ -158,6 +158,7 @@ def mx_quantize_transposed(src, round_t=ROUND_SR, tensor_id_t=0, pre_quant=1, wa
     Returns (codes_t[cols, rows/2], scales_t[cols, rows/32], codes_row, scales_row);
     the last two are None unless want_row.  With row_in=(codes, scales) the given
     row result is re-quantized and src may be None (pass shape=(rows, cols)).
+    seed: an int, or a one-element int64 device tensor read by the kernel when it runs.
     """
     if src is not None:
         rows, cols, ld = _matrix(src)
@@ -172,6 +173,13 @@ def mx_quantize_transposed(src, round_t=ROUND_SR, tensor_id_t=0, pre_quant=1, wa
         codes_row = scales_row = None
         if want_row:
             codes_row, scales_row = _u8((rows, cols // 2), device), _u8((rows, cols // 32), device)
+    if torch.is_tensor(seed):
+        # a seed in device memory travels through the batched entry point (one request)
+        job = {"out": (codes_t, scales_t, codes_row, scales_row), "tensor_id_t": tensor_id_t, "tensor_id_row": tensor_id_row,
+               "pre_quant": pre_quant, "seed": seed, "index_base": index_base}
+        job.update({"src": src} if src is not None else {"row_in": row_in, "shape": (rows, cols)})
+        mx_quantize_transposed_batch([job], round_t, round_row, scale_mode, stream)
+        return codes_t, scales_t, codes_row, scales_row
     rc_in, rs_in = row_in if row_in is not None else (None, None)
     rc = lib().mx_quantize_transposed(_ptr(src), dtype, rows, cols, ld, _ptr(codes_t), _ptr(scales_t),
                                       round_t, tensor_id_t, pre_quant, _ptr(codes_row), _ptr(scales_row),

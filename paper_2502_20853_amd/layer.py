@@ -44,18 +44,9 @@ class MxLinearStep:
                 self.w_ema = torch.empty(W.shape, dtype=torch.float32, device=W.device)
                 update_ema = 2
             B.mx_ema_weight_quant(W, self.w_ema, self.beta, update_ema, self.scale_mode, out=(self.wq, self.ws))
-            if torch.is_tensor(seed):
-                B.mx_quantize_transposed_batch(
-                    [{"row_in": (self.wq, self.ws), "shape": (self.C, self.D), "out": (self.wtq, self.wts, None, None),
-                      "tensor_id_t": Q4, "seed": seed}], B.ROUND_SR, B.ROUND_RTN, self.scale_mode)
-            else:
-                B.mx_quantize_transposed(None, B.ROUND_SR, Q4, 1, False, row_in=(self.wq, self.ws),
-                                         scale_mode=self.scale_mode, seed=seed, shape=(self.C, self.D),
-                                         out=(self.wtq, self.wts, None, None))
-        elif torch.is_tensor(seed):
-            B.mx_quantize_transposed_batch(
-                [{"src": W, "out": (self.wtq, self.wts, self.wq, self.ws), "tensor_id_t": Q4, "tensor_id_row": Q2, "seed": seed}],
-                B.ROUND_SR, B.ROUND_RTN, self.scale_mode)
+            B.mx_quantize_transposed(None, B.ROUND_SR, Q4, 1, False, row_in=(self.wq, self.ws),
+                                     scale_mode=self.scale_mode, seed=seed, shape=(self.C, self.D),
+                                     out=(self.wtq, self.wts, None, None))
         else:
             B.mx_quantize_transposed(W, B.ROUND_SR, Q4, 1, True, B.ROUND_RTN, Q2, scale_mode=self.scale_mode,
                                      seed=seed, out=(self.wtq, self.wts, self.wq, self.ws))
@@ -68,13 +59,8 @@ class MxLinearStep:
                  {"src": W, "out": (self.wtq, self.wts, self.wq, self.ws), "tensor_id_t": Q4, "tensor_id_row": Q2, "seed": seed}],
                 B.ROUND_SR, B.ROUND_RTN, self.scale_mode)
         else:
-            if torch.is_tensor(seed):
-                B.mx_quantize_transposed_batch(
-                    [{"src": X, "out": (self.xtq, self.xts, self.xq, self.xs), "tensor_id_t": Q6, "tensor_id_row": Q1, "seed": seed}],
-                    B.ROUND_SR, B.ROUND_RTN, self.scale_mode)
-            else:
-                B.mx_quantize_transposed(X, B.ROUND_SR, Q6, 1, True, B.ROUND_RTN, Q1, scale_mode=self.scale_mode,
-                                         seed=seed, out=(self.xtq, self.xts, self.xq, self.xs))
+            B.mx_quantize_transposed(X, B.ROUND_SR, Q6, 1, True, B.ROUND_RTN, Q1, scale_mode=self.scale_mode,
+                                     seed=seed, out=(self.xtq, self.xts, self.xq, self.xs))
             self.quantize_weight(W, seed)
 
     def forward(self, X, W, seed):
@@ -82,13 +68,8 @@ class MxLinearStep:
         return B.mx_linear_fwd(self.xq, self.xs, self.wq, self.ws, out=self.y, workspace=self.workspace)
 
     def backward(self, dY, seed):
-        if torch.is_tensor(seed):
-            B.mx_quantize_transposed_batch(
-                [{"src": dY, "out": (self.dytq, self.dyts, self.dyq, self.dys), "tensor_id_t": Q5, "tensor_id_row": Q3,
-                  "pre_quant": 0, "seed": seed}], B.ROUND_SR, B.ROUND_SR, self.scale_mode)
-        else:
-            B.mx_quantize_transposed(dY, B.ROUND_SR, Q5, 0, True, B.ROUND_SR, Q3, scale_mode=self.scale_mode,
-                                     seed=seed, out=(self.dytq, self.dyts, self.dyq, self.dys))
+        B.mx_quantize_transposed(dY, B.ROUND_SR, Q5, 0, True, B.ROUND_SR, Q3, scale_mode=self.scale_mode,
+                                 seed=seed, out=(self.dytq, self.dyts, self.dyq, self.dys))
         B.mx_linear_bwd_dx(self.dyq, self.dys, self.wtq, self.wts, out=self.dx, workspace=self.workspace)
         B.mx_linear_bwd_dw(self.dytq, self.dyts, self.xtq, self.xts, out=self.dw, workspace=self.workspace)
         return self.dx, self.dw

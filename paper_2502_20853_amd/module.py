@@ -77,11 +77,13 @@ class MxLinear(torch.nn.Module):
     double quantization (Sec. 3.3); flow="microscaling": Eqs. 6-7 (all deterministic, the backward
     operands quantized from the full-precision tensors).  qema=True takes the forward weight codes
     from Q-EMA (Sec. 5); the moving average advances once per training-mode forward.  The stochastic
-    rounding streams are keyed by (seed, number of forward calls so far).
+    rounding streams are keyed by (seed, number of forward calls so far).  device_seed=True keeps that
+    key in device memory and advances it with a kernel, so that a forward + backward recorded into a
+    graph rounds with new numbers on every replay (same values as the host-side key, call for call).
     """
 
     def __init__(self, in_features, out_features, bias=True, device="cuda", dtype=torch.float32,
-                 flow=TETRAJET, scale_mode=B.SCALE_TRUNCFREE, qema=False, beta=0.998, seed=0):
+                 flow=TETRAJET, scale_mode=B.SCALE_TRUNCFREE, qema=False, beta=0.998, seed=0, device_seed=False):
         super().__init__()
         if in_features % 32 or out_features % 32:
             raise ValueError("in_features and out_features must be multiples of 32")
@@ -95,6 +97,9 @@ class MxLinear(torch.nn.Module):
         self.register_buffer("w_ema", torch.zeros((out_features, in_features), device=device, dtype=torch.float32)
                              if qema else None)
         self.calls = 0                     # forward calls so far (host-side: reading it must not synchronize)
+        start = (((self.seed & 0xFFFFFFFF) << 32) - 1) & 0xFFFFFFFFFFFFFFFF      # one before the first key, as a 64-bit word
+        self.register_buffer("seed_state", torch.tensor([start - (1 << 64) if start >> 63 else start], dtype=torch.int64,
+                                                        device=device) if device_seed else None)
         self._ema_started = False
         self._ws = None
 
@@ -131,7 +136,10 @@ class MxLinear(torch.nn.Module):
     def forward(self, x):
         lead = x.shape[:-1]
         x2d = x.reshape(-1, self.in_features)
-        seed = ((self.seed & 0xFFFFFFFF) << 32) + (self.calls & 0xFFFFFFFF)
+        if self.seed_state is not None:
+            seed = self.seed_state.add_(1)                 # the word the kernels read; the backward pass reads it too
+        else:
+            seed = ((self.seed & 0xFFFFFFFF) << 32) + (self.calls & 0xFFFFFFFF)
         self.calls += 1
         y = _MxLinearFn.apply(x2d, self.weight, self, seed)
         if self.bias is not None:

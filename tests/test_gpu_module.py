@@ -116,3 +116,48 @@ def test_module_trains_a_small_mlp(mx):
         opt.step()
         losses.append(float(loss.detach()))
     assert losses[-1] < 0.5 * losses[0], (losses[0], losses[-1])
+
+
+def test_module_device_seed_equals_host_seed_and_replays_in_a_graph(mx):
+    """device_seed=True: the same Y, dX, dW as the host-side key, call for call (eagerly); and a whole
+    forward + backward recorded into a graph gives, replay after replay, what the eager module gives on
+    its next calls (new rounding numbers each time, so the gradients of two replays differ)."""
+    import mx_workloads as wl
+    N, D, C = 96, 64, 128
+    X, W, dY = wl.linear_layer(N, D, C, seed=8)
+    lins = [mx.MxLinear(D, C, bias=False, seed=0x9ABCDEF0, device_seed=ds) for ds in (False, True)]
+    for lin in lins:
+        with torch.no_grad():
+            lin.weight.copy_(dev(W))
+
+    def eager(lin):
+        x = dev(X).requires_grad_(True)
+        lin.weight.grad = None
+        y = lin(x)
+        (y * dev(dY)).sum().backward()
+        return y.detach().clone(), x.grad.clone(), lin.weight.grad.clone()
+
+    for call in range(2):
+        a, b = eager(lins[0]), eager(lins[1])
+        for u, v, nm in zip(a, b, ("Y", "dX", "dW")):
+            assert torch.equal(u, v), (call, nm)
+    # record call 3 of the device-seed module; replays are then calls 3, 4, 5 of the host-seed module
+    lin = lins[1]
+    xs = dev(X).requires_grad_(True)
+    dys = dev(dY)
+    lin.weight.grad = None
+    graph = torch.cuda.CUDAGraph()
+    before = lin.seed_state.clone()
+    with torch.cuda.graph(graph):
+        ys = lin(xs)
+        (ys * dys).sum().backward()
+    lin.seed_state.copy_(before)                       # recording ran nothing: the key still names call 2
+    seen = []
+    for call in range(3):
+        graph.replay()
+        torch.cuda.synchronize()
+        want = eager(lins[0])
+        for u, v, nm in zip((ys, xs.grad, lin.weight.grad), want, ("Y", "dX", "dW")):
+            assert torch.equal(u, v), (call, nm)
+        seen.append(xs.grad.clone())
+    assert not torch.equal(seen[0], seen[1]) and not torch.equal(seen[1], seen[2])
