@@ -161,6 +161,16 @@ int mx_linear_fwd(const uint8_t* xq, const uint8_t* xs, const uint8_t* wq, const
                   int64_t N, int64_t C, int64_t D,
                   void* y, int y_dtype, int64_t ldy,
                   void* workspace, size_t workspace_bytes, void* stream);
+/* mx_linear_fwd with a bias row added in the product's output stage, before the one rounding to
+ * y_dtype: Y = Q1(X) . Q2(W)^T + 1 . bias^T (Eq. 3 gives the product; the bias is the linear layer's
+ * own, kept outside the quantized operands).  Saves the separate pass over Y that adding it afterwards
+ * costs (read + write of N x C elements).
+ *   bias   device, FP32, C values, 16-byte aligned (else MX_ERR_ALIGN); NULL is MX_ERR_NULL.
+ *   C      must be a multiple of 4 (else MX_ERR_SHAPE).  Everything else as mx_linear_fwd. */
+int mx_linear_fwd_bias(const uint8_t* xq, const uint8_t* xs, const uint8_t* wq, const uint8_t* ws,
+                  int64_t N, int64_t C, int64_t D, const float* bias,
+                  void* y, int y_dtype, int64_t ldy,
+                  void* workspace, size_t workspace_bytes, void* stream);
 int mx_linear_bwd_dx(const uint8_t* dyq, const uint8_t* dys, const uint8_t* wtq, const uint8_t* wts,
                   int64_t N, int64_t C, int64_t D,
                   void* dx, int dx_dtype, int64_t lddx,

@@ -4,7 +4,7 @@ binding with the same names."""
 from .binding import (  # noqa: F401
     DTYPE_BF16, DTYPE_F32, GEMM_BWD_DW, GEMM_BWD_DX, GEMM_FWD, ROUND_RTN, ROUND_SR,
     SCALE_FLOOR, SCALE_TRUNCFREE, MxError,
-    mx_dequantize, mx_ema_weight_quant, mx_linear_bwd_dw, mx_linear_bwd_dx, mx_linear_fwd,
+    mx_dequantize, mx_ema_weight_quant, mx_linear_bwd_dw, mx_linear_bwd_dx, mx_linear_fwd, mx_linear_fwd_bias,
     mx_linear_workspace_bytes, mx_quantize, mx_quantize_transposed, mx_quantize_transposed_batch, mx_version,
     OscillationState, mx_oscillation_accumulate, mx_ramping_factor,
     RateOfChangeState, mx_quant_confidence, mx_rate_of_change_step,

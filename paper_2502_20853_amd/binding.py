@@ -24,7 +24,7 @@ ROUND_RTN, ROUND_SR = 0, 1
 SCALE_TRUNCFREE, SCALE_FLOOR = 0, 1
 GEMM_FWD, GEMM_BWD_DX, GEMM_BWD_DW = 0, 1, 2
 
-EXPORTS = ["mx_quantize", "mx_quantize_transposed", "mx_quantize_transposed_batch", "mx_linear_fwd", "mx_linear_bwd_dx",
+EXPORTS = ["mx_quantize", "mx_quantize_transposed", "mx_quantize_transposed_batch", "mx_linear_fwd", "mx_linear_fwd_bias", "mx_linear_bwd_dx",
            "mx_linear_bwd_dw", "mx_ema_weight_quant", "mx_linear_workspace_bytes",
            "mx_oscillation_accumulate", "mx_ramping_factor",
            "mx_ramping_adamw_step", "mx_quant_confidence", "mx_rate_of_change_workspace_bytes", "mx_rate_of_change_step",
@@ -73,6 +73,8 @@ def lib():
         fn = getattr(L, name)
         fn.restype = ci
         fn.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, ci, i64, vp, sz, vp]
+    L.mx_linear_fwd_bias.restype = ci
+    L.mx_linear_fwd_bias.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, vp, ci, i64, vp, sz, vp]
     L.mx_ema_weight_quant.restype = ci
     L.mx_ema_weight_quant.argtypes = [vp, ci, vp, f32, ci, i64, i64, i64, vp, vp, ci, vp]
     L.mx_linear_workspace_bytes.restype = sz
@@ -247,6 +249,23 @@ def mx_linear_fwd(xq, xs, wq, ws, out=None, out_dtype=torch.float32, workspace=N
     """Y[N, C] = Q1(X) . Q2(W)^T from packed operands xq[N, D/2], wq[C, D/2]."""
     N, D, C = xq.shape[0], xq.shape[1] * 2, wq.shape[0]
     return _linear("mx_linear_fwd", GEMM_FWD, xq, xs, wq, ws, N, C, D, (N, C), out, out_dtype, workspace, stream)
+
+
+def mx_linear_fwd_bias(xq, xs, wq, ws, bias, out=None, out_dtype=torch.float32, workspace=None, stream=None):
+    """Y[N, C] = Q1(X) . Q2(W)^T + bias, the bias (float32, C values) added in the product's output stage."""
+    N, D, C = xq.shape[0], xq.shape[1] * 2, wq.shape[0]
+    if bias.dtype != torch.float32 or not bias.is_contiguous() or bias.numel() != C:
+        raise ValueError("bias must be a contiguous float32 tensor of C values")
+    if out is None:
+        out = torch.empty((N, C), dtype=out_dtype, device=xq.device)
+    need = mx_linear_workspace_bytes(GEMM_FWD, N, C, D)
+    if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
+        workspace = torch.empty(need, dtype=torch.uint8, device=xq.device)
+    wbytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    rc = lib().mx_linear_fwd_bias(_ptr(xq), _ptr(xs), _ptr(wq), _ptr(ws), N, C, D, _ptr(bias),
+                                  _ptr(out), _src_dtype(out), out.stride(0), _ptr(workspace), wbytes, _stream(stream))
+    _check("mx_linear_fwd_bias", rc)
+    return out
 
 
 def mx_linear_bwd_dx(dyq, dys, wtq, wts, out=None, out_dtype=torch.float32, workspace=None, stream=None):

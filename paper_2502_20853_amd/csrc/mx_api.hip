@@ -50,10 +50,14 @@ int check_gemm_call(const uint8_t* aq, const uint8_t* as, const uint8_t* bq, con
 
 int run_gemm(const uint8_t* aq, const uint8_t* as, const uint8_t* bq, const uint8_t* bs,
              int64_t m, int64_t n, int64_t k, void* out, int out_dtype, int64_t ldo,
-             void* workspace, size_t workspace_bytes, void* stream)
+             void* workspace, size_t workspace_bytes, void* stream, const float* bias = nullptr)
 {
     int rc = check_gemm_call(aq, as, bq, bs, m, n, k, out, out_dtype, ldo);
     if (rc != MX_OK) return rc;
+    if (bias) {
+        if ((n % 4) != 0) return MX_ERR_SHAPE;               // the kernels read the bias four columns at a time
+        if (!aligned(bias, 16)) return MX_ERR_ALIGN;
+    }
     int split = mxl::gemm_split_k(m, n, k);
     size_t need = split > 1 ? (size_t)split * (size_t)m * (size_t)n * sizeof(float) : 0;
     if (need > 0) {
@@ -64,7 +68,7 @@ int run_gemm(const uint8_t* aq, const uint8_t* as, const uint8_t* bq, const uint
     p.a_codes = aq; p.a_scales = as; p.b_codes = bq; p.b_scales = bs;
     p.m = m; p.n = n; p.k = k;
     p.c = out; p.c_bf16 = out_dtype == MX_DTYPE_BF16; p.ldc = ldo;
-    p.workspace = workspace; p.split_k = split;
+    p.workspace = workspace; p.split_k = split; p.bias = bias;
     return hip_status(mxl::launch_gemm(p, static_cast<hipStream_t>(stream)));
 }
 
@@ -171,6 +175,15 @@ int mx_linear_fwd(const uint8_t* xq, const uint8_t* xs, const uint8_t* wq, const
 {
     if (N <= 0 || C <= 0 || D <= 0) return (!xq || !xs || !wq || !ws || !y) ? MX_ERR_NULL : MX_ERR_SHAPE;
     return run_gemm(xq, xs, wq, ws, N, C, D, y, y_dtype, ldy, workspace, workspace_bytes, stream);
+}
+
+int mx_linear_fwd_bias(const uint8_t* xq, const uint8_t* xs, const uint8_t* wq, const uint8_t* ws,
+                  int64_t N, int64_t C, int64_t D, const float* bias, void* y, int y_dtype, int64_t ldy,
+                  void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!bias) return MX_ERR_NULL;
+    if (N <= 0 || C <= 0 || D <= 0) return (!xq || !xs || !wq || !ws || !y) ? MX_ERR_NULL : MX_ERR_SHAPE;
+    return run_gemm(xq, xs, wq, ws, N, C, D, y, y_dtype, ldy, workspace, workspace_bytes, stream, bias);
 }
 
 int mx_linear_bwd_dx(const uint8_t* dyq, const uint8_t* dys, const uint8_t* wtq, const uint8_t* wts,

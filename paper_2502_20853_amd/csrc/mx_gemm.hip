@@ -50,6 +50,7 @@ struct GemmArgs {
     int split_k;
     uint32_t tiles_m, tiles_n;
     int stagger;             // start delay of every other workgroup of an XCD, in s_sleep(32) units
+    const float* bias;       // n values added to every row of a final output (n % 4 == 0), or null
 };
 
 constexpr int KSTEP_BYTES = 64;     // 128 FP4 elements
@@ -258,6 +259,7 @@ void mx_gemm_kernel(GemmArgs g)
             const uint32_t nn = n0 + wn * WN + j * 16 + lkb * 4;
             if (nn >= g.n) continue;
             v4f v = acc[i][j];
+            if (g.bias) v += *reinterpret_cast<const v4f*>(g.bias + nn);      // nn + 3 < n: n is a multiple of 4
             size_t off = (size_t)mm * ldc + nn;
             if (nn + 3 < g.n && vec_ok) {
                 if (as_bf16) {
@@ -282,7 +284,7 @@ void mx_gemm_kernel(GemmArgs g)
 
 // Sum the split-K partials in a fixed order and write the final output.
 __global__ void splitk_reduce_kernel(const float* part, int split, uint32_t m, uint32_t n,
-                                     void* c, int64_t ldc, int c_bf16)
+                                     void* c, int64_t ldc, int c_bf16, const float* bias)
 {
     size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     size_t total = (size_t)m * n;
@@ -290,6 +292,7 @@ __global__ void splitk_reduce_kernel(const float* part, int split, uint32_t m, u
     float s = 0.f;
     for (int z = 0; z < split; ++z) s += part[(size_t)z * total + idx];
     uint32_t r = (uint32_t)(idx / n), col = (uint32_t)(idx - (size_t)r * n);
+    if (bias) s += bias[col];
     if (c_bf16) static_cast<uint16_t*>(c)[(size_t)r * ldc + col] = f32_to_bf16_rne(s);
     else        static_cast<float*>(c)[(size_t)r * ldc + col] = s;
 }
@@ -297,7 +300,7 @@ __global__ void splitk_reduce_kernel(const float* part, int split, uint32_t m, u
 // The same for n % 4 == 0 and 16-byte aligned rows of the output: four columns per thread, the
 // partial loads of a thread issued back to back (same summation order per element).
 __global__ void splitk_reduce4_kernel(const float* part, int split, uint32_t m, uint32_t n,
-                                      void* c, int64_t ldc, int c_bf16)
+                                      void* c, int64_t ldc, int c_bf16, const float* bias)
 {
     const size_t q = (size_t)blockIdx.x * blockDim.x + threadIdx.x;       // index of a group of 4 columns
     const size_t total = (size_t)m * n;
@@ -320,6 +323,10 @@ __global__ void splitk_reduce4_kernel(const float* part, int split, uint32_t m, 
     }
     const size_t idx = q * 4;
     const uint32_t r = (uint32_t)(idx / n), col = (uint32_t)(idx - (size_t)r * n);
+    if (bias) {
+        const float4 bv = *reinterpret_cast<const float4*>(bias + col);
+        s.x += bv.x; s.y += bv.y; s.z += bv.z; s.w += bv.w;
+    }
     if (c_bf16) {
         uint2 o;
         o.x = f32x2_to_bf16x2(s.x, s.y);
@@ -373,6 +380,14 @@ static_assert(D_WAVES * D_EP_BYTES <= D_LDS_BYTES, "epilogue strips must fit in 
 #define MX_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
 #define MX_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
 
+// Bias of four consecutive output columns starting at `col` (a multiple of 4), zero when there is no
+// bias or the columns lie beyond n.
+__device__ __forceinline__ v4f bias_of_columns(const GemmArgs& g, uint32_t col)
+{
+    if (g.bias != nullptr && col < g.n) return *reinterpret_cast<const v4f*>(g.bias + col);
+    return v4f{0.f, 0.f, 0.f, 0.f};
+}
+
 // Accumulators -> per-wave LDS strip (32 rows x 128 columns) -> global, so that every
 // store is 16 bytes per lane and a wave writes whole row segments.  The LDS region must
 // no longer be in use by any wave of the workgroup.  The wave owns output rows
@@ -397,9 +412,10 @@ __device__ __forceinline__ void gemm_epilogue_32x32(const GemmArgs& g, uint8_t* 
             for (int j = 0; j < 4; ++j)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
+                    const v4f bv = bias_of_columns(g, nbase + 32 * j + 8 * q + 4 * lhalf);
                     uint2 pk;
-                    pk.x = f32x2_to_bf16x2(acc[i][j][4 * q], acc[i][j][4 * q + 1]);
-                    pk.y = f32x2_to_bf16x2(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+                    pk.x = f32x2_to_bf16x2(acc[i][j][4 * q] + bv.x, acc[i][j][4 * q + 1] + bv.y);
+                    pk.y = f32x2_to_bf16x2(acc[i][j][4 * q + 2] + bv.z, acc[i][j][4 * q + 3] + bv.w);
                     *reinterpret_cast<uint2*>(ep + lrow * D_EP_PITCH_BF16 + (32 * j + 8 * q + 4 * lhalf) * 2) = pk;
                 }
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -428,9 +444,12 @@ __device__ __forceinline__ void gemm_epilogue_32x32(const GemmArgs& g, uint8_t* 
 #pragma unroll
             for (int j = 0; j < 4; ++j)
 #pragma unroll
-                for (int q = 0; q < 4; ++q)
+                for (int q = 0; q < 4; ++q) {
+                    const v4f bv = bias_of_columns(g, nbase + 32 * j + 8 * q + 4 * lhalf);
                     *reinterpret_cast<float4*>(ep + lrow * D_EP_PITCH_F32 + (32 * j + 8 * q + 4 * lhalf) * 4) =
-                        make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+                        make_float4(acc[i][j][4 * q] + bv.x, acc[i][j][4 * q + 1] + bv.y, acc[i][j][4 * q + 2] + bv.z,
+                                    acc[i][j][4 * q + 3] + bv.w);
+                }
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
             for (int it = 0; it < 16; ++it) {
@@ -649,10 +668,17 @@ __device__ __forceinline__ void store16(void* dst, v4i v)
     else        *reinterpret_cast<v4i*>(dst) = v;
 }
 
+// bias: LDS address of the bias value of column nbase (FP32, 128 values), or null.
 template <bool STREAM>
 __device__ __forceinline__ void gemm_epilogue_chunked(const GemmArgs& g, uint8_t* ep, v16f (&acc)[2][4],
-                                                      uint32_t mrow0, uint32_t nbase, int lane_in, uint32_t zsplit)
+                                                      uint32_t mrow0, uint32_t nbase, int lane_in, uint32_t zsplit,
+                                                      const __attribute__((address_space(3))) uint8_t* bias)
 {
+    // bias of the four columns a lane holds in accumulator registers 4q..4q+3 of column block jb
+    auto bias4 = [&](int jb, int q, uint32_t lhalf) -> v4f {
+        if (bias == nullptr) return v4f{0.f, 0.f, 0.f, 0.f};
+        return *reinterpret_cast<const __attribute__((address_space(3))) v4f*>(bias + (32 * jb + 8 * q + 4 * lhalf) * 4);
+    };
     // lane-derived indices are recomputed at every call instead of living across the K loop
     (void)lane_in;
     const uint32_t lane = fresh_lane_id();
@@ -677,9 +703,10 @@ __device__ __forceinline__ void gemm_epilogue_chunked(const GemmArgs& g, uint8_t
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
                         const v16f& a = acc[i][2 * jp + jj];
+                        const v4f bv = bias4(2 * jp + jj, q, lhalf);
                         uint2 pk;
-                        pk.x = f32x2_to_bf16x2(a[4 * q], a[4 * q + 1]);
-                        pk.y = f32x2_to_bf16x2(a[4 * q + 2], a[4 * q + 3]);
+                        pk.x = f32x2_to_bf16x2(a[4 * q] + bv.x, a[4 * q + 1] + bv.y);
+                        pk.y = f32x2_to_bf16x2(a[4 * q + 2] + bv.z, a[4 * q + 3] + bv.w);
                         *reinterpret_cast<uint2*>(ep + lrow * P_EP_PITCH + (32 * jj + 8 * q + 4 * lhalf) * 2) = pk;
                     }
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -708,9 +735,12 @@ __device__ __forceinline__ void gemm_epilogue_chunked(const GemmArgs& g, uint8_t
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
 #pragma unroll
-                for (int q = 0; q < 4; ++q)
+                for (int q = 0; q < 4; ++q) {
+                    const v4f bv = bias4(j, q, lhalf);
                     *reinterpret_cast<float4*>(ep + lrow * P_EP_PITCH + (8 * q + 4 * lhalf) * 4) =
-                        make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+                        make_float4(acc[i][j][4 * q] + bv.x, acc[i][j][4 * q + 1] + bv.y, acc[i][j][4 * q + 2] + bv.z,
+                                    acc[i][j][4 * q + 3] + bv.w);
+                }
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
                 for (int it = 0; it < 4; ++it) {
@@ -743,7 +773,8 @@ __device__ __forceinline__ void gemm_epilogue_chunked(const GemmArgs& g, uint8_t
 // DMA latency sits between two MFMA bursts of the same wave.
 //   Per 256 x 256 x 128 step the CU loads 32 KB through L2 -> LDS instead of the 2 x 24 KB of
 //   two 256 x 128 workgroups.
-//   LDS: 3 code stages x 32 KB | 3 scale slots x [512 rows][16 B] | output staging 8 x 4.5 KB.
+//   LDS: 3 code stages x 32 KB | 3 scale slots x [512 rows][16 B] | output staging 8 x 4.5 KB |
+//        2 x 1 KB of bias values (the tile being multiplied and the one being loaded).
 // Two cursors run over the workgroup's tile list.  The read cursor names the K step whose
 // operands the next L phase reads; the issue cursor runs two stages ahead of it (also across
 // tile boundaries) and names the stage the same L phase loads.  Stage q of a tile lives in
@@ -760,7 +791,8 @@ constexpr int Q_STAGE_BYTES = (Q_BM + Q_BN) * 64;                       // 32768
 constexpr int Q_SCALE_OFF = Q_STAGES * Q_STAGE_BYTES;                   // 98304
 constexpr int Q_SCALE_SLOT = (Q_BM + Q_BN) * 16;                        // 8192
 constexpr int Q_EP_OFF = Q_SCALE_OFF + 3 * Q_SCALE_SLOT;                // 122880
-constexpr int Q_LDS_BYTES = Q_EP_OFF + Q_WAVES * P_EP_BYTES;            // 159744
+constexpr int Q_BIAS_OFF = Q_EP_OFF + Q_WAVES * P_EP_BYTES;             // 159744: two slots of 256 bias values
+constexpr int Q_LDS_BYTES = Q_BIAS_OFF + 2 * 1024;                      // 161792
 static_assert(Q_LDS_BYTES <= 160 * 1024, "one workgroup per CU");
 constexpr unsigned Q_SLOTS = 256;
 
@@ -795,7 +827,7 @@ __device__ __forceinline__ void dma_load16_at(uint32_t lds_addr, const uint8_t* 
 // The whole tile walk of one wave; GRP (0: columns 0-127, M phase first; 1: columns 128-255, L phase
 // first) is a template parameter so that each group's loop is straight-line code.  All cursor
 // state is wave-uniform (scalar registers) and advanced with compares and adds only.
-template <int GRP>
+template <int GRP, bool BIAS>
 __device__ __forceinline__ void pingpong_wave(const GemmArgs& g, lds_u8* lds, const int wave)
 {
     const uint32_t tiles = g.tiles_m * g.tiles_n, total = tiles * (uint32_t)g.split_k;
@@ -831,6 +863,7 @@ __device__ __forceinline__ void pingpong_wave(const GemmArgs& g, lds_u8* lds, co
     uint32_t i_dst = lds0 + wave * 2048;                          // this wave's A piece of the stage buffer
     uint32_t i_sdst = lds0 + Q_SCALE_OFF + wave * 1024;           // this wave's piece of the scale slot
     int i_buf = 0, i_slot = 0;
+    uint32_t i_bias = lds0 + Q_BIAS_OFF;                          // bias slot of the next tile to be issued
     auto set_issue_tile = [&](uint32_t t) {
         const uint32_t z = t / tiles, r = t - z * tiles, tm = r / g.tiles_n;
         const uint32_t m0 = tm * Q_BM, n0 = (r - tm * g.tiles_n) * Q_BN;
@@ -857,6 +890,14 @@ __device__ __forceinline__ void pingpong_wave(const GemmArgs& g, lds_u8* lds, co
         i_q = 0;
         i_due = 0;
         i_j = 0;
+        // The tile's 256 bias values go to the slot that the tile before the previous one used; that tile's
+        // output stage ended, in every wave, before the barriers of the previous tile's K loop (>= 4 steps),
+        // and this point lies inside that loop.  One wave loads; its later waits cover the load (loads
+        // complete in order) and barriers follow before any wave reads the slot.
+        if (BIAS && GRP == 0 && wave == 0) {
+            dma_load16_at(i_bias, reinterpret_cast<const uint8_t*>(g.bias + n0), min(4u * ln, g.n - 4u - n0) * 4u);
+            i_bias = i_bias == lds0 + Q_BIAS_OFF ? i_bias + 1024u : i_bias - 1024u;
+        }
     };
     // Loads the next stage (and the scale block that travels with it) and waits for every load
     // issued in earlier phases.
@@ -1006,6 +1047,7 @@ __device__ __forceinline__ void pingpong_wave(const GemmArgs& g, lds_u8* lds, co
     //      that buffer; and every wave has waited for its part of stage k+1, which group 0 reads
     //      right after it.  Between barriers the two waves of a SIMD drift freely: one is in its
     //      MFMA burst while the other reads and loads. ----
+    uint32_t c_bias = Q_BIAS_OFF;                                 // bias slot of the tile being multiplied
     for (uint32_t c_tile = first; c_tile < range_end; c_tile += stride) {
         const int nk = tile_steps(c_tile);
         for (int k = 0; k < nk; ++k) {
@@ -1022,17 +1064,22 @@ __device__ __forceinline__ void pingpong_wave(const GemmArgs& g, lds_u8* lds, co
         const uint32_t z = c_tile / tiles, r = c_tile - z * tiles, tm = r / g.tiles_n;
         const uint32_t m0 = tm * Q_BM + wm * 64, n0 = (r - tm * g.tiles_n) * Q_BN + GRP * 128;
         uint8_t* ep = (uint8_t*)(lds + Q_EP_OFF + wave * P_EP_BYTES);
-        if (g.split_k == 1) gemm_epilogue_chunked<true>(g, ep, acc, m0, n0, lane, z);
-        else                gemm_epilogue_chunked<false>(g, ep, acc, m0, n0, lane, z);
+        const lds_u8* bias = BIAS ? lds + c_bias + GRP * 512 : nullptr;
+        if (BIAS) c_bias = c_bias == (uint32_t)Q_BIAS_OFF ? c_bias + 1024u : c_bias - 1024u;
+        if (g.split_k == 1) gemm_epilogue_chunked<true>(g, ep, acc, m0, n0, lane, z, bias);
+        else                gemm_epilogue_chunked<false>(g, ep, acc, m0, n0, lane, z, nullptr);
         zero_acc();
     }
     // the cursor's trailing loads target this workgroup's LDS: they must land before it is released
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 
+// BIAS: a bias row is added in the output stage (a separate instance: the plain product's code is
+// the same with and without this feature in the source).
+template <bool BIAS>
 __global__ __launch_bounds__(Q_NT, 2) void mx_gemm_pingpong_kernel(GemmArgs g)
 {
-    __shared__ __attribute__((aligned(1024))) uint8_t lds[Q_LDS_BYTES];
+    __shared__ __attribute__((aligned(1024))) uint8_t lds[BIAS ? Q_LDS_BYTES : Q_BIAS_OFF];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     // Short-K tiles spend as long storing as multiplying.  Started together, all compute units store
     // at the same time, the burst (33 MB per round) takes longer to drain than the next K loop has
@@ -1040,8 +1087,8 @@ __global__ __launch_bounds__(Q_NT, 2) void mx_gemm_pingpong_kernel(GemmArgs g)
     // of the workgroups start half a K loop later, so that one half stores while the other multiplies.
     if ((blockIdx.x >> 3) & 1)
         for (int i = 0; i < g.stagger; ++i) __builtin_amdgcn_s_sleep(32);
-    if (wave < 4) pingpong_wave<0>(g, (lds_u8*)lds, wave);
-    else          pingpong_wave<1>(g, (lds_u8*)lds, wave);
+    if (wave < 4) pingpong_wave<0, BIAS>(g, (lds_u8*)lds, wave);
+    else          pingpong_wave<1, BIAS>(g, (lds_u8*)lds, wave);
 }
 
 }  // namespace
@@ -1077,6 +1124,7 @@ hipError_t launch_gemm(const GemmParams& p, hipStream_t st)
     g.split_k = (int)((ksteps + steps_per - 1) / steps_per);   // drop empty splits
     g.c = g.split_k > 1 ? p.workspace : p.c;
     g.ldc = p.ldc; g.c_bf16 = p.c_bf16;
+    g.bias = g.split_k > 1 ? nullptr : p.bias;                  // partial sums get none: the reduction adds it
     if ((p.k & 127) == 0) {
         g.tiles_m = (uint32_t)((p.m + D_BM - 1) / D_BM);
         g.tiles_n = (uint32_t)((p.n + D_BN - 1) / D_BN);
@@ -1089,7 +1137,9 @@ hipError_t launch_gemm(const GemmParams& p, hipStream_t st)
             // measured on the ViT-B products: 2.5 us (3 x 2048 clocks) gains 5-15 % at K = 768 and
             // 3-5 % at K = 2304, nothing at K = 3072; pointless below two rounds of tiles
             g.stagger = (g.split_k == 1 && nblk >= 2 * Q_SLOTS && p.k <= 2304) ? 3 : 0;
-            hipLaunchKernelGGL(mx_gemm_pingpong_kernel, dim3(nblk < Q_SLOTS ? nblk : Q_SLOTS), dim3(Q_NT), 0, st, g);
+            const dim3 pgrid(nblk < Q_SLOTS ? nblk : Q_SLOTS);
+            if (g.bias) hipLaunchKernelGGL(mx_gemm_pingpong_kernel<true>, pgrid, dim3(Q_NT), 0, st, g);
+            else        hipLaunchKernelGGL(mx_gemm_pingpong_kernel<false>, pgrid, dim3(Q_NT), 0, st, g);
         } else {
             hipLaunchKernelGGL(mx_gemm_dma_kernel, grid, dim3(D_NT), 0, st, g);
         }
@@ -1110,11 +1160,11 @@ hipError_t launch_gemm(const GemmParams& p, hipStream_t st)
         if (vec) {
             dim3 rgrid((unsigned)((total / 4 + 255) / 256)), rblock(256);
             hipLaunchKernelGGL(splitk_reduce4_kernel, rgrid, rblock, 0, st,
-                               static_cast<const float*>(p.workspace), g.split_k, g.m, g.n, p.c, p.ldc, (int)p.c_bf16);
+                               static_cast<const float*>(p.workspace), g.split_k, g.m, g.n, p.c, p.ldc, (int)p.c_bf16, p.bias);
         } else {
             dim3 rgrid((unsigned)((total + 255) / 256)), rblock(256);
             hipLaunchKernelGGL(splitk_reduce_kernel, rgrid, rblock, 0, st,
-                               static_cast<const float*>(p.workspace), g.split_k, g.m, g.n, p.c, p.ldc, (int)p.c_bf16);
+                               static_cast<const float*>(p.workspace), g.split_k, g.m, g.n, p.c, p.ldc, (int)p.c_bf16, p.bias);
         }
         e = hipGetLastError();
     }

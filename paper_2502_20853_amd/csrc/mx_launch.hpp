@@ -53,6 +53,7 @@ struct GemmParams {
     int64_t ldc;
     void* workspace;
     int split_k;     // >= 1; > 1 needs workspace of split_k * m * n floats
+    const float* bias = nullptr;   // n values added to every output row (needs n % 4 == 0), or null
 };
 
 hipError_t launch_quantize_rows(const QuantRowsParams& p, hipStream_t st);

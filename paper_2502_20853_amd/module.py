@@ -21,7 +21,7 @@ def _pad_rows(t, rows):
 
 class _MxLinearFn(torch.autograd.Function):
     @staticmethod
-    def forward(ctx, x2d, weight, mod, seed):
+    def forward(ctx, x2d, weight, bias, mod, seed):
         N, D = x2d.shape
         C = weight.shape[0]
         Np = (N + 31) // 32 * 32
@@ -42,8 +42,14 @@ class _MxLinearFn(torch.autograd.Function):
             xtq, xts, xq, xs = B.mx_quantize_transposed(x2d, rnd_t, Q6, pre, True, B.ROUND_RTN, Q1,
                                                         scale_mode=mod.scale_mode, seed=seed)
             wq, ws, wtq, wts = mod._quantize_weight(weight, rnd_t, pre, seed)
-        y = B.mx_linear_fwd(xq, xs, wq, ws, out_dtype=x2d.dtype, workspace=mod._workspace(B.GEMM_FWD, Np, C, D))
+        ws_fwd = mod._workspace(B.GEMM_FWD, Np, C, D)
+        if bias is None:
+            y = B.mx_linear_fwd(xq, xs, wq, ws, out_dtype=x2d.dtype, workspace=ws_fwd)
+        else:                                              # added in the product's output stage
+            y = B.mx_linear_fwd_bias(xq, xs, wq, ws, bias.detach().float().contiguous(), out_dtype=x2d.dtype,
+                                     workspace=ws_fwd)
         ctx.save_for_backward(xtq, xts, wtq, wts)
+        ctx.bias_dtype = None if bias is None else bias.dtype
         ctx.mod, ctx.seed, ctx.N, ctx.x_dtype, ctx.w_dtype = mod, seed, N, x2d.dtype, weight.dtype
         return y[:N]
 
@@ -52,6 +58,9 @@ class _MxLinearFn(torch.autograd.Function):
         xtq, xts, wtq, wts = ctx.saved_tensors
         mod, N = ctx.mod, ctx.N
         D, C, Np = xtq.shape[0], wtq.shape[1] * 2, xtq.shape[1] * 2
+        dbias = None
+        if ctx.bias_dtype is not None and ctx.needs_input_grad[2]:
+            dbias = dy.sum(dim=0, dtype=torch.float32).to(ctx.bias_dtype)      # the bias is outside the quantized products
         dy = _pad_rows(dy.contiguous(), Np)
         rnd = B.ROUND_SR if mod.flow == TETRAJET else B.ROUND_RTN
         dytq, dyts, dyq, dys = B.mx_quantize_transposed(dy, rnd, Q5, 0, True, rnd, Q3,
@@ -65,7 +74,7 @@ class _MxLinearFn(torch.autograd.Function):
                                     workspace=mod._workspace(B.GEMM_BWD_DW, Np, C, D))
             if ctx.w_dtype != torch.float32:
                 dw = dw.to(ctx.w_dtype)
-        return dx, dw, None, None
+        return dx, dw, dbias, None, None
 
 
 class MxLinear(torch.nn.Module):
@@ -141,7 +150,5 @@ class MxLinear(torch.nn.Module):
         else:
             seed = ((self.seed & 0xFFFFFFFF) << 32) + (self.calls & 0xFFFFFFFF)
         self.calls += 1
-        y = _MxLinearFn.apply(x2d, self.weight, self, seed)
-        if self.bias is not None:
-            y = y + self.bias.to(y.dtype)
+        y = _MxLinearFn.apply(x2d, self.weight, self.bias, self, seed)
         return y.reshape(*lead, self.out_features)

@@ -91,6 +91,15 @@ def g(L, fn, a=FAKE, as_=FAKE, b=FAKE, bs=FAKE, N=64, C=64, D=64, out=FAKE, dt=0
     return getattr(L, fn)(P(a), P(as_), P(b), P(bs), N, C, D, P(out), dt, ldo, P(ws), wsb, P(0))
 
 
+def test_linear_fwd_bias_rejects(L):
+    def call(bias=FAKE, a=FAKE, C=64, ldo=64, D=64):
+        return L.mx_linear_fwd_bias(P(a), P(FAKE), P(FAKE), P(FAKE), 64, C, D, P(bias), P(FAKE), 0, ldo, P(0), 0, P(0))
+    assert call(bias=0) == -1 and call(a=0) == -1
+    assert call(C=66, ldo=66) == -2                   # the bias is read four columns at a time
+    assert call(bias=FAKE + 8) == -5
+    assert call(D=48) == -2                           # everything else as mx_linear_fwd
+
+
 def test_linear_rejects(L):
     for fn in ("mx_linear_fwd", "mx_linear_bwd_dx", "mx_linear_bwd_dw"):
         assert g(L, fn, a=0) == -1 and g(L, fn, bs=0) == -1 and g(L, fn, out=0) == -1

@@ -275,6 +275,60 @@ def test_gemm_more_tiles_than_resident_workgroups(mx, orc, m, n, k):
     assert np.all(np.abs(got.sum(axis=1) - row) <= 1e-5 * rowabs)
 
 
+@pytest.mark.parametrize("out", ["f32", "bf16"])
+@pytest.mark.parametrize("m,n,k", [(256, 768, 192), (300, 200, 96),             # 16x16x128 kernel, ragged tiles
+                                    (300, 200, 384), (33, 700, 256),             # short-K 32x32x64 kernel
+                                    (515, 260, 1024), (768, 768, 512), (40, 48, 640),   # main kernel; 4 columns in the last tile
+                                    (64, 1000, 4096), (100, 300, 4736)])         # K split: the reduction adds the bias
+def test_linear_fwd_bias(mx, orc, m, n, k, out):
+    """Y = A.B^T + bias with the bias added before the one rounding to the output type, on every kernel
+    path; against the FP64 product of the same operands plus the bias."""
+    ac, as_ = random_packed(m, k, 31, 125, 129)
+    bc, bs = random_packed(n, k, 32, 125, 129)
+    bias = (np.random.default_rng(n).standard_normal(n) * 64).astype(np.float32)
+    bias[: min(4, n)] = [0.0, -0.0, 1e-3, -4096.0][: min(4, n)]
+    got = mx.mx_linear_fwd_bias(dev(ac), dev(as_), dev(bc), dev(bs), dev(bias),
+                                out_dtype=torch.bfloat16 if out == "bf16" else torch.float32)
+    ref = orc.gemm_f64(ac, as_, bc, bs) + bias.astype(np.float64)[None, :]
+    absref = np.abs(orc.dequantize(ac, as_)) @ np.abs(orc.dequantize(bc, bs)).T + np.abs(bias)[None, :]
+    tol = 1e-5 * absref + (np.abs(ref) * 2.0 ** -8 if out == "bf16" else 0.0)
+    err = np.abs(host(got.float()).astype(np.float64) - ref)
+    assert np.all(err <= tol), (np.max(err / (absref + 1e-300)), np.unravel_index(np.argmax(err / (tol + 1e-300)), err.shape))
+
+
+def test_linear_fwd_bias_strided_output_of_a_k_split(mx, orc):
+    """K split whose output rows are not 16-byte aligned: the scalar form of the reduction adds the bias."""
+    m, n, k = 64, 1000, 4096
+    ac, as_ = random_packed(m, k, 33, 125, 129)
+    bc, bs = random_packed(n, k, 34, 125, 129)
+    bias = np.random.default_rng(5).standard_normal(n).astype(np.float32)
+    wide = torch.zeros((m, n + 1), dtype=torch.float32, device="cuda")
+    mx.mx_linear_fwd_bias(dev(ac), dev(as_), dev(bc), dev(bs), dev(bias), out=wide[:, :n])
+    ref = orc.gemm_f64(ac, as_, bc, bs) + bias.astype(np.float64)[None, :]
+    absref = np.abs(orc.dequantize(ac, as_)) @ np.abs(orc.dequantize(bc, bs)).T + np.abs(bias)[None, :]
+    got = host(wide).astype(np.float64)
+    assert np.all(np.abs(got[:, :n] - ref) <= 1e-5 * absref) and np.all(got[:, n] == 0)
+
+
+@pytest.mark.parametrize("m,n,k", [(8192, 6400, 512), (6100, 2900, 640)])
+def test_linear_fwd_bias_over_several_tiles_per_workgroup(mx, orc, m, n, k):
+    """More output tiles than workgroups (up to 3.1 per workgroup at the shortest K loop the main kernel
+    takes): each tile must see its own 256 bias values.  The bias encodes its column, so a value from
+    another tile's slot is far outside the tolerance."""
+    ac, as_ = random_packed(m, k, 35, 120, 130)
+    bc, bs = random_packed(n, k, 36, 120, 130)
+    bias = (np.arange(n, dtype=np.float32) - n / 2) * 4096.0
+    got = host(mx.mx_linear_fwd_bias(dev(ac), dev(as_), dev(bc), dev(bs), dev(bias))).astype(np.float64)
+    rng = np.random.default_rng(k)
+    ii = np.concatenate([rng.integers(0, m, 30000), [0, m - 1, 0, m - 1]])
+    jj = np.concatenate([rng.integers(0, n, 30000), [0, 0, n - 1, n - 1]])
+    ref, absref = orc.gemm_f64_sampled(ac, as_, bc, bs, ii, jj)
+    assert np.all(np.abs(got[ii, jj] - (ref + bias[jj])) <= 1e-5 * (absref + np.abs(bias[jj])))
+    # every entry: subtracting the bias must leave the plain product
+    plain = host(mx.mx_linear_fwd(dev(ac), dev(as_), dev(bc), dev(bs))).astype(np.float64)
+    assert np.all(np.abs((got - bias[None, :]) - plain) <= 2.0 ** -22 * (np.abs(plain) + np.abs(bias)[None, :]) + 1e-30)
+
+
 def test_gemm_scale_bytes_and_one_hot(mx, orc):
     # operand with a single nonzero per row pins the lane <-> (row, K block) mapping of codes and scales
     m, n, k = 48, 40, 256
