@@ -235,6 +235,30 @@ def main():
         except Exception as exc:                           # reported, never fatal to the measurement above
             graph_ms = "failed: %s" % (exc,)
 
+    # forward product with the layer's bias added in its output stage, against the bare product and
+    # against the bare product followed by a separate add (outside the timed region)
+    fwd_bias = []
+    B = mx.binding
+    if not args.no_other_schedule:
+        for (name, N, D, C), st in zip(layers, steps_obj):
+            bias = torch.randn(C, device="cuda")
+            bias_out = bias.to(st.y.dtype)
+            runs = {"fused_us": lambda: B.mx_linear_fwd_bias(st.xq, st.xs, st.wq, st.ws, bias, out=st.y, workspace=st.workspace),
+                    "bare_us": lambda: B.mx_linear_fwd(st.xq, st.xs, st.wq, st.ws, out=st.y, workspace=st.workspace),
+                    "bare_then_add_us": lambda: B.mx_linear_fwd(st.xq, st.xs, st.wq, st.ws, out=st.y, workspace=st.workspace).add_(bias_out)}
+            row = {"layer": name, "shape": [N, C, D]}
+            for key, fn in runs.items():
+                for _ in range(3):
+                    fn()
+                e0, e1 = ev(), ev()
+                e0.record()
+                for _ in range(10):
+                    fn()
+                e1.record()
+                torch.cuda.synchronize()
+                row[key] = round(e0.elapsed_time(e1) / 10 * 1e3, 1)
+            fwd_bias.append(row)
+
     # Q-EMA weight quantizer (Sec. 5), outside the timed region: the four weights of the block, one
     # update + quantization each, as a training step with Q-EMA would issue them
     qema = []
@@ -402,6 +426,7 @@ def main():
                        "ms_per_step": quant_ms, "bytes_per_step": q_bytes, "alu": quant_alu},
         "gemm_ms_per_step": gemm_ms,
         "launches": launches,
+        "forward_with_bias": fwd_bias,
         "qema_weight_quant": qema,
         "oscillation_detection": osc,
         "other_schedule": None if other_ms is None else {
