@@ -416,7 +416,7 @@ def main():
             args.workload, layers[0][1], ",".join("%s %d->%d" % (n, d, c) for (n, _, d, c) in layers)),
             "quantizers": "Q1,Q2 RTN; Q3..Q6 stochastic (Philox4x32-10); truncation-free scale; double quantization",
             "streams": args.streams, "steps_with_kernel_events": n_recorded},
-        "roofline": {"bound": "mfma", "kernel": "mx_gemm_pingpong_kernel (12 launches per step)",
+        "roofline": {"bound": "mfma", "kernel": "mx_gemm_pingpong_kernel<false> (12 launches per step)",
                      "achieved": achieved, "peak": PEAK_FP4_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_FP4_TFLOPS,
                      "flops_per_launch": total_flops / n_gemm, "avg_launch_ms": gemm_ms / n_gemm,
