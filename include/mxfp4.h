@@ -117,6 +117,13 @@ int mx_quantize_transposed(const void* src, int dtype, int64_t rows, int64_t col
  *           keeps its arguments, so a host-side seed would repeat the same draws on every replay;
  *           with seed_dev the caller changes the word between replays (by a kernel or a copy on the
  *           same stream) and every replay rounds with fresh numbers.  The word is only read.
+ *   col_sums   NULL, or DEVICE out, FP32 [cols]: the column sums of the source, sum over r of src[r][c],
+ *           taken from the values the quantizer has loaded anyway (for dY this is the gradient of the
+ *           layer's bias, which otherwise costs its own pass over dY).  FP32 sums in a fixed order
+ *           (4 rows per lane, 8 lanes, 8 waves; then the 256-row blocks as eight contiguous runs, each
+ *           in index order, and the eight runs in order): a call repeats bit for bit.  Needs a source (MX_ERR_MODE with row_codes_in) and
+ *   col_sum_workspace   DEVICE scratch of mx_column_sum_workspace_bytes(rows, cols) bytes
+ *           (MX_ERR_WORKSPACE if NULL); a second, small kernel on the same stream finishes the sums.
  * All jobs must read the same kind of source: all F32, all BF16 (else MX_ERR_DTYPE), or all from
  * row_codes_in (else MX_ERR_MODE).  Any error of a single job is returned as that call would return
  * it, and nothing is launched.
@@ -138,9 +145,12 @@ typedef struct mx_transposed_job {
     uint64_t seed;
     uint64_t index_base;
     const uint64_t* seed_dev;
+    float* col_sums;
+    float* col_sum_workspace;
 } mx_transposed_job;
 int mx_quantize_transposed_batch(const mx_transposed_job* jobs, int count,
                 int round_t, int round_row, int scale_mode, void* stream);
+size_t mx_column_sum_workspace_bytes(int64_t rows, int64_t cols);
 
 /*
  * The three products (Sec. 3.3, Eqs. 3-5), FP32 accumulation on the

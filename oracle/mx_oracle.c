@@ -498,6 +498,18 @@ void orc_quant_confidence(const float* w, int64_t rows, int64_t cols, int64_t ld
         }
 }
 
+/* Column sums of a matrix, out[c] = sum over r of x[r][c], rows in index order, FP64.  For the
+ * gradient dY of a linear layer's output (Sec. 3.3) this is the gradient of the layer's bias; the
+ * layer's products themselves carry no bias. */
+void orc_column_sums(const float* x, int64_t rows, int64_t cols, int64_t ld, double* out)
+{
+    for (int64_t c = 0; c < cols; ++c) {
+        double s = 0.0;
+        for (int64_t r = 0; r < rows; ++r) s += (double)x[r * ld + c];
+        out[c] = s;
+    }
+}
+
 double orc_rate_of_change_term(const float* x, int64_t rows, int64_t cols, int64_t ld, float* x_prev)
 {
     double diff2 = 0.0, prev2 = 0.0;

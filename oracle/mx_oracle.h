@@ -161,6 +161,7 @@ void orc_quant_confidence(const float* w, int64_t rows, int64_t cols, int64_t ld
  * Returns ||x - x_prev||_F / ||x_prev||_F in FP64 (differences of FP32 values are exact in FP64;
  * the sums of squares run in FP64 in index order), then sets x_prev = x.  x_prev is dense
  * [rows x cols].  A zero ||x_prev|| gives 0 if the difference is zero too, +infinity otherwise. */
+void orc_column_sums(const float* x, int64_t rows, int64_t cols, int64_t ld, double* out);
 double orc_rate_of_change_term(const float* x, int64_t rows, int64_t cols, int64_t ld, float* x_prev);
 
 /* X_i = P_i * 2^s (Sec. 3.1), exact in double. */

@@ -80,6 +80,8 @@ def lib():
         L.orc_oscillation_accumulate.argtypes = [_f32p, _i64, _i64, _i64, _u8p, _u8p, _f32p, _f32p, _f32p, _f32p, _int]
         L.orc_quant_confidence.restype = None
         L.orc_quant_confidence.argtypes = [_f32p, _i64, _i64, _i64, _int, _f32p, ctypes.POINTER(ctypes.c_uint64), _int]
+        L.orc_column_sums.restype = None
+        L.orc_column_sums.argtypes = [_f32p, _i64, _i64, _i64, _f64p]
         L.orc_rate_of_change_term.restype = ctypes.c_double
         L.orc_rate_of_change_term.argtypes = [_f32p, _i64, _i64, _i64, _f32p]
         L.orc_ramping_adamw_step.restype = None
@@ -271,6 +273,15 @@ def quant_confidence(w, scale_mode=SCALE_TRUNCFREE, bins=0):
     lib().orc_quant_confidence(_p(w, _f32p), rows, cols, w.strides[0] // 4, int(scale_mode), _p(conf, _f32p),
                                hist.ctypes.data_as(ctypes.POINTER(ctypes.c_uint64)) if bins > 0 else None, int(bins))
     return (conf, hist) if bins > 0 else conf
+
+
+def column_sums(x):
+    """out[c] = sum over r of x[r][c], FP64 (the bias gradient when x is dY)."""
+    x = _f32(x)
+    rows, cols = x.shape
+    out = np.zeros(cols, np.float64)
+    lib().orc_column_sums(_p(x, _f32p), rows, cols, x.strides[0] // 4, _p(out, _f64p))
+    return out
 
 
 def rate_of_change_term(x, x_prev):

@@ -24,7 +24,7 @@ ROUND_RTN, ROUND_SR = 0, 1
 SCALE_TRUNCFREE, SCALE_FLOOR = 0, 1
 GEMM_FWD, GEMM_BWD_DX, GEMM_BWD_DW = 0, 1, 2
 
-EXPORTS = ["mx_quantize", "mx_quantize_transposed", "mx_quantize_transposed_batch", "mx_linear_fwd", "mx_linear_fwd_bias", "mx_linear_bwd_dx",
+EXPORTS = ["mx_quantize", "mx_quantize_transposed", "mx_quantize_transposed_batch", "mx_column_sum_workspace_bytes", "mx_linear_fwd", "mx_linear_fwd_bias", "mx_linear_bwd_dx",
            "mx_linear_bwd_dw", "mx_ema_weight_quant", "mx_linear_workspace_bytes",
            "mx_oscillation_accumulate", "mx_ramping_factor",
            "mx_ramping_adamw_step", "mx_quant_confidence", "mx_rate_of_change_workspace_bytes", "mx_rate_of_change_step",
@@ -38,7 +38,8 @@ class _TransposedJob(ctypes.Structure):
                 ("tensor_id_t", ctypes.c_uint32), ("pre_quant", ctypes.c_int), ("codes_row", ctypes.c_void_p),
                 ("scales_row", ctypes.c_void_p), ("tensor_id_row", ctypes.c_uint32),
                 ("row_codes_in", ctypes.c_void_p), ("row_scales_in", ctypes.c_void_p),
-                ("seed", ctypes.c_uint64), ("index_base", ctypes.c_uint64), ("seed_dev", ctypes.c_void_p)]
+                ("seed", ctypes.c_uint64), ("index_base", ctypes.c_uint64), ("seed_dev", ctypes.c_void_p),
+                ("col_sums", ctypes.c_void_p), ("col_sum_workspace", ctypes.c_void_p)]
 
 
 class MxError(RuntimeError):
@@ -73,6 +74,8 @@ def lib():
         fn = getattr(L, name)
         fn.restype = ci
         fn.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, ci, i64, vp, sz, vp]
+    L.mx_column_sum_workspace_bytes.restype = sz
+    L.mx_column_sum_workspace_bytes.argtypes = [i64, i64]
     L.mx_linear_fwd_bias.restype = ci
     L.mx_linear_fwd_bias.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, vp, ci, i64, vp, sz, vp]
     L.mx_ema_weight_quant.restype = ci
@@ -194,11 +197,13 @@ def mx_quantize_transposed(src, round_t=ROUND_SR, tensor_id_t=0, pre_quant=1, wa
 def mx_quantize_transposed_batch(jobs, round_t=ROUND_SR, round_row=ROUND_RTN, scale_mode=SCALE_TRUNCFREE, stream=None):
     """Several transposed quantizations in one launch.  jobs: list of dicts with the keys
     src, out=(codes_t, scales_t, codes_row, scales_row) and optionally tensor_id_t, tensor_id_row,
-    pre_quant (1), seed (0), index_base (0); the roundings and the scale rule are shared.
+    pre_quant (1), seed (0), index_base (0), col_sums (a float32 tensor of `cols` values that receives the
+    column sums of src; col_sum_workspace optional); the roundings and the scale rule are shared.
     Instead of src a job may give row_in=(codes, scales) and shape=(rows, cols).  seed may be a
     one-element int64 device tensor: the kernel then reads the seed from it when it runs
     (seed_dev of the C ABI), which is what a launch recorded into a graph needs."""
     arr = (_TransposedJob * len(jobs))()
+    keep = []                                      # scratch made here lives until the launch is enqueued
     for j, job in zip(arr, jobs):
         src = job.get("src")
         codes_t, scales_t, codes_row, scales_row = job["out"]
@@ -222,6 +227,17 @@ def mx_quantize_transposed_batch(jobs, round_t=ROUND_SR, round_row=ROUND_RTN, sc
             j.seed, j.seed_dev = 0, seed.data_ptr()
         else:
             j.seed, j.seed_dev = seed, None
+        col_sums = job.get("col_sums")
+        j.col_sums = j.col_sum_workspace = None
+        if col_sums is not None:
+            if col_sums.dtype != torch.float32 or not col_sums.is_contiguous() or col_sums.numel() != cols:
+                raise ValueError("col_sums must be a contiguous float32 tensor of `cols` values")
+            scratch = job.get("col_sum_workspace")
+            need = int(lib().mx_column_sum_workspace_bytes(rows, cols))
+            if scratch is None or scratch.numel() * scratch.element_size() < need:
+                scratch = torch.empty(need // 4, dtype=torch.float32, device=col_sums.device)
+            keep.append(scratch)
+            j.col_sums, j.col_sum_workspace = col_sums.data_ptr(), scratch.data_ptr()
     rc = lib().mx_quantize_transposed_batch(arr, len(jobs), round_t, round_row, scale_mode, _stream(stream))
     _check("mx_quantize_transposed_batch", rc)
 

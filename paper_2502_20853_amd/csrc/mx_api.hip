@@ -162,11 +162,23 @@ int mx_quantize_transposed_batch(const mx_transposed_job* jobs, int count,
         if (rc != MX_OK) return rc;
         if (q.seed_dev && !aligned(q.seed_dev, 8)) return MX_ERR_ALIGN;
         p[j].seed_dev = q.seed_dev;
+        if (q.col_sums) {
+            if (!q.src) return MX_ERR_MODE;                           // sums are those of a source tensor
+            if (!q.col_sum_workspace) return MX_ERR_WORKSPACE;
+            if (!aligned(q.col_sums, 4) || !aligned(q.col_sum_workspace, 4)) return MX_ERR_ALIGN;
+            p[j].col_sums = q.col_sums; p[j].col_sum_workspace = q.col_sum_workspace;
+        }
         // one kernel serves the launch: the jobs must read the same kind of source
         if ((p[j].row_codes_in != nullptr) != (p[0].row_codes_in != nullptr)) return MX_ERR_MODE;
         if (p[j].bf16 != p[0].bf16) return MX_ERR_DTYPE;
     }
     return hip_status(mxl::launch_quantize_tile_batch(p, count, static_cast<hipStream_t>(stream)));
+}
+
+size_t mx_column_sum_workspace_bytes(int64_t rows, int64_t cols)
+{
+    if (rows <= 0 || cols <= 0) return 0;
+    return mxl::column_sum_workspace_bytes(rows, cols);
 }
 
 int mx_linear_fwd(const uint8_t* xq, const uint8_t* xs, const uint8_t* wq, const uint8_t* ws,

@@ -57,6 +57,7 @@ __device__ __forceinline__ float fwd_scale(uint32_t byte)
 //     round-toward-plus-infinity on |x|.
 __device__ __forceinline__ void f32_round_toward_plus_inf()  { __builtin_amdgcn_s_setreg(0x801, 1); }   // MODE[1:0]
 __device__ __forceinline__ void f32_round_toward_minus_inf() { __builtin_amdgcn_s_setreg(0x801, 2); }
+__device__ __forceinline__ void f32_round_to_nearest_even()  { __builtin_amdgcn_s_setreg(0x801, 0); }
 
 constexpr uint32_t GRID_MAX_BITS = 0x01C00000u;      // 6 * 2^-126
 

@@ -39,6 +39,8 @@ struct QuantTileParams {
     uint64_t seed;
     uint64_t index_base;
     const uint64_t* seed_dev = nullptr;   // device word that replaces `seed` when set
+    float* col_sums = nullptr;            // [cols] column sums of the source (needs a source), with
+    float* col_sum_workspace = nullptr;   // column_sum_workspace_bytes(rows, cols) of scratch
 };
 
 // C[m x n] = A[m x k] . B[n x k]^T, operands packed MXFP4 along k.
@@ -59,6 +61,7 @@ struct GemmParams {
 hipError_t launch_quantize_rows(const QuantRowsParams& p, hipStream_t st);
 hipError_t launch_ema_quantize(const QuantRowsParams& p, float* ema, float beta, int update_ema, hipStream_t st);
 hipError_t launch_quantize_tile(const QuantTileParams& p, hipStream_t st);
+size_t column_sum_workspace_bytes(int64_t rows, int64_t cols);
 // Up to 4 tensors in one launch; they must share source kind, roundings and scale rule.
 hipError_t launch_quantize_tile_batch(const QuantTileParams* jobs, int count, hipStream_t st);
 hipError_t launch_dequantize(const uint8_t* codes, const uint8_t* scales, int64_t rows, int64_t cols,

@@ -170,6 +170,8 @@ constexpr int ST_COL_OFF = 256 * ST_PITCH;          // transposed     [256][ST_P
 constexpr int ST_SROW_OFF = 2 * 256 * ST_PITCH;     // row scales     [256][8]
 constexpr int ST_SCOL_OFF = ST_SROW_OFF + 256 * 8;  // transposed scales [256][8]
 constexpr int ST_BYTES = ST_SCOL_OFF + 256 * 8;     // 77824: two workgroups per CU
+constexpr int ST_CSUM_OFF = ST_BYTES;               // COLSUM instances: column sums per wave, [8][128] floats
+constexpr int ST_BYTES_CSUM = ST_BYTES + 8 * 128 * 4; // 81920: still two workgroups per CU
 
 struct TileArgs {
     const void* src;
@@ -189,6 +191,7 @@ struct TileArgs {
     uint32_t k0, k1, tensor_id_t, tensor_id_row;
     uint64_t index_base;
     const uint32_t* seed_dev;  // when set: the two key words are read from here instead of k0, k1
+    float* col_sum_partials;   // COLSUM instances: [ceil(rows / 256)][cols] sums of the source over 256-row blocks, or null
 };
 
 __device__ __forceinline__ uint32_t xor_lane_max(uint32_t v, int mask)
@@ -240,6 +243,19 @@ __device__ __forceinline__ void write_staged(const uint8_t* codes_st, const uint
     }
 }
 
+// Sum of v over the 8 lanes that share lane % 8 (the 8 row groups of a wave tile), in a fixed order,
+// returned in all of them: the partner 8 lanes away inside a row of 16 (DPP rotate), then the rows of
+// 16 and the halves of the wave (lane-swap instructions; a swap of a register with its copy leaves
+// the two partners' values side by side).
+__device__ __forceinline__ float sum_over_row_groups(float v)
+{
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x128, 0xF, 0xF, true));   // row_ror:8
+    const auto p16 = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    v = __uint_as_float(p16[0]) + __uint_as_float(p16[1]);
+    const auto p32 = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(p32[0]) + __uint_as_float(p32[1]);
+}
+
 // Up to TILE_BATCH_MAX tensors per launch (e.g. the activation and the weight of a layer: one launch,
 // and the small tensor's workgroups fill the last round of the large one's).  first[j] is the first
 // workgroup of job j (0xFFFFFFFF for unused slots); all jobs share the template parameters.
@@ -250,7 +266,9 @@ struct TileBatch {
 };
 
 // SRC: 0 = FP32 source, 1 = bf16 source, 2 = packed row result given
-template <int SRC, bool ROW_SR, bool T_SR, bool FLOOR>
+// COLSUM: also the column sums of the source (a bias gradient is that of dY), per 256-row block; a
+// separate instance, so that the plain quantizer's code does not change with this feature.
+template <int SRC, bool ROW_SR, bool T_SR, bool FLOOR, bool COLSUM = false>
 __global__ __launch_bounds__(TILE_THREADS, 4) void quantize_tile_kernel(TileBatch batch)
 {
     uint32_t job = 0;
@@ -265,7 +283,7 @@ __global__ __launch_bounds__(TILE_THREADS, 4) void quantize_tile_kernel(TileBatc
         k0 = __builtin_amdgcn_readfirstlane(a.seed_dev[0]);
         k1 = __builtin_amdgcn_readfirstlane(a.seed_dev[1]);
     }
-    __shared__ __attribute__((aligned(16))) uint8_t st[ST_BYTES];
+    __shared__ __attribute__((aligned(16))) uint8_t st[COLSUM ? ST_BYTES_CSUM : ST_BYTES];
     // FP32 sources need the rounding mode of each rule (switched per phase when they differ).
     // bf16 and packed sources scale exactly wherever a round_D threshold is near (8 significant
     // bits), so there the mode of round_S, if any, serves the whole kernel.
@@ -329,6 +347,20 @@ __global__ __launch_bounds__(TILE_THREADS, 4) void quantize_tile_kernel(TileBatc
                         else          x[j] = load8(static_cast<const float*>(a.src) + off);
                     }
                 }
+            }
+            // ---- column sums of the source over this wave's 32 rows -------------
+            if (COLSUM && a.col_sum_partials != nullptr) {
+                f32_round_to_nearest_even();
+                float cs[8];
+#pragma unroll
+                for (int t = 0; t < 8; ++t)
+                    cs[t] = sum_over_row_groups(((x[0].v[t] + x[1].v[t]) + x[2].v[t]) + x[3].v[t]);
+                if (rg == 0) {
+                    float* dst = reinterpret_cast<float*>(st + ST_CSUM_OFF) + wr * 128 + lcol0;
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) dst[t] = cs[t];
+                }
+                if (!SWITCH_MODES) set_round_mode_for<(ROW_SR || T_SR)>();
             }
             // ---- 1x32 quantizer of the same elements ---------------------------
             if (want_row || a.pre_quant) {
@@ -410,6 +442,37 @@ __global__ __launch_bounds__(TILE_THREADS, 4) void quantize_tile_kernel(TileBatc
     write_staged(st + ST_COL_OFF, st + ST_SCOL_OFF, ncols_here, nrows_here >> 5,
                  a.codes_t + (size_t)mcol0 * half_rows + (mrow0 >> 1), half_rows,
                  a.scales_t + (size_t)mcol0 * grp_rows + (mrow0 >> 5), grp_rows, tid);
+    if (COLSUM && a.col_sum_partials != nullptr && (uint32_t)tid < ncols_here) {
+        // the waves that had rows, in order; one value per column of this 256-row block
+        const float* cs = reinterpret_cast<const float*>(st + ST_CSUM_OFF) + tid;
+        float s = cs[0];
+        for (uint32_t w = 1; w < (nrows_here >> 5); ++w) s += cs[w * 128];
+        a.col_sum_partials[(size_t)row_block * a.cols + mcol0 + tid] = s;
+    }
+}
+
+// Sums the per-block column sums in a fixed order: a workgroup owns 32 columns; each of its 8 parts
+// (32 lanes) adds up a contiguous eighth of the blocks in index order (independent loads, 128 bytes
+// per row of 32 lanes), then the eight parts are added in order.
+__global__ __launch_bounds__(256) void column_sum_finish_kernel(const float* partials, uint32_t blocks, uint32_t cols, float* out)
+{
+    __shared__ float part[8][32];
+    const uint32_t lc = threadIdx.x & 31u, p = threadIdx.x >> 5;
+    const uint32_t c = blockIdx.x * 32u + lc;
+    const uint32_t per = (blocks + 7u) / 8u;
+    float s = 0.f;
+    if (c < cols) {
+        const uint32_t b0 = min(blocks, p * per), b1 = min(blocks, b0 + per);
+        for (uint32_t b = b0; b < b1; ++b) s += partials[(size_t)b * cols + c];
+    }
+    part[p][lc] = s;
+    __syncthreads();
+    if (p == 0 && c < cols) {
+        float t = part[0][lc];
+#pragma unroll
+        for (int q = 1; q < 8; ++q) t += part[q][lc];
+        out[c] = t;
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -732,17 +795,24 @@ hipError_t launch_ema_quantize(const QuantRowsParams& p, float* ema, float beta,
     return hipGetLastError();
 }
 
-template <int SRC, bool FL>
-static void launch_tile_src(const TileBatch& a, bool row_sr, bool t_sr, dim3 grid, hipStream_t st)
+template <int SRC, bool FL, bool CS>
+static void launch_tile_flags(const TileBatch& a, bool row_sr, bool t_sr, dim3 grid, hipStream_t st)
 {
     dim3 block(TILE_THREADS);
     if (row_sr) {
-        if (t_sr) hipLaunchKernelGGL((quantize_tile_kernel<SRC, true, true, FL>), grid, block, 0, st, a);
-        else      hipLaunchKernelGGL((quantize_tile_kernel<SRC, true, false, FL>), grid, block, 0, st, a);
+        if (t_sr) hipLaunchKernelGGL((quantize_tile_kernel<SRC, true, true, FL, CS>), grid, block, 0, st, a);
+        else      hipLaunchKernelGGL((quantize_tile_kernel<SRC, true, false, FL, CS>), grid, block, 0, st, a);
     } else {
-        if (t_sr) hipLaunchKernelGGL((quantize_tile_kernel<SRC, false, true, FL>), grid, block, 0, st, a);
-        else      hipLaunchKernelGGL((quantize_tile_kernel<SRC, false, false, FL>), grid, block, 0, st, a);
+        if (t_sr) hipLaunchKernelGGL((quantize_tile_kernel<SRC, false, true, FL, CS>), grid, block, 0, st, a);
+        else      hipLaunchKernelGGL((quantize_tile_kernel<SRC, false, false, FL, CS>), grid, block, 0, st, a);
     }
+}
+
+template <int SRC, bool FL>
+static void launch_tile_src(const TileBatch& a, bool row_sr, bool t_sr, bool col_sums, dim3 grid, hipStream_t st)
+{
+    if (SRC != 2 && col_sums) launch_tile_flags<SRC, FL, (SRC != 2)>(a, row_sr, t_sr, grid, st);
+    else                      launch_tile_flags<SRC, FL, false>(a, row_sr, t_sr, grid, st);
 }
 
 // Fills the kernel arguments of one tensor; returns its number of workgroups.
@@ -755,6 +825,7 @@ static uint32_t make_tile_args(const QuantTileParams& p, TileArgs& a)
     a.pre_quant = p.pre_quant;
     a.k0 = (uint32_t)p.seed; a.k1 = (uint32_t)(p.seed >> 32);
     a.seed_dev = reinterpret_cast<const uint32_t*>(p.seed_dev);
+    a.col_sum_partials = p.col_sums ? p.col_sum_workspace : nullptr;
     a.tensor_id_t = p.tensor_id_t; a.tensor_id_row = p.tensor_id_row; a.index_base = p.index_base;
     // Macro tile of a workgroup (8 waves): 256 rows x 128 columns (whole 128-byte lines of the
     // transposed codes, 64-byte pieces of the row codes; measured a few percent faster than
@@ -781,6 +852,7 @@ hipError_t launch_quantize_tile_batch(const QuantTileParams* jobs, int count, hi
     const bool row_sr = p.row_codes_in ? false : p.sr_row;
     TileBatch b{};
     uint32_t blocks = 0;
+    bool col_sums = false;
     for (int j = 0; j < TILE_BATCH_MAX; ++j) {
         b.first[j] = 0xFFFFFFFFu;
         if (j >= count) continue;
@@ -791,18 +863,32 @@ hipError_t launch_quantize_tile_batch(const QuantTileParams* jobs, int count, hi
             return hipErrorInvalidValue;
         b.first[j] = blocks;
         blocks += make_tile_args(q, b.job[j]);
+        col_sums = col_sums || q.col_sums != nullptr;
     }
     dim3 grid(blocks);
     if (p.floor_mode) {
-        if (p.row_codes_in)  launch_tile_src<2, true>(b, row_sr, p.sr_t, grid, st);
-        else if (p.bf16)     launch_tile_src<1, true>(b, row_sr, p.sr_t, grid, st);
-        else                 launch_tile_src<0, true>(b, row_sr, p.sr_t, grid, st);
+        if (p.row_codes_in)  launch_tile_src<2, true>(b, row_sr, p.sr_t, col_sums, grid, st);
+        else if (p.bf16)     launch_tile_src<1, true>(b, row_sr, p.sr_t, col_sums, grid, st);
+        else                 launch_tile_src<0, true>(b, row_sr, p.sr_t, col_sums, grid, st);
     } else {
-        if (p.row_codes_in)  launch_tile_src<2, false>(b, row_sr, p.sr_t, grid, st);
-        else if (p.bf16)     launch_tile_src<1, false>(b, row_sr, p.sr_t, grid, st);
-        else                 launch_tile_src<0, false>(b, row_sr, p.sr_t, grid, st);
+        if (p.row_codes_in)  launch_tile_src<2, false>(b, row_sr, p.sr_t, col_sums, grid, st);
+        else if (p.bf16)     launch_tile_src<1, false>(b, row_sr, p.sr_t, col_sums, grid, st);
+        else                 launch_tile_src<0, false>(b, row_sr, p.sr_t, col_sums, grid, st);
     }
-    return hipGetLastError();
+    hipError_t e = hipGetLastError();
+    for (int j = 0; j < count && e == hipSuccess; ++j) {
+        const QuantTileParams& q = jobs[j];
+        if (!q.col_sums) continue;
+        hipLaunchKernelGGL(column_sum_finish_kernel, dim3((unsigned)((q.cols + 31) / 32)), dim3(256), 0, st,
+                           q.col_sum_workspace, (uint32_t)((q.rows + 255) / 256), (uint32_t)q.cols, q.col_sums);
+        e = hipGetLastError();
+    }
+    return e;
+}
+
+size_t column_sum_workspace_bytes(int64_t rows, int64_t cols)
+{
+    return (size_t)((rows + 255) / 256) * (size_t)cols * sizeof(float);
 }
 
 hipError_t launch_quantize_tile(const QuantTileParams& p, hipStream_t st)

@@ -58,13 +58,22 @@ class _MxLinearFn(torch.autograd.Function):
         xtq, xts, wtq, wts = ctx.saved_tensors
         mod, N = ctx.mod, ctx.N
         D, C, Np = xtq.shape[0], wtq.shape[1] * 2, xtq.shape[1] * 2
-        dbias = None
-        if ctx.bias_dtype is not None and ctx.needs_input_grad[2]:
-            dbias = dy.sum(dim=0, dtype=torch.float32).to(ctx.bias_dtype)      # the bias is outside the quantized products
         dy = _pad_rows(dy.contiguous(), Np)
         rnd = B.ROUND_SR if mod.flow == TETRAJET else B.ROUND_RTN
-        dytq, dyts, dyq, dys = B.mx_quantize_transposed(dy, rnd, Q5, 0, True, rnd, Q3,
-                                                        scale_mode=mod.scale_mode, seed=ctx.seed)
+        dbias = None
+        if ctx.bias_dtype is not None and ctx.needs_input_grad[2]:
+            # the bias gradient is the column sum of dY: taken by the quantizer from the values it loads
+            # (the zero rows of the padding add nothing)
+            u8 = lambda *shape: torch.empty(shape, dtype=torch.uint8, device=dy.device)
+            dytq, dyts, dyq, dys = u8(C, Np // 2), u8(C, Np // 32), u8(Np, C // 2), u8(Np, C // 32)
+            dbias = torch.empty(C, dtype=torch.float32, device=dy.device)
+            B.mx_quantize_transposed_batch(
+                [{"src": dy, "out": (dytq, dyts, dyq, dys), "tensor_id_t": Q5, "tensor_id_row": Q3, "pre_quant": 0,
+                  "seed": ctx.seed, "col_sums": dbias}], rnd, rnd, mod.scale_mode)
+            dbias = dbias.to(ctx.bias_dtype)
+        else:
+            dytq, dyts, dyq, dys = B.mx_quantize_transposed(dy, rnd, Q5, 0, True, rnd, Q3,
+                                                            scale_mode=mod.scale_mode, seed=ctx.seed)
         dx = dw = None
         if ctx.needs_input_grad[0]:
             dx = B.mx_linear_bwd_dx(dyq, dys, wtq, wts, out_dtype=ctx.x_dtype,

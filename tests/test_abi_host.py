@@ -206,6 +206,7 @@ def test_transposed_batch_rejects(L):
         j.tensor_id_t, j.tensor_id_row, j.pre_quant = 6, 1, 1
         j.row_codes_in = j.row_scales_in = None
         j.seed, j.index_base, j.seed_dev = 0, 0, None
+        j.col_sums = j.col_sum_workspace = None
         for k, v in kw.items():
             setattr(j, k, v)
         return j
@@ -224,3 +225,8 @@ def test_transposed_batch_rejects(L):
     assert call([job(), given]) == -4                              # nor a source with a given row result
     assert call([job(index_base=4)]) == -5                         # stochastic streams start on a block of 8
     assert call([job(seed_dev=FAKE + 4)]) == -5                    # a device seed is a 64-bit word, 8-byte aligned
+    given2 = job(src=None, codes_row=None, scales_row=None, row_codes_in=FAKE, row_scales_in=FAKE, col_sums=FAKE, col_sum_workspace=FAKE)
+    assert call([given2]) == -4                                    # column sums are those of a source tensor
+    assert call([job(col_sums=FAKE)]) == -6                        # and need their scratch
+    assert call([job(col_sums=FAKE + 2, col_sum_workspace=FAKE)]) == -5
+    assert L.mx_column_sum_workspace_bytes(50432, 2304) == 197 * 2304 * 4 and L.mx_column_sum_workspace_bytes(0, 64) == 0

@@ -510,6 +510,55 @@ def test_config_vit_large_qema_layer(mx, orc):
     _check_layer(mx, orc, step, xt, wt, dy, y, dx, dw, N, D, C, True, True, "vit_large proj q-ema")
 
 
+# ------------------------------------------------- column sums with the fused quantizer ----
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("rows,cols", [(32, 32), (288, 320), (544, 96), (4096 + 96, 4096 + 160)])
+def test_column_sums_with_the_fused_quantizer(mx, orc, dtype, rows, cols):
+    """col_sums of the batched entry point: the sums of the source columns against FP64 (tolerance of an
+    FP32 sum), bit-identical on a second call, and packed outputs unchanged by the option.  Shapes with
+    ragged 256-row blocks, narrow tiles, and a wide launch with a narrow tail."""
+    x = mixed_matrix(rows, cols + 8, seed=90 + rows, dtype=dtype)
+    X = dev(x, dtype)[:, :cols]
+    want = orc.quantize_transposed(np.ascontiguousarray(x[:, :cols]), round_t=1, tensor_id_t=5, pre_quant=0,
+                                   round_row=1, tensor_id_row=3, seed=9)
+    sums = []
+    for rep in range(2):
+        out = tuple(torch.empty(w.shape, dtype=torch.uint8, device="cuda") for w in want)
+        cs = torch.full((cols,), float("nan"), device="cuda")
+        mx.mx_quantize_transposed_batch([{"src": X, "out": out, "tensor_id_t": 5, "tensor_id_row": 3, "pre_quant": 0,
+                                          "seed": 9, "col_sums": cs}], 1, 1, 0)
+        for g, w, nm in zip(out, want, ("codes_t", "scales_t", "codes_row", "scales_row")):
+            assert_same_bytes(g, w, nm)
+        sums.append(host(cs))
+    assert np.array_equal(sums[0], sums[1])
+    ref = orc.column_sums(np.ascontiguousarray(x[:, :cols]))
+    absref = np.abs(x[:, :cols]).astype(np.float64).sum(0)
+    # every value passes at most 4 + 3 + 8 additions inside a 256-row block, then fewer than one per block plus 8
+    tol = (32 + (rows + 255) // 256) * 2.0 ** -24 * absref
+    assert np.all(np.abs(sums[0].astype(np.float64) - ref) <= tol + 1e-30), np.max(np.abs(sums[0] - ref) / (absref + 1e-300))
+
+
+def test_column_sums_in_a_batch_of_two(mx, orc):
+    """Two tensors in one launch, only the second with column sums; X-type flags (row RTN, double quantization)."""
+    xa = mixed_matrix(320, 256, seed=95, dtype="bf16")
+    xb = mixed_matrix(544, 128, seed=96, dtype="bf16")
+    outs, wants = [], []
+    for x in (xa, xb):
+        w = orc.quantize_transposed(x, round_t=1, tensor_id_t=6, pre_quant=1, round_row=0, tensor_id_row=1, seed=4)
+        wants.append(w)
+        outs.append(tuple(torch.empty(t.shape, dtype=torch.uint8, device="cuda") for t in w))
+    cs = torch.zeros(128, device="cuda")
+    mx.mx_quantize_transposed_batch(
+        [{"src": dev(xa, "bf16"), "out": outs[0], "tensor_id_t": 6, "tensor_id_row": 1, "seed": 4},
+         {"src": dev(xb, "bf16"), "out": outs[1], "tensor_id_t": 6, "tensor_id_row": 1, "seed": 4, "col_sums": cs}], 1, 0, 0)
+    for out, want in zip(outs, wants):
+        for g, w, nm in zip(out, want, ("codes_t", "scales_t", "codes_row", "scales_row")):
+            assert_same_bytes(g, w, nm)
+    ref = orc.column_sums(xb)
+    assert np.all(np.abs(host(cs).astype(np.float64) - ref) <= 35 * 2.0 ** -24 * np.abs(xb).astype(np.float64).sum(0) + 1e-30)
+
+
 # ------------------------------------------------- seed in device memory, graph replay ----
 
 def test_device_seed_equals_host_seed(mx, orc):

@@ -824,3 +824,30 @@ def test_ramping_adamw_first_update_closed_form_and_refactor(orc):
     assert st["updates"][0] == 1 and st["acc_steps"][0] == 0
     assert abs(st["m"][0] - 0.1 * 3.0) < 1e-15                     # mean of 1, 2, 3, 6
     assert abs(st["w"][0] - (-2e-2)) < 1e-9                        # lr_w = 2 * lr
+
+
+# ------------------------------------------------------------- column sums (bias gradient) ----
+
+def test_column_sums_closed_forms(orc):
+    """Values fixed by arithmetic: x[r][c] = c + 1 sums to rows * (c + 1); x[r][c] = r to rows(rows-1)/2;
+    a sign alternating down the rows cancels (even row count) or leaves one term (odd); one element
+    alone; a strided view sums its own columns only; FP64 keeps what FP32 accumulation would lose."""
+    rows, cols = 37, 64
+    c1 = np.tile(np.arange(1, cols + 1, dtype=np.float32), (rows, 1))
+    assert np.array_equal(orc.column_sums(c1), rows * np.arange(1, cols + 1, dtype=np.float64))
+    r1 = np.tile(np.arange(rows, dtype=np.float32)[:, None], (1, cols))
+    assert np.array_equal(orc.column_sums(r1), np.full(cols, rows * (rows - 1) / 2.0))
+    alt = np.where(np.arange(rows)[:, None] % 2 == 0, 1.0, -1.0).astype(np.float32) * np.arange(1, cols + 1, dtype=np.float32)
+    assert np.array_equal(orc.column_sums(alt), np.arange(1, cols + 1, dtype=np.float64))       # 37 rows: one term left
+    assert np.array_equal(orc.column_sums(alt[:36]), np.zeros(cols))
+    one = np.zeros((rows, cols), np.float32)
+    one[29, 5] = -2.5
+    want = np.zeros(cols)
+    want[5] = -2.5
+    assert np.array_equal(orc.column_sums(one), want)
+    wide = np.arange(rows * 2 * cols, dtype=np.float32).reshape(rows, 2 * cols)
+    left = orc.column_sums(wide[:, :cols])
+    assert np.array_equal(left, (np.arange(rows, dtype=np.float64)[:, None] * 2 * cols + np.arange(cols)).sum(0))
+    big = np.full((4097, 32), 1.0, np.float32)
+    big[0] = 2.0 ** 25                                   # in FP32, 2^25 + 1 = 2^25: 4096 ones would vanish
+    assert np.array_equal(orc.column_sums(big), np.full(32, 2.0 ** 25 + 4096))
