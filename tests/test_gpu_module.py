@@ -125,27 +125,28 @@ def test_module_device_seed_equals_host_seed_and_replays_in_a_graph(mx):
     import mx_workloads as wl
     N, D, C = 96, 64, 128
     X, W, dY = wl.linear_layer(N, D, C, seed=8)
-    lins = [mx.MxLinear(D, C, bias=False, seed=0x9ABCDEF0, device_seed=ds) for ds in (False, True)]
+    lins = [mx.MxLinear(D, C, bias=True, seed=0x9ABCDEF0, device_seed=ds) for ds in (False, True)]
     for lin in lins:
         with torch.no_grad():
             lin.weight.copy_(dev(W))
+            lin.bias.copy_(dev(np.linspace(-2, 2, C, dtype=np.float32)))
 
     def eager(lin):
         x = dev(X).requires_grad_(True)
-        lin.weight.grad = None
+        lin.weight.grad = lin.bias.grad = None
         y = lin(x)
         (y * dev(dY)).sum().backward()
-        return y.detach().clone(), x.grad.clone(), lin.weight.grad.clone()
+        return y.detach().clone(), x.grad.clone(), lin.weight.grad.clone(), lin.bias.grad.clone()
 
     for call in range(2):
         a, b = eager(lins[0]), eager(lins[1])
-        for u, v, nm in zip(a, b, ("Y", "dX", "dW")):
+        for u, v, nm in zip(a, b, ("Y", "dX", "dW", "dbias")):
             assert torch.equal(u, v), (call, nm)
     # record call 3 of the device-seed module; replays are then calls 3, 4, 5 of the host-seed module
     lin = lins[1]
     xs = dev(X).requires_grad_(True)
     dys = dev(dY)
-    lin.weight.grad = None
+    lin.weight.grad = lin.bias.grad = None
     graph = torch.cuda.CUDAGraph()
     before = lin.seed_state.clone()
     with torch.cuda.graph(graph):
@@ -157,7 +158,7 @@ def test_module_device_seed_equals_host_seed_and_replays_in_a_graph(mx):
         graph.replay()
         torch.cuda.synchronize()
         want = eager(lins[0])
-        for u, v, nm in zip((ys, xs.grad, lin.weight.grad), want, ("Y", "dX", "dW")):
+        for u, v, nm in zip((ys, xs.grad, lin.weight.grad, lin.bias.grad), want, ("Y", "dX", "dW", "dbias")):
             assert torch.equal(u, v), (call, nm)
         seen.append(xs.grad.clone())
     assert not torch.equal(seen[0], seen[1]) and not torch.equal(seen[1], seen[2])
