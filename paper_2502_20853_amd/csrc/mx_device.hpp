@@ -272,6 +272,22 @@ __device__ __forceinline__ F8 load8(const uint16_t* p)   // bf16 bit patterns
     return r;
 }
 
+// The same in two steps, for loads issued ahead of their use: 4 registers hold 8 bf16 values.
+typedef uint32_t bf16x8_raw __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ bf16x8_raw load8_raw(const uint16_t* p)
+{
+    return __builtin_nontemporal_load(reinterpret_cast<const bf16x8_raw*>(p));
+}
+__device__ __forceinline__ F8 expand8(bf16x8_raw a)
+{
+    F8 r;
+    r.v[0] = __uint_as_float(a.x << 16); r.v[1] = __uint_as_float(a.x & 0xFFFF0000u);
+    r.v[2] = __uint_as_float(a.y << 16); r.v[3] = __uint_as_float(a.y & 0xFFFF0000u);
+    r.v[4] = __uint_as_float(a.z << 16); r.v[5] = __uint_as_float(a.z & 0xFFFF0000u);
+    r.v[6] = __uint_as_float(a.w << 16); r.v[7] = __uint_as_float(a.w & 0xFFFF0000u);
+    return r;
+}
+
 __device__ __forceinline__ F8 zero8()
 {
     F8 r;
