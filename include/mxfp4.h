@@ -121,7 +121,8 @@ int mx_quantize_transposed(const void* src, int dtype, int64_t rows, int64_t col
  *           taken from the values the quantizer has loaded anyway (for dY this is the gradient of the
  *           layer's bias, which otherwise costs its own pass over dY).  FP32 sums in a fixed order
  *           (4 rows per lane, 8 lanes, 8 waves; then the 256-row blocks as eight contiguous runs, each
- *           in index order, and the eight runs in order): a call repeats bit for bit.  Needs a source (MX_ERR_MODE with row_codes_in) and
+ *           in index order, and the eight runs in order): a call repeats bit for bit.  Needs a source
+ *           (MX_ERR_MODE with row_codes_in), 4-byte alignment, and
  *   col_sum_workspace   DEVICE scratch of mx_column_sum_workspace_bytes(rows, cols) bytes
  *           (MX_ERR_WORKSPACE if NULL); a second, small kernel on the same stream finishes the sums.
  * All jobs must read the same kind of source: all F32, all BF16 (else MX_ERR_DTYPE), or all from
