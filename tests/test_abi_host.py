@@ -230,3 +230,22 @@ def test_transposed_batch_rejects(L):
     assert call([job(col_sums=FAKE)]) == -6                        # and need their scratch
     assert call([job(col_sums=FAKE + 2, col_sum_workspace=FAKE)]) == -5
     assert L.mx_column_sum_workspace_bytes(50432, 2304) == 197 * 2304 * 4 and L.mx_column_sum_workspace_bytes(0, 64) == 0
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/mxfp4.h compiles as C99 on its own (no C++ or HIP types at the boundary), and a C
+    translation unit can name every declared entry point."""
+    import re
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    header = os.path.join(ROOT, "include", "mxfp4.h")
+    names = sorted(set(re.findall(r"\b(mx_[a-z0-9_]+)\s*\(", open(header).read())))
+    assert "mx_linear_fwd" in names and "mx_quantize_transposed_batch" in names
+    src = tmp_path / "use.c"
+    src.write_text('#include "mxfp4.h"\n' + "".join("void* p_%s = (void*)%s;\n" % (n, n) for n in names)
+                   + "int main(void) { mx_transposed_job j; (void)j; return 0; }\n")
+    subprocess.run([gcc, "-std=c99", "-pedantic", "-Wall", "-Werror", "-Wno-pedantic", "-I", os.path.dirname(header),
+                    "-c", str(src), "-o", str(tmp_path / "use.o")], check=True)
