@@ -605,6 +605,35 @@ def test_layer_pass_recorded_into_a_graph(mx, orc, qema):
                      "replay with seed %d" % seed)
 
 
+def test_two_streams_give_the_single_stream_results(mx, orc):
+    """Two layers run concurrently on two streams (separate buffers): every packed byte and every product
+    value equals what the same calls give one after the other on one stream (the library holds no state)."""
+    import mx_workloads as wl
+    shapes = [(2048 + 32, 256, 384), (1024 + 96, 384, 256)]
+    data = [wl.linear_layer(N, D, C, seed=40 + i, dtype="bf16", outliers=2) for i, (N, D, C) in enumerate(shapes)]
+    dev_data = [tuple(dev(t, "bf16") for t in d) for d in data]
+
+    def run(streams):
+        steps = [mx.MxLinearStep(N, D, C, out_dtype=torch.float32) for (N, D, C) in shapes]
+        torch.cuda.synchronize()
+        for rep in range(3):                             # several rounds so that the two streams really overlap
+            for st, (X, W, dY), s in zip(steps, dev_data, streams):
+                with torch.cuda.stream(s):
+                    st.forward(X, W, seed=21)
+                    st.backward(dY, seed=21)
+        torch.cuda.synchronize()
+        return [[t.clone() for t in (st.xq, st.xtq, st.wtq, st.dyq, st.dytq, st.y, st.dx, st.dw)] for st in steps]
+
+    main = torch.cuda.current_stream()
+    serial = run([main, main])
+    both = run([torch.cuda.Stream(), torch.cuda.Stream()])
+    for a_layer, b_layer in zip(serial, both):
+        for u, v in zip(a_layer, b_layer):
+            assert torch.equal(u, v)
+    xt, wt, dy = oracle_layer(orc, *data[0], seed=21)
+    assert_same_bytes(both[0][1], xt[0], "Q6 under two streams")
+
+
 # ------------------------------------------------- full size, bench launch configuration ----
 
 def test_full_size_vit_base_qkv_layer(mx, orc):
