@@ -410,11 +410,12 @@ def main():
         "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "mxfp4 (e2m1 x e8m0) products, f32 accumulate; %s sources" % cfg["dtype"],
+        "dtype": "mxfp4",
         "data": "synthetic",
         "config": {"workload": "%s: N=%d tokens, layers %s, Y/dX bf16, dW f32" % (
             args.workload, layers[0][1], ",".join("%s %d->%d" % (n, d, c) for (n, _, d, c) in layers)),
             "quantizers": "Q1,Q2 RTN; Q3..Q6 stochastic (Philox4x32-10); truncation-free scale; double quantization",
+            "arithmetic": "E2M1 elements x E8M0 group scales in the products, FP32 accumulation; %s sources" % cfg["dtype"],
             "streams": args.streams, "steps_with_kernel_events": n_recorded},
         "roofline": {"bound": "mfma", "kernel": "mx_gemm_pingpong_kernel<false> (12 launches per step)",
                      "achieved": achieved, "peak": PEAK_FP4_TFLOPS, "unit": "TFLOP/s",
