@@ -249,3 +249,11 @@ def test_header_is_plain_c(tmp_path):
                    + "int main(void) { mx_transposed_job j; (void)j; return 0; }\n")
     subprocess.run([gcc, "-std=c99", "-pedantic", "-Wall", "-Werror", "-Wno-pedantic", "-I", os.path.dirname(header),
                     "-c", str(src), "-o", str(tmp_path / "use.o")], check=True)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py --gpus N with N > 1 exits with a message before it touches a GPU."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "one GPU" in (r.stdout + r.stderr)
