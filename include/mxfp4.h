@@ -119,9 +119,12 @@ int mx_quantize_transposed(const void* src, int dtype, int64_t rows, int64_t col
  *           same stream) and every replay rounds with fresh numbers.  The word is only read.
  *   col_sums   NULL, or DEVICE out, FP32 [cols]: the column sums of the source, sum over r of src[r][c],
  *           taken from the values the quantizer has loaded anyway (for dY this is the gradient of the
- *           layer's bias, which otherwise costs its own pass over dY).  FP32 sums in a fixed order
- *           (4 rows per lane, 8 lanes, 8 waves; then the 256-row blocks as eight contiguous runs, each
- *           in index order, and the eight runs in order): a call repeats bit for bit.  Needs a source
+ *           layer's bias, which otherwise costs its own pass over dY).  FP32 sums, every addition
+ *           rounded to nearest even, in one fixed order, so that a call repeats bit for bit: rows in
+ *           blocks of 256, a block in tiles of 32 rows; in a tile, four consecutive rows left to right,
+ *           g_i = ((x[4i] + x[4i+1]) + x[4i+2]) + x[4i+3], then ((g0+g1) + (g2+g3)) + ((g4+g5) + (g6+g7));
+ *           the tiles of a block in index order; the blocks as eight contiguous runs of ceil(blocks/8),
+ *           each run in index order starting from 0, and the eight runs in index order.  Needs a source
  *           (MX_ERR_MODE with row_codes_in), 4-byte alignment, and
  *   col_sum_workspace   DEVICE scratch of mx_column_sum_workspace_bytes(rows, cols) bytes
  *           (MX_ERR_WORKSPACE if NULL); a second, small kernel on the same stream finishes the sums.
@@ -195,7 +198,11 @@ int mx_linear_bwd_dw(const uint8_t* dytq, const uint8_t* dyts, const uint8_t* xt
  * Q-EMA (Sec. 5 Eq. 8, Algorithm 1): 1x32 quantizer of the weight w[rows x cols]
  * whose scale comes from w and whose choice between the two E2M1 neighbours of
  * w/S is the one nearer to w_ema/S (q1 iff strictly nearer).  A w/S that is
- * itself an E2M1 value is kept.
+ * itself an E2M1 value is kept.  The two neighbours are the bracketing pair
+ * q1 <= w/S <= q2 of Sec. 3.2; where E2M1's spacing changes, |w/S| in (2, 2.25)
+ * or (4, 4.5), this is not the pair of the two nearest values (1.5, 2 resp.
+ * 3, 4), and the bracket is the reading taken: the result never lies beyond a
+ * representable value from w/S, and w_ema = w gives mx_quantize's RTN result.
  *   w        device, F32 or BF16, row stride ld
  *   w_ema    device, FP32, in/out, same shape and the same row stride ld
  *   update_ema  0: use w_ema as is; 1: w_ema <- beta*w_ema + (1-beta)*w (FP32,

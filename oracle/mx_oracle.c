@@ -122,7 +122,7 @@ static double scale_to_group(float x, int s, int scale_mode)
 {
     double y = ldexp((double)x, -s);
     if (scale_mode == ORC_SCALE_FLOOR) {
-        /* Eq. 2's scale can leave |y| > Q_p: "exceeding values will be truncated" */
+        /* Eq. 2's scale can leave |y| > Q_p; such values saturate at +-Q_p (Sec. 3.2) */
         if (y > 6.0) y = 6.0;
         if (y < -6.0) y = -6.0;
     }
@@ -160,6 +160,15 @@ static int round_sr_d(double y, uint32_t r16)
 
 int orc_round_sr(float y, uint32_t r16) { return round_sr_d((double)y, r16); }
 
+/* Q-EMA's choice (Algorithm 1).  The candidate pair (q1, q2) is read as the BRACKETING pair of
+ * y = w/S, q1 <= y <= q2, the pair Sec. 3.2 names with the same symbols.  Algorithm 1's wording
+ * (the two values nearest to y) and Sec. 5's (the two values of smallest error) name a different
+ * pair wherever E2M1's spacing changes: for |y| in (2, 2.25) the two nearest values are 1.5 and 2
+ * while the bracket is (2, 3), and for |y| in (4, 4.5) they are 3 and 4 while the bracket is (4, 6).
+ * The bracket is taken because the threshold that y can oscillate across is the midpoint of the two
+ * values either side of it (Sec. 4.1), because a choice outside the bracket would move the weight
+ * past a representable value that lies between it and the result, and because only the bracket
+ * makes Q-EMA with W_EMA = W identical to round_D on every input. */
 static int round_ema_d(double y, double z)
 {
     int sign = signbit(y) ? 8 : 0;

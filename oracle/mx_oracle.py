@@ -284,6 +284,41 @@ def column_sums(x):
     return out
 
 
+def column_sums_f32_ordered(x):
+    """The same column sums in FP32, added in the one order the library's interface documents for its
+    col_sums output (so that the kernel's result can be compared bit for bit, rounding mode included):
+    rows in blocks of 256, a block in tiles of 32 rows; inside a tile four consecutive rows are added
+    left to right, g_i = ((x[4i] + x[4i+1]) + x[4i+2]) + x[4i+3], the eight g_i pairwise as a balanced
+    tree ((g0 + g1) + (g2 + g3)) + ((g4 + g5) + (g6 + g7)); the tiles of a block in index order; the
+    blocks as eight contiguous runs of ceil(blocks / 8), each run added in index order starting from 0,
+    and the eight runs in index order.  Every addition rounds to nearest even.  rows % 32 == 0."""
+    x = _f32(x)
+    rows, cols = x.shape
+    assert rows % 32 == 0
+    f = np.float32
+    blocks = (rows + 255) // 256
+    partial = np.zeros((blocks, cols), f)
+    for b in range(blocks):
+        r0, r1 = b * 256, min(rows, b * 256 + 256)
+        acc = None
+        for t0 in range(r0, r1, 32):
+            g = [((x[t0 + 4 * i] + x[t0 + 4 * i + 1]) + x[t0 + 4 * i + 2]) + x[t0 + 4 * i + 3] for i in range(8)]
+            tile = ((g[0] + g[1]) + (g[2] + g[3])) + ((g[4] + g[5]) + (g[6] + g[7]))
+            acc = tile if acc is None else (acc + tile).astype(f)
+        partial[b] = acc
+    per = (blocks + 7) // 8
+    runs = []
+    for p in range(8):
+        s = np.zeros(cols, f)
+        for b in range(min(blocks, p * per), min(blocks, p * per + per)):
+            s = (s + partial[b]).astype(f)
+        runs.append(s)
+    out = runs[0]
+    for p in range(1, 8):
+        out = (out + runs[p]).astype(f)
+    return out
+
+
 def rate_of_change_term(x, x_prev):
     """||x - x_prev||_F / ||x_prev||_F (Sec. 4.1), FP64; x_prev (float32, dense, shape of x) is then set to x."""
     x = _f32(x)

@@ -1,22 +1,30 @@
-// C[m x n] = A[m x k] . B[n x k]^T on packed MXFP4 operands, FP32 accumulation
-// on gfx950's block-scaled FP4 matrix cores (V_MFMA_SCALE_F32_16X16X128_F8F6F4).
-// All three products of the layer (Eqs. 3-5, Sec. 3.3) have this form because
-// every operand is stored along its own contraction dimension.
+// C[m x n] = A[m x k] . B[n x k]^T on packed MXFP4 operands, FP32 accumulation on gfx950's
+// block-scaled FP4 matrix cores.  All three products of the layer (Eqs. 3-5, Sec. 3.3) have
+// this form because every operand is stored along its own contraction dimension.
 //
-// Kernel structure
-//   - workgroup tile BM x BN, K step 128 (= 64 bytes of codes and 4 scale bytes
-//     per row), double-buffered in LDS;
-//   - one 16x16x128 MFMA consumes, per lane, 32 consecutive K elements (16 bytes,
-//     exactly one MX group) of row (lane % 16), K block (lane / 16), and that
-//     group's E8M0 scale byte;
-//   - code tiles sit in LDS row-major with the 16-byte chunk index XOR-swizzled
-//     by (row >> 2) & 3 so that both the 16-byte stores (4 lanes per row) and
-//     the MFMA operand reads (16 rows per K block) are bank-conflict free;
-//   - scale tiles sit in LDS as [k block][row % 16][row-tile % 4] per group of
-//     four 16-row tiles, so one 32-bit LDS read hands a lane the scale bytes of
-//     four MFMAs, picked by the instruction's op_sel;
-//   - the MFMA's first operand is the B (n) side, so that a lane ends up with
-//     four consecutive n of one m and stores 8 or 16 contiguous bytes.
+// Three kernels, chosen by the launcher at the end of the file:
+//   mx_gemm_pingpong_kernel  the main path (K a multiple of 128, at least 4 K steps per K split;
+//       every ViT-B/L product): V_MFMA_SCALE_F32_32X32X64_F8F6F4, one persistent workgroup of
+//       8 waves per compute unit, tile 256 x 256, operands global -> LDS by DMA loads, two wave
+//       groups alternating between their MFMA burst and their LDS/DMA work.  Described in full
+//       above the kernel.
+//   mx_gemm_dma_kernel       K a multiple of 128 but fewer than 4 K steps per split: same MFMA and
+//       LDS layout, 4 waves, tile 256 x 128, one tile per workgroup.
+//   mx_gemm_kernel           any K that is a multiple of 32 (e.g. 192): V_MFMA_SCALE_F32_16X16X128_F8F6F4,
+//       register-staged loads, zero-filled K tail.
+// A K-split product (dW: K = tokens, small output) writes FP32 partials to the caller's workspace
+// and splitk_reduce*_kernel adds them in a fixed order.
+//
+// Common to all three:
+//   - K step 128 = 64 bytes of codes and 4 scale bytes per row;
+//   - an MFMA consumes, per lane, 32 consecutive K elements (16 bytes, exactly one MX group) of
+//     one row and that group's E8M0 scale byte (16x16x128: row lane % 16, K block lane / 16;
+//     32x32x64: row lane % 32, K block lane / 32);
+//   - code tiles sit in LDS row-major with the 16-byte chunk index XOR-swizzled by (row >> 2) & 3,
+//     so that both the 16-byte writes (4 lanes per row) and the MFMA operand reads (one chunk of
+//     16 or 32 rows) are bank-conflict free;
+//   - the MFMA's first operand is the B (n) side, so that a lane ends up with runs of four
+//     consecutive n of one m and stores 8 or 16 contiguous bytes.
 #include "mx_launch.hpp"
 
 #include <type_traits>
@@ -814,14 +822,13 @@ typedef __attribute__((address_space(3))) uint8_t lds_u8;
 // the first LDS write that might overlap, which here is the output staging that runs while the
 // next tile's loads are in flight; this kernel places every such wait itself.  And the address
 // takes the scalar-base form directly (uniform 64-bit base, 32-bit lane offset) instead of 64-bit
-// per-lane addresses.  M0 (the LDS destination) is a reserved register that compiled code of
-// this kernel does not otherwise use, so it is not listed as clobbered.
+// per-lane addresses.  M0 (the LDS destination) is listed as clobbered.
 __device__ __forceinline__ void dma_load16_at(uint32_t lds_addr, const uint8_t* base, uint32_t voff)
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
                  : "s"(lds_addr), "v"(voff), "s"(base)
-                 : "memory");
+                 : "memory", "m0");
 }
 
 // The whole tile walk of one wave; GRP (0: columns 0-127, M phase first; 1: columns 128-255, L phase

@@ -464,7 +464,9 @@ __global__ __launch_bounds__(TILE_THREADS, 4) void quantize_tile_kernel(TileBatc
                  a.codes_t + (size_t)mcol0 * half_rows + (mrow0 >> 1), half_rows,
                  a.scales_t + (size_t)mcol0 * grp_rows + (mrow0 >> 5), grp_rows, tid);
     if (COLSUM && a.col_sum_partials != nullptr && (uint32_t)tid < ncols_here) {
-        // the waves that had rows, in order; one value per column of this 256-row block
+        // the waves that had rows, in order; one value per column of this 256-row block.  Round to
+        // nearest like the per-wave sums (no quantizer arithmetic follows, the mode is not restored).
+        f32_round_to_nearest_even();
         const float* cs = reinterpret_cast<const float*>(st + ST_CSUM_OFF) + tid;
         float s = cs[0];
         for (uint32_t w = 1; w < (nrows_here >> 5); ++w) s += cs[w * 128];

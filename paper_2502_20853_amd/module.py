@@ -1,12 +1,18 @@
 """torch.autograd / nn.Module front end of the MXFP4 linear layer: the forward and backward of Eqs. 3-5
 (Sec. 3.3) as calls of the C ABI.  Plumbing only -- every quantizer and every product runs in the HIP
 library; what is saved for the backward pass is the packed 4-bit operands, not the activations."""
+import itertools
+
 import torch
 
 from . import binding as B
 from .layer import Q1, Q2, Q3, Q4, Q5, Q6
 
 TETRAJET, MICROSCALING = "tetrajet", "microscaling"
+
+# Layers are numbered in the order they are constructed; the number goes into every layer's Philox key
+# so that two layers never round with the same random numbers (see MxLinear).
+_layer_ids = itertools.count()
 
 
 def _pad_rows(t, rows):
@@ -94,14 +100,23 @@ class MxLinear(torch.nn.Module):
     bfloat16.  flow="tetrajet": deterministic forward quantizers, stochastic backward quantizers,
     double quantization (Sec. 3.3); flow="microscaling": Eqs. 6-7 (all deterministic, the backward
     operands quantized from the full-precision tensors).  qema=True takes the forward weight codes
-    from Q-EMA (Sec. 5); the moving average advances once per training-mode forward.  The stochastic
-    rounding streams are keyed by (seed, number of forward calls so far).  device_seed=True keeps that
-    key in device memory and advances it with a kernel, so that a forward + backward recorded into a
-    graph rounds with new numbers on every replay (same values as the host-side key, call for call).
+    from Q-EMA (Sec. 5); the moving average advances once per training-mode forward.
+
+    Stochastic rounding streams.  The 64-bit Philox key of a forward call and of its backward is
+    (seed & 0xFFFF) << 48 | (layer_id & 0xFFFF) << 32 | number of forward calls so far.  layer_id
+    defaults to the layer's position in the order of construction in this process, so the layers of a
+    model draw independent numbers (the unbiasedness argument of Sec. 3.4 needs the rounding of dY in
+    one layer to be independent of the rounding that produced it in the next); pass layer_id to fix
+    it, e.g. to reproduce a run with a different construction order.  device_seed=True keeps the key in
+    device memory and advances it with a kernel, so that a forward + backward recorded into a graph
+    rounds with new numbers on every replay (same values as the host-side key, call for call); each
+    forward call keeps its own copy of the key for its backward, so several forwards may precede the
+    first backward (micro-batches, a module used twice).
     """
 
     def __init__(self, in_features, out_features, bias=True, device="cuda", dtype=torch.float32,
-                 flow=TETRAJET, scale_mode=B.SCALE_TRUNCFREE, qema=False, beta=0.998, seed=0, device_seed=False):
+                 flow=TETRAJET, scale_mode=B.SCALE_TRUNCFREE, qema=False, beta=0.998, seed=0, device_seed=False,
+                 layer_id=None):
         super().__init__()
         if in_features % 32 or out_features % 32:
             raise ValueError("in_features and out_features must be multiples of 32")
@@ -115,7 +130,9 @@ class MxLinear(torch.nn.Module):
         self.register_buffer("w_ema", torch.zeros((out_features, in_features), device=device, dtype=torch.float32)
                              if qema else None)
         self.calls = 0                     # forward calls so far (host-side: reading it must not synchronize)
-        start = (((self.seed & 0xFFFFFFFF) << 32) - 1) & 0xFFFFFFFFFFFFFFFF      # one before the first key, as a 64-bit word
+        self.layer_id = next(_layer_ids) if layer_id is None else int(layer_id)
+        self.key_high = ((self.seed & 0xFFFF) << 16) | (self.layer_id & 0xFFFF)   # upper 32 bits of the Philox key
+        start = ((self.key_high << 32) - 1) & 0xFFFFFFFFFFFFFFFF                 # one before the first key, as a 64-bit word
         self.register_buffer("seed_state", torch.tensor([start - (1 << 64) if start >> 63 else start], dtype=torch.int64,
                                                         device=device) if device_seed else None)
         self._ema_started = False
@@ -155,9 +172,11 @@ class MxLinear(torch.nn.Module):
         lead = x.shape[:-1]
         x2d = x.reshape(-1, self.in_features)
         if self.seed_state is not None:
-            seed = self.seed_state.add_(1)                 # the word the kernels read; the backward pass reads it too
+            # the word the kernels read: this call's own copy, which its backward pass reads too, so
+            # that later forward calls (which advance seed_state) do not change it
+            seed = self.seed_state.add_(1).clone()
         else:
-            seed = ((self.seed & 0xFFFFFFFF) << 32) + (self.calls & 0xFFFFFFFF)
+            seed = (self.key_high << 32) + (self.calls & 0xFFFFFFFF)
         self.calls += 1
         y = _MxLinearFn.apply(x2d, self.weight, self.bias, self, seed)
         return y.reshape(*lead, self.out_features)

@@ -29,13 +29,13 @@ def test_module_forward_backward_matches_oracle(mx, orc, flow):
     import mx_workloads as wl
     N, D, C, Np = 200, 96, 160, 224
     X, W, dY = wl.linear_layer(N, D, C, seed=2, outliers=2)
-    lin = mx.MxLinear(D, C, bias=True, flow=flow, seed=3)
+    lin = mx.MxLinear(D, C, bias=True, flow=flow, seed=3, layer_id=5)
     with torch.no_grad():
         lin.weight.copy_(dev(W))
         lin.bias.copy_(dev(np.linspace(-1, 1, C, dtype=np.float32)))
     y, dx, dw = _run_module(lin, X.reshape(2, 100, D), dY.reshape(2, 100, C))
     assert y.shape == (2, 100, C) and dx.shape == (2, 100, D) and dw.shape == (C, D)
-    seed = 3 << 32                                      # first call of a module with seed 3
+    seed = ((3 << 16) | 5) << 32                        # first call of the module with seed 3 and layer id 5
     Xp, dYp = _padded(X, Np), _padded(dY, Np)
     if flow == "tetrajet":
         xt, wt, dy = oracle_layer(orc, Xp, W, dYp, seed=seed)
@@ -125,7 +125,7 @@ def test_module_device_seed_equals_host_seed_and_replays_in_a_graph(mx):
     import mx_workloads as wl
     N, D, C = 96, 64, 128
     X, W, dY = wl.linear_layer(N, D, C, seed=8)
-    lins = [mx.MxLinear(D, C, bias=True, seed=0x9ABCDEF0, device_seed=ds) for ds in (False, True)]
+    lins = [mx.MxLinear(D, C, bias=True, seed=0x9ABC, layer_id=0xDEF0, device_seed=ds) for ds in (False, True)]
     for lin in lins:
         with torch.no_grad():
             lin.weight.copy_(dev(W))
@@ -162,3 +162,41 @@ def test_module_device_seed_equals_host_seed_and_replays_in_a_graph(mx):
             assert torch.equal(u, v), (call, nm)
         seen.append(xs.grad.clone())
     assert not torch.equal(seen[0], seen[1]) and not torch.equal(seen[1], seen[2])
+
+
+def test_layers_of_a_model_round_with_independent_streams(mx):
+    """Two layers of the same shape built with default arguments, given the same weight, input and output
+    gradient: the deterministic forward agrees bit for bit, the stochastically rounded backward does not
+    (each layer's Philox key carries its own layer id, Sec. 3.4's independence)."""
+    import mx_workloads as wl
+    N, D, C = 96, 64, 128
+    X, W, dY = wl.linear_layer(N, D, C, seed=12)
+    a, b = mx.MxLinear(D, C, bias=False), mx.MxLinear(D, C, bias=False)
+    assert a.layer_id != b.layer_id and a.key_high != b.key_high
+    outs = []
+    for lin in (a, b):
+        with torch.no_grad():
+            lin.weight.copy_(dev(W))
+        outs.append(_run_module(lin, X, dY))
+    assert torch.equal(outs[0][0], outs[1][0])
+    assert not torch.equal(outs[0][1], outs[1][1]) and not torch.equal(outs[0][2], outs[1][2])
+
+
+def test_device_seed_backward_uses_the_key_of_its_own_forward(mx):
+    """Two forward calls before the first backward (micro-batches): with the key in device memory each
+    backward still rounds with the key of its own forward, as the host-side key does."""
+    import mx_workloads as wl
+    N, D, C = 64, 64, 96
+    X, W, dY = wl.linear_layer(N, D, C, seed=13)
+    grads = []
+    for ds in (False, True):
+        lin = mx.MxLinear(D, C, bias=False, seed=4, layer_id=9, device_seed=ds)
+        with torch.no_grad():
+            lin.weight.copy_(dev(W))
+        x1, x2 = dev(X).requires_grad_(True), dev(X).requires_grad_(True)
+        y1, y2 = lin(x1), lin(x2)
+        (y1 * dev(dY)).sum().backward()
+        (y2 * dev(dY)).sum().backward()
+        grads.append((x1.grad.clone(), x2.grad.clone()))
+    assert torch.equal(grads[0][0], grads[1][0]) and torch.equal(grads[0][1], grads[1][1])
+    assert not torch.equal(grads[0][0], grads[0][1])

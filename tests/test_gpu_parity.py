@@ -469,30 +469,41 @@ def test_config_vit_tiny_all_layers(mx, orc, dtype):
         _check_layer(mx, orc, step, xt, wt, dy, y, dx, dw, N, D, C, False, False, "vit_tiny %s %s" % (name, dtype))
 
 
-def test_config_vit_small_fc_layers(mx, orc):
-    """ViT-Small batch 128 (N = 25216 = 98.5 x 256): fc1 and fc2, bf16 sources and outputs."""
+def _config_layer(name, layer):
     import mx_workloads as wl
-    for li, (name, N, D, C) in enumerate(wl.config_layers("vit_small_b128")):
-        if name not in ("fc1", "fc2"):
-            continue
-        X, W, dY = wl.linear_layer(N, D, C, seed=10 + li, dtype="bf16")
-        step = mx.MxLinearStep(N, D, C, out_dtype=torch.bfloat16, dw_dtype=torch.float32)
-        y = step.forward(dev(X, "bf16"), dev(W, "bf16"), seed=li)
-        dx, dw = step.backward(dev(dY, "bf16"), seed=li)
-        xt, wt, dy = oracle_layer(orc, X, W, dY, seed=li)
-        _check_layer(mx, orc, step, xt, wt, dy, y, dx, dw, N, D, C, True, True, "vit_small " + name)
+    for li, (ln, N, D, C) in enumerate(wl.config_layers(name)):
+        if ln == layer:
+            return li, N, D, C
+    raise KeyError(layer)
 
 
-def test_config_vit_large_qema_layer(mx, orc):
-    """ViT-Large batch 256, proj layer (1024 -> 1024) with the weight through Q-EMA: 20 steps of the
-    master-weight walk, each followed by the EMA update and quantization; the last step's codes feed
-    the forward product and (re-quantized by Q4) the dX product."""
+@pytest.mark.parametrize("layer", ["qkv", "proj", "fc1", "fc2"])
+def test_config_vit_small_layer(mx, orc, layer):
+    """ViT-Small batch 128 (N = 25216 = 98.5 x 256), every layer of the block at full size, bf16 sources
+    and outputs, stochastic rounding on all backward quantizers: all packed bytes, 4096 sampled entries
+    of each product."""
     import mx_workloads as wl
-    N, D, C = 50432, 1024, 1024
-    X, _, dY = wl.linear_layer(N, D, C, seed=5, dtype="bf16")
+    li, N, D, C = _config_layer("vit_small_b128", layer)
+    X, W, dY = wl.linear_layer(N, D, C, seed=10 + li, dtype="bf16")
+    step = mx.MxLinearStep(N, D, C, out_dtype=torch.bfloat16, dw_dtype=torch.float32)
+    y = step.forward(dev(X, "bf16"), dev(W, "bf16"), seed=li)
+    dx, dw = step.backward(dev(dY, "bf16"), seed=li)
+    xt, wt, dy = oracle_layer(orc, X, W, dY, seed=li)
+    _check_layer(mx, orc, step, xt, wt, dy, y, dx, dw, N, D, C, True, True, "vit_small " + layer)
+
+
+@pytest.mark.parametrize("layer", ["qkv", "proj", "fc1", "fc2"])
+def test_config_vit_large_qema_layer(mx, orc, layer):
+    """ViT-Large batch 256, every layer of the block at full size with the weight through Q-EMA: 20 steps
+    of the master-weight walk, each followed by the EMA update and quantization (codes and EMA state
+    checked at every step); the last step's codes feed the forward product and, re-quantized by Q4, the
+    dX product.  All packed bytes, 4096 sampled entries of each product."""
+    import mx_workloads as wl
+    li, N, D, C = _config_layer("vit_large_b256", layer)
+    X, _, dY = wl.linear_layer(N, D, C, seed=5 + li, dtype="bf16")
     step = mx.MxLinearStep(N, D, C, out_dtype=torch.bfloat16, dw_dtype=torch.float32, qema=True, beta=0.998)
     ema = None
-    for t, W in enumerate(wl.weight_walk(C, D, seed=5, steps=20)):
+    for t, W in enumerate(wl.weight_walk(C, D, seed=5 + li, steps=20)):
         if ema is None:
             ema = np.zeros_like(W)
         wc, wsc = orc.ema_weight_quant(W, ema, beta=0.998, update_ema=2 if t == 0 else 1)
@@ -506,8 +517,9 @@ def test_config_vit_large_qema_layer(mx, orc):
     wt4 = orc.quantize_transposed(W, round_t=1, tensor_id_t=4, pre_quant=1, want_row=False, row_in=(wc, wsc), seed=20)
     xt = orc.quantize_transposed(X, round_t=1, tensor_id_t=6, pre_quant=1, round_row=0, tensor_id_row=1, seed=20)
     dy = orc.quantize_transposed(dY, round_t=1, tensor_id_t=5, pre_quant=0, round_row=1, tensor_id_row=3, seed=20)
+    del X, dY
     wt = (wt4[0], wt4[1], wc, wsc)
-    _check_layer(mx, orc, step, xt, wt, dy, y, dx, dw, N, D, C, True, True, "vit_large proj q-ema")
+    _check_layer(mx, orc, step, xt, wt, dy, y, dx, dw, N, D, C, True, True, "vit_large %s q-ema" % layer)
 
 
 # ------------------------------------------------- column sums with the fused quantizer ----
@@ -537,6 +549,9 @@ def test_column_sums_with_the_fused_quantizer(mx, orc, dtype, rows, cols):
     # every value passes at most 4 + 3 + 8 additions inside a 256-row block, then fewer than one per block plus 8
     tol = (32 + (rows + 255) // 256) * 2.0 ** -24 * absref
     assert np.all(np.abs(sums[0].astype(np.float64) - ref) <= tol + 1e-30), np.max(np.abs(sums[0] - ref) / (absref + 1e-300))
+    # and bit for bit the FP32 sums in the order the interface documents (round to nearest in every
+    # addition, although the stochastic quantizer around them runs under a directed rounding mode)
+    assert np.array_equal(sums[0], orc.column_sums_f32_ordered(np.ascontiguousarray(x[:, :cols])))
 
 
 def test_column_sums_in_a_batch_of_two(mx, orc):
@@ -557,6 +572,7 @@ def test_column_sums_in_a_batch_of_two(mx, orc):
             assert_same_bytes(g, w, nm)
     ref = orc.column_sums(xb)
     assert np.all(np.abs(host(cs).astype(np.float64) - ref) <= 35 * 2.0 ** -24 * np.abs(xb).astype(np.float64).sum(0) + 1e-30)
+    assert np.array_equal(host(cs), orc.column_sums_f32_ordered(xb))
 
 
 # ------------------------------------------------- seed in device memory, graph replay ----
@@ -636,35 +652,20 @@ def test_two_streams_give_the_single_stream_results(mx, orc):
 
 # ------------------------------------------------- full size, bench launch configuration ----
 
-def test_full_size_vit_base_qkv_layer(mx, orc):
-    """ViT-B/16 batch 256 qkv layer (N = 50432, 768 -> 2304), bf16 sources, the exact calls and
-    buffers bench.py times: all packed bytes compared in full, products on 4096 sampled entries each."""
+@pytest.mark.parametrize("layer", ["qkv", "proj", "fc1", "fc2"])
+def test_full_size_vit_base_layer(mx, orc, layer):
+    """ViT-B/16 batch 256 (N = 50432), every layer of the block, bf16 sources, the exact calls, buffers
+    and launch configuration bench.py times (one launch for X and W, bf16 Y and dX, FP32 dW through the
+    K-split path): all packed bytes compared in full, products on 4096 sampled entries each."""
     import mx_workloads as wl
-    N, D, C = 50432, 768, 2304
-    X, W, dY = wl.linear_layer(N, D, C, seed=0, dtype="bf16")
+    li, N, D, C = _config_layer("vit_base_b256", layer)
+    X, W, dY = wl.linear_layer(N, D, C, seed=li, dtype="bf16")
     step = mx.MxLinearStep(N, D, C, out_dtype=torch.bfloat16, dw_dtype=torch.float32)
-    y = step.forward(dev(X, "bf16"), dev(W, "bf16"), seed=7)
-    dx, dw = step.backward(dev(dY, "bf16"), seed=7)
-    xt, wt, dy = oracle_layer(orc, X, W, dY, seed=7)
+    y = step.forward(dev(X, "bf16"), dev(W, "bf16"), seed=7 + li)
+    dx, dw = step.backward(dev(dY, "bf16"), seed=7 + li)
+    xt, wt, dy = oracle_layer(orc, X, W, dY, seed=7 + li)
     del X, W, dY
-    for got, want, nm in ((step.xq, xt[2], "Q1"), (step.xs, xt[3], "S1"), (step.xtq, xt[0], "Q6"), (step.xts, xt[1], "S6"),
-                          (step.wq, wt[2], "Q2"), (step.ws, wt[3], "S2"), (step.wtq, wt[0], "Q4"), (step.wts, wt[1], "S4"),
-                          (step.dyq, dy[2], "Q3"), (step.dys, dy[3], "S3"), (step.dytq, dy[0], "Q5"), (step.dyts, dy[1], "S5")):
-        assert_same_bytes(got, want, nm)
-    rng = np.random.default_rng(0)
-
-    def sampled(out, ops, m, n, nm, bf16):
-        ii = rng.integers(0, m, 4096)
-        jj = rng.integers(0, n, 4096)
-        ii[:4], jj[:4] = [0, m - 1, 0, m - 1], [0, 0, n - 1, n - 1]         # corners of the edge tiles
-        ref, absref = orc.gemm_f64_sampled(*ops, ii, jj)
-        got = host(out.float())[ii, jj].astype(np.float64)
-        tol = 1e-5 * absref + (np.abs(ref) * 2.0 ** -8 if bf16 else 0.0)
-        assert np.all(np.abs(got - ref) <= tol), (nm, np.max(np.abs(got - ref) / (absref + 1e-300)))
-
-    sampled(y, (xt[2], xt[3], wt[2], wt[3]), N, C, "Y", True)
-    sampled(dx, (dy[2], dy[3], wt[0], wt[1]), N, D, "dX", True)
-    sampled(dw, (dy[0], dy[1], xt[0], xt[1]), C, D, "dW", False)
+    _check_layer(mx, orc, step, xt, wt, dy, y, dx, dw, N, D, C, True, True, "vit_base " + layer)
 
 
 # ------------------------------------------------- Q-Ramping: oscillation detection ----

@@ -47,3 +47,15 @@ def test_state_dict_round_trip_keeps_integer_state():
             got = new.state[p_new][name]
             assert got.dtype == t.dtype and torch.equal(got, t), name
             assert got.data_ptr() != t.data_ptr()
+
+
+def test_layers_get_distinct_philox_keys_by_default():
+    """Two layers built with default arguments draw from different Philox keys (the upper key word
+    carries the layer's construction number), and an explicit layer_id fixes the key."""
+    from paper_2502_20853_amd.module import MxLinear
+    a, b = MxLinear(64, 96, device="cpu"), MxLinear(64, 96, device="cpu")
+    assert a.layer_id != b.layer_id and a.key_high != b.key_high
+    c, d = MxLinear(64, 96, device="cpu", seed=3, layer_id=7), MxLinear(64, 96, device="cpu", seed=3, layer_id=7)
+    assert c.key_high == d.key_high == ((3 << 16) | 7)
+    e = MxLinear(64, 96, device="cpu", seed=3, layer_id=7, device_seed=True)
+    assert int(e.seed_state.item()) & 0xFFFFFFFFFFFFFFFF == ((c.key_high << 32) - 1) & 0xFFFFFFFFFFFFFFFF

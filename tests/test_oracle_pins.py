@@ -851,3 +851,37 @@ def test_column_sums_closed_forms(orc):
     big = np.full((4097, 32), 1.0, np.float32)
     big[0] = 2.0 ** 25                                   # in FP32, 2^25 + 1 = 2^25: 4096 ones would vanish
     assert np.array_equal(orc.column_sums(big), np.full(32, 2.0 ** 25 + 4096))
+
+
+def test_column_sums_f32_ordered_pins(orc):
+    """The FP32 fixed-order sums: exact (equal to the FP64 sums) whenever every partial sum is an integer
+    below 2^24; on values built so that the order of the additions decides the result they give what the
+    documented order gives, worked out by hand, and not what index order would give."""
+    rng = np.random.default_rng(3)
+    for rows in (32, 288, 2080):
+        x = rng.integers(-64, 64, (rows, 40)).astype(np.float32)
+        assert np.array_equal(orc.column_sums_f32_ordered(x).astype(np.float64), orc.column_sums(x))
+    # one tile: rows 0..3 hold 2^24, 1, 1, 1 -> ((2^24 + 1) + 1) + 1 = 2^24 in FP32 (each +1 is a tie to even);
+    # rows 4..7 hold 1, 1, 1, 1 -> 4; the tree then adds 2^24 + 4 exactly.  Index order from row 4 on would
+    # give the same, but starting the rows 4..7 before the rows 0..3 would not: the value pins the grouping.
+    x = np.zeros((32, 1), np.float32)
+    x[0, 0] = 2.0 ** 24
+    x[1:8, 0] = 1.0
+    assert orc.column_sums_f32_ordered(x)[0] == np.float32(2.0 ** 24 + 4)
+    assert orc.column_sums(x)[0] == 2.0 ** 24 + 7
+    # balanced tree over the eight row groups: g0 = 2^24, g1 = g2 = g3 = 1 (one row each)
+    # -> (2^24 + 1) + (1 + 1) = 2^24 + 2, where a left-to-right chain would lose all three ones
+    x = np.zeros((32, 1), np.float32)
+    x[0, 0], x[4, 0], x[8, 0], x[12, 0] = 2.0 ** 24, 1.0, 1.0, 1.0
+    assert orc.column_sums_f32_ordered(x)[0] == np.float32(2.0 ** 24 + 2)
+    # blocks: 9 blocks make runs of 2.  Block 0 = 2^24 and blocks 2, 3 = 1: run 1 = 1 + 1 = 2 survives,
+    # 2^24 + 2 (one chain over the blocks in index order would lose both ones).  Block 0 = 2^24 and
+    # blocks 1, 2 = 1: block 1 is lost inside run 0 and run 1 = 1 is lost in the last chain: 2^24, where
+    # the exact sum 2^24 + 2 is representable.
+    x = np.zeros((9 * 256, 1), np.float32)
+    x[0, 0], x[2 * 256, 0], x[3 * 256, 0] = 2.0 ** 24, 1.0, 1.0
+    assert orc.column_sums_f32_ordered(x)[0] == np.float32(2.0 ** 24 + 2)
+    x = np.zeros((9 * 256, 1), np.float32)
+    x[0, 0], x[1 * 256, 0], x[2 * 256, 0] = 2.0 ** 24, 1.0, 1.0
+    assert orc.column_sums_f32_ordered(x)[0] == np.float32(2.0 ** 24)
+    assert orc.column_sums(x)[0] == 2.0 ** 24 + 2
