@@ -195,6 +195,27 @@ int mx_linear_bwd_dw(const uint8_t* dytq, const uint8_t* dyts, const uint8_t* xt
                   void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * mx_linear_bwd_dw for callers that cannot allocate device memory and have no workspace to pass:
+ * code under HIP graph capture, tight serving or training loops that own no allocator, harnesses
+ * that forbid hipMalloc.  Same product, same kernels and the same result bit for bit as
+ * mx_linear_bwd_dw with a workspace; the FP32 partial sums of the K split go to a device array of
+ * MX_NOALLOC_MAX_WORKSPACE_BYTES that is part of the library's code object (each GPU the library
+ * runs on holds its own copy until the process ends).  The call allocates and frees nothing and
+ * calls no allocating routine; its first call on a device looks the array's address up once.
+ *   Arguments, layouts, alignment and errors as mx_linear_bwd_dw.  Sizes whose K split needs more
+ *   than MX_NOALLOC_MAX_WORKSPACE_BYTES (mx_linear_workspace_bytes(MX_GEMM_BWD_DW, N, C, D)) are
+ *   rejected with MX_ERR_WORKSPACE and nothing is launched; every layer of the ViT-T/S/B/L
+ *   configurations fits.
+ *   All calls on one GPU share that GPU's array: calls that may overlap in time (different streams,
+ *   different host threads) race on it and must be serialised by the caller.  The array keeps the
+ *   previous call's partial sums; the kernels overwrite what they read, so nothing is cleared.
+ */
+#define MX_NOALLOC_MAX_WORKSPACE_BYTES (64u << 20)
+int mx_linear_bwd_dw_noalloc(const uint8_t* dytq, const uint8_t* dyts, const uint8_t* xtq, const uint8_t* xts,
+                  int64_t N, int64_t C, int64_t D,
+                  void* dw, int dw_dtype, int64_t lddw, void* stream);
+
+/*
  * Q-EMA (Sec. 5 Eq. 8, Algorithm 1): 1x32 quantizer of the weight w[rows x cols]
  * whose scale comes from w and whose choice between the two E2M1 neighbours of
  * w/S is the one nearer to w_ema/S (q1 iff strictly nearer).  A w/S that is

@@ -25,7 +25,7 @@ SCALE_TRUNCFREE, SCALE_FLOOR = 0, 1
 GEMM_FWD, GEMM_BWD_DX, GEMM_BWD_DW = 0, 1, 2
 
 EXPORTS = ["mx_quantize", "mx_quantize_transposed", "mx_quantize_transposed_batch", "mx_column_sum_workspace_bytes", "mx_linear_fwd", "mx_linear_fwd_bias", "mx_linear_bwd_dx",
-           "mx_linear_bwd_dw", "mx_ema_weight_quant", "mx_linear_workspace_bytes",
+           "mx_linear_bwd_dw", "mx_linear_bwd_dw_noalloc", "mx_ema_weight_quant", "mx_linear_workspace_bytes",
            "mx_oscillation_accumulate", "mx_ramping_factor",
            "mx_ramping_adamw_step", "mx_quant_confidence", "mx_rate_of_change_workspace_bytes", "mx_rate_of_change_step",
            "mx_dequantize", "mx_calibration_copy", "mx_last_hip_error", "mx_version"]
@@ -74,6 +74,8 @@ def lib():
         fn = getattr(L, name)
         fn.restype = ci
         fn.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, ci, i64, vp, sz, vp]
+    L.mx_linear_bwd_dw_noalloc.restype = ci
+    L.mx_linear_bwd_dw_noalloc.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, ci, i64, vp]
     L.mx_column_sum_workspace_bytes.restype = sz
     L.mx_column_sum_workspace_bytes.argtypes = [i64, i64]
     L.mx_linear_fwd_bias.restype = ci
@@ -294,6 +296,21 @@ def mx_linear_bwd_dw(dytq, dyts, xtq, xts, out=None, out_dtype=torch.float32, wo
     """dW[C, D] from dytq[C, N/2] and xtq[D, N/2]."""
     C, N, D = dytq.shape[0], dytq.shape[1] * 2, xtq.shape[0]
     return _linear("mx_linear_bwd_dw", GEMM_BWD_DW, dytq, dyts, xtq, xts, N, C, D, (C, D), out, out_dtype, workspace, stream)
+
+
+NOALLOC_MAX_WORKSPACE_BYTES = 64 << 20
+
+
+def mx_linear_bwd_dw_noalloc(dytq, dyts, xtq, xts, out, stream=None):
+    """dW[C, D] into the caller's `out`, the K-split partials in the library's own device array: the
+    call allocates nothing (so `out` is required)."""
+    C, N, D = dytq.shape[0], dytq.shape[1] * 2, xtq.shape[0]
+    if tuple(out.shape) != (C, D) or out.stride(1) != 1:
+        raise ValueError("out must be [C, D] with unit column stride")
+    rc = lib().mx_linear_bwd_dw_noalloc(_ptr(dytq), _ptr(dyts), _ptr(xtq), _ptr(xts), N, C, D,
+                                        _ptr(out), _src_dtype(out), out.stride(0), _stream(stream))
+    _check("mx_linear_bwd_dw_noalloc", rc)
+    return out
 
 
 def mx_ema_weight_quant(w, w_ema, beta=0.998, update_ema=1, scale_mode=SCALE_TRUNCFREE, out=None, stream=None):

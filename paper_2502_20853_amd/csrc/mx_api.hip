@@ -72,6 +72,33 @@ int run_gemm(const uint8_t* aq, const uint8_t* as, const uint8_t* bq, const uint
     return hip_status(mxl::launch_gemm(p, static_cast<hipStream_t>(stream)));
 }
 
+// ---- scratch memory of mx_linear_bwd_dw_noalloc: a device array that is part of the code object,
+//      so it exists on every GPU the library is loaded on, from load to process end ----
+static __device__ __align__(256) unsigned char scratch[MX_NOALLOC_MAX_WORKSPACE_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+std::atomic<void*> g_scratch_ptr[MAX_DEVICES];
+
+// Device address of `scratch` on the current device.  In host code the array's name is only a handle
+// for the runtime: the address a kernel may use comes from hipGetSymbolAddress, once per device (each
+// GPU holds its own copy at its own address).  Two threads racing here store the same value.
+int scratch_of_current_device(void** out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_status(e);
+    if (dev < 0 || dev >= MAX_DEVICES) return hip_status(hipErrorInvalidDevice);
+    void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (p == nullptr) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_status(e);
+        if (p == nullptr) return hip_status(hipErrorInvalidSymbol);
+        g_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return MX_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -212,6 +239,25 @@ int mx_linear_bwd_dw(const uint8_t* dytq, const uint8_t* dyts, const uint8_t* xt
 {
     if (N <= 0 || C <= 0 || D <= 0) return (!dytq || !dyts || !xtq || !xts || !dw) ? MX_ERR_NULL : MX_ERR_SHAPE;
     return run_gemm(dytq, dyts, xtq, xts, C, D, N, dw, dw_dtype, lddw, workspace, workspace_bytes, stream);
+}
+
+int mx_linear_bwd_dw_noalloc(const uint8_t* dytq, const uint8_t* dyts, const uint8_t* xtq, const uint8_t* xts,
+                  int64_t N, int64_t C, int64_t D, void* dw, int dw_dtype, int64_t lddw, void* stream)
+{
+    if (N <= 0 || C <= 0 || D <= 0) return (!dytq || !dyts || !xtq || !xts || !dw) ? MX_ERR_NULL : MX_ERR_SHAPE;
+    // every argument check of the product first: an invalid call returns before the scratch is looked up
+    int rc = check_gemm_call(dytq, dyts, xtq, xts, C, D, N, dw, dw_dtype, lddw);
+    if (rc != MX_OK) return rc;
+    const int split = mxl::gemm_split_k(C, D, N);
+    const size_t need = split > 1 ? (size_t)split * (size_t)C * (size_t)D * sizeof(float) : 0;
+    if (need > (size_t)MX_NOALLOC_MAX_WORKSPACE_BYTES) return MX_ERR_WORKSPACE;
+    void* ws = nullptr;
+    if (need > 0) {
+        rc = scratch_of_current_device(&ws);
+        if (rc != MX_OK) return rc;
+    }
+    // The K-split partials are written in full before the reduction reads them: nothing has to start at zero.
+    return run_gemm(dytq, dyts, xtq, xts, C, D, N, dw, dw_dtype, lddw, ws, need, stream);
 }
 
 int mx_ema_weight_quant(const void* w, int dtype, float* w_ema, float beta, int update_ema,

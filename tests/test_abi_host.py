@@ -257,3 +257,29 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
     assert r.returncode != 0 and "one GPU" in (r.stdout + r.stderr)
+
+
+def test_no_alloc_dw_validates_like_the_workspace_entry_point(L):
+    """mx_linear_bwd_dw_noalloc returns the argument errors of mx_linear_bwd_dw before it touches the GPU
+    (null pointers, contraction length not a multiple of 32, bad dtype, misaligned operands), and the
+    K-split workspace of any shape the policy can choose fits the library's own array."""
+    from paper_2502_20853_amd import binding
+    f = L.mx_linear_bwd_dw_noalloc
+    ok = dict(a=FAKE, a_s=FAKE, b=FAKE, b_s=FAKE, N=4096, C=256, D=256, out=FAKE, dt=0, ld=256)
+
+    def call(**kw):
+        v = dict(ok, **kw)
+        return f(P(v["a"]), P(v["a_s"]), P(v["b"]), P(v["b_s"]), v["N"], v["C"], v["D"], P(v["out"]), v["dt"], v["ld"], P(0))
+
+    assert call(a=0) == binding.MX_ERR_NULL and call(out=0) == binding.MX_ERR_NULL
+    assert call(N=4100) == binding.MX_ERR_SHAPE and call(N=0) == binding.MX_ERR_SHAPE and call(ld=128) == binding.MX_ERR_SHAPE
+    assert call(dt=7) == binding.MX_ERR_DTYPE
+    assert call(a=FAKE + 4) == binding.MX_ERR_ALIGN and call(out=FAKE + 4) == binding.MX_ERR_ALIGN
+    import random
+    rng = random.Random(0)
+    worst = 0
+    for _ in range(20000):
+        C, D = rng.randint(1, 6000), rng.randint(1, 6000)
+        N = 32 * rng.randint(1, 1 << 14)
+        worst = max(worst, L.mx_linear_workspace_bytes(binding.GEMM_BWD_DW, N, C, D))
+    assert 0 < worst <= binding.NOALLOC_MAX_WORKSPACE_BYTES
