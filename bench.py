@@ -259,6 +259,32 @@ def main():
                 row[key] = round(e0.elapsed_time(e1) / 10 * 1e3, 1)
             fwd_bias.append(row)
 
+    # What the matrix cores sustain on given operand bytes, outside the timed region: the products' MFMA in
+    # a register-resident loop (no LDS, no memory), one workgroup of 8 waves per compute unit, about a
+    # millisecond per launch, on constant bytes, on uniformly random bytes and on the packed codes of this
+    # workload's activations.  A calibration figure next to the roofline, never its peak.
+    mfma_cal = {}
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    gen_cal = torch.Generator(device="cuda").manual_seed(11)
+    need = mx.binding.CALIBRATION_MFMA_OPERAND_BYTES
+    cal_inputs = {"constant_bytes_0x22": torch.full((need,), 0x22, dtype=torch.uint8, device="cuda"),
+                  "random_bytes": torch.randint(0, 256, (need,), dtype=torch.uint8, device="cuda", generator=gen_cal),
+                  "quantized_activation_codes": steps_obj[0].xq.reshape(-1)[:need].contiguous()}
+    cal_sink = torch.empty(n_cu * 512, dtype=torch.float32, device="cuda")
+    for key, ops in cal_inputs.items():
+        for _ in range(2):
+            mx.binding.mx_calibration_mfma(ops, n_cu, 2000, cal_sink)
+        e0, e1 = ev(), ev()
+        e0.record()
+        fl = 0.0
+        for _ in range(3):
+            fl += mx.binding.mx_calibration_mfma(ops, n_cu, 2000, cal_sink)
+        e1.record()
+        torch.cuda.synchronize()
+        mfma_cal[key] = round(fl / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
+    mfma_cal.update({"unit": "TFLOP/s", "kernel": "calibration_mfma_kernel", "workgroups": n_cu, "waves_per_simd": 2,
+                     "note": "register-resident V_MFMA_SCALE_F32_32X32X64_F8F6F4 loop; calibration only, not the roofline peak"})
+
     # Q-EMA weight quantizer (Sec. 5), outside the timed region: the four weights of the block, one
     # update + quantization each, as a training step with Q-EMA would issue them
     qema = []
@@ -426,6 +452,7 @@ def main():
                        "unit": "GB/s", "frac": q_bytes / (quant_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
                        "ms_per_step": quant_ms, "bytes_per_step": q_bytes, "alu": quant_alu},
         "gemm_ms_per_step": gemm_ms,
+        "mfma_sustained": mfma_cal,
         "launches": launches,
         "forward_with_bias": fwd_bias,
         "qema_weight_quant": qema,

@@ -346,6 +346,21 @@ int mx_dequantize(const uint8_t* codes, const uint8_t* scales, int64_t rows, int
  * pointers): a dispatch with known HBM traffic, used to scale profiler byte counters. */
 int mx_calibration_copy(void* dst, const void* src, size_t bytes, void* stream);
 
+/* Register-resident loop of the products' matrix instruction (V_MFMA_SCALE_F32_32X32X64_F8F6F4, FP4 x
+ * FP4, group scales 2^0): a dispatch with a known number of flops and no memory traffic inside its
+ * loop, used to measure the rate the matrix cores sustain on GIVEN operand bytes (the rate depends on
+ * the bytes: constant bytes run faster than random or real quantized ones, at the same instruction
+ * stream).  A reported calibration figure, never a roofline peak.
+ *   operands    device, MX_CALIBRATION_MFMA_OPERAND_BYTES bytes, 16-byte aligned: packed FP4 codes, every
+ *               lane of the 8 waves of a workgroup reads 12 x 16 bytes of it once (all workgroups the same)
+ *   workgroups  workgroups of 8 waves to launch (one per compute unit fills the chip: two waves per SIMD)
+ *   iterations  loop count; each wave issues 16 MFMAs (8 independent accumulator tiles x two 64-K slices) per
+ *               iteration: flops = workgroups * 8 * iterations * 16 * 2 * 32 * 32 * 64
+ *   sink        device out, FP32, workgroups * 512 values (keeps the accumulators alive; contents unspecified)
+ */
+#define MX_CALIBRATION_MFMA_OPERAND_BYTES 98304
+int mx_calibration_mfma(const uint8_t* operands, int workgroups, int iterations, float* sink, void* stream);
+
 /* Raw hipError_t of the last launch that made a call return MX_ERR_HIP (0 if none). */
 int mx_last_hip_error(void);
 

@@ -28,7 +28,7 @@ EXPORTS = ["mx_quantize", "mx_quantize_transposed", "mx_quantize_transposed_batc
            "mx_linear_bwd_dw", "mx_linear_bwd_dw_noalloc", "mx_ema_weight_quant", "mx_linear_workspace_bytes",
            "mx_oscillation_accumulate", "mx_ramping_factor",
            "mx_ramping_adamw_step", "mx_quant_confidence", "mx_rate_of_change_workspace_bytes", "mx_rate_of_change_step",
-           "mx_dequantize", "mx_calibration_copy", "mx_last_hip_error", "mx_version"]
+           "mx_dequantize", "mx_calibration_copy", "mx_calibration_mfma", "mx_last_hip_error", "mx_version"]
 
 
 class _TransposedJob(ctypes.Structure):
@@ -100,6 +100,8 @@ def lib():
     L.mx_dequantize.argtypes = [vp, vp, i64, i64, vp, vp]
     L.mx_calibration_copy.restype = ci
     L.mx_calibration_copy.argtypes = [vp, vp, sz, vp]
+    L.mx_calibration_mfma.restype = ci
+    L.mx_calibration_mfma.argtypes = [vp, ci, ci, vp, vp]
     L.mx_last_hip_error.restype = ci
     L.mx_last_hip_error.argtypes = []
     L.mx_version.restype = ctypes.c_char_p
@@ -460,3 +462,18 @@ def mx_calibration_copy(dst, src, stream=None):
     rc = lib().mx_calibration_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream))
     _check("mx_calibration_copy", rc)
     return dst
+
+
+CALIBRATION_MFMA_OPERAND_BYTES = 98304
+
+
+def mx_calibration_mfma(operands, workgroups, iterations, sink=None, stream=None):
+    """Register-resident loop of the products' MFMA on the given operand bytes (uint8, at least
+    CALIBRATION_MFMA_OPERAND_BYTES); returns the number of flops the launch performs."""
+    if operands.dtype != torch.uint8 or operands.numel() < CALIBRATION_MFMA_OPERAND_BYTES or not operands.is_contiguous():
+        raise ValueError("operands must be a contiguous uint8 tensor of at least %d bytes" % CALIBRATION_MFMA_OPERAND_BYTES)
+    if sink is None:
+        sink = torch.empty(workgroups * 512, dtype=torch.float32, device=operands.device)
+    rc = lib().mx_calibration_mfma(_ptr(operands), workgroups, iterations, _ptr(sink), _stream(stream))
+    _check("mx_calibration_mfma", rc)
+    return workgroups * 8 * iterations * 16 * 2.0 * 32 * 32 * 64

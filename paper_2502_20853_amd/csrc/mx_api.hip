@@ -392,6 +392,14 @@ int mx_calibration_copy(void* dst, const void* src, size_t bytes, void* stream)
     return hip_status(mxl::launch_calibration_copy(dst, src, bytes, static_cast<hipStream_t>(stream)));
 }
 
+int mx_calibration_mfma(const uint8_t* operands, int workgroups, int iterations, float* sink, void* stream)
+{
+    if (!operands || !sink) return MX_ERR_NULL;
+    if (workgroups < 1 || workgroups > 65536 || iterations < 1 || iterations > (1 << 24)) return MX_ERR_SHAPE;
+    if (!aligned(operands, 16) || !aligned(sink, 4)) return MX_ERR_ALIGN;
+    return hip_status(mxl::launch_calibration_mfma(operands, workgroups, iterations, sink, static_cast<hipStream_t>(stream)));
+}
+
 int mx_last_hip_error(void) { return g_last_hip_error.load(); }
 
 const char* mx_version(void) { return "mxfp4-gfx950 0.1"; }

@@ -29,6 +29,13 @@
 
 #include <type_traits>
 
+// Timing hooks for instrumented builds of this file (a build that defines them before including it);
+// they expand to nothing in the library.
+#ifndef MX_PROBE
+#define MX_PROBE_INIT
+#define MX_PROBE(id)
+#endif
+
 namespace {
 
 // compile-time loop: the MFMA's op_sel (which scale byte) must be an immediate
@@ -676,6 +683,101 @@ __device__ __forceinline__ void store16(void* dst, v4i v)
     else        *reinterpret_cast<v4i*>(dst) = v;
 }
 
+typedef __attribute__((address_space(3))) uint8_t lds_u8;
+typedef int v2i __attribute__((ext_vector_type(2)));
+
+// The same output stage for a wave tile that lies wholly inside the matrix and whose rows can be
+// stored 16 bytes at a time (the common case; every tile of a ViT-B product): no bounds tests, no
+// per-store address arithmetic (a store's address is a uniform tile pointer plus one per-lane
+// offset that is computed once), and no waits between the LDS writes and reads of a chunk (the LDS
+// executes a wave's instructions in order; the compiler waits where a register needs its data).
+// BIAS: add the 128 FP32 bias values at LDS address `bias` (column nbase first).
+template <bool STREAM, bool BIAS>
+__device__ __forceinline__ void gemm_epilogue_interior(const GemmArgs& g, lds_u8* ep, v16f (&acc)[2][4],
+                                                       uint32_t mrow0, uint32_t nbase, uint32_t zsplit, int64_t ldc,
+                                                       const lds_u8* bias)
+{
+    typedef __attribute__((address_space(3))) v4i lds_v4i;
+    typedef __attribute__((address_space(3))) v2i lds_v2i;
+    typedef __attribute__((address_space(3))) v4f lds_v4f;
+    const uint32_t lane = fresh_lane_id();
+    const uint32_t lrow = lane & 31, lhalf = lane >> 5;
+    const uint32_t rrow = lane >> 3, rchunk = lane & 7;
+    const lds_u8* rd = ep + rrow * P_EP_PITCH + rchunk * 16;
+    auto bias4 = [&](int jb, int q) -> v4f {
+        return *reinterpret_cast<const lds_v4f*>(bias + (32 * jb + 8 * q + 4 * lhalf) * 4);
+    };
+    // Four (bf16) or eight (FP32) chunks of 32 rows x 128 bytes pass through the wave's LDS strip.  The
+    // strip's accesses execute in program order, so the writes of chunk c+1 are issued right after the
+    // reads of chunk c and before the global stores that wait for those reads: the LDS round trip of a
+    // chunk is hidden behind the next chunk's conversion instead of being waited for 16 times.
+    if (g.c_bf16 && g.split_k == 1) {
+        lds_u8* wr = ep + lrow * P_EP_PITCH + lhalf * 8;
+        uint8_t* tile = static_cast<uint8_t*>(g.c) + ((size_t)mrow0 * ldc + nbase) * 2;       // uniform
+        const uint32_t voff = rrow * (uint32_t)ldc * 2u + rchunk * 16u;
+        auto write_chunk = [&](int i, int jp) {
+#pragma unroll
+            for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const v16f& a = acc[i][2 * jp + jj];
+                    v2i pk;
+                    if (BIAS) {
+                        const v4f bv = bias4(2 * jp + jj, q);
+                        pk.x = (int)f32x2_to_bf16x2(a[4 * q] + bv.x, a[4 * q + 1] + bv.y);
+                        pk.y = (int)f32x2_to_bf16x2(a[4 * q + 2] + bv.z, a[4 * q + 3] + bv.w);
+                    } else {
+                        pk.x = (int)f32x2_to_bf16x2(a[4 * q], a[4 * q + 1]);
+                        pk.y = (int)f32x2_to_bf16x2(a[4 * q + 2], a[4 * q + 3]);
+                    }
+                    *reinterpret_cast<lds_v2i*>(wr + (32 * jj + 8 * q) * 2) = pk;
+                }
+        };
+        v4i v[4];
+        write_chunk(0, 0);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int i = c >> 1, jp = c & 1;
+#pragma unroll
+            for (int it = 0; it < 4; ++it) v[it] = *reinterpret_cast<const lds_v4i*>(rd + it * 8 * P_EP_PITCH);
+            if (c + 1 < 4) write_chunk((c + 1) >> 1, (c + 1) & 1);
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {
+                uint8_t* dst = tile + ((size_t)(i * 32 + it * 8) * ldc + jp * 64) * 2;            // uniform
+                store16<STREAM>(dst + voff, v[it]);
+            }
+        }
+    } else {
+        lds_u8* wr = ep + lrow * P_EP_PITCH + lhalf * 16;
+        float* base = static_cast<float*>(g.c);
+        if (g.split_k > 1) base += (size_t)zsplit * g.m * g.n;
+        uint8_t* tile = reinterpret_cast<uint8_t*>(base) + ((size_t)mrow0 * ldc + nbase) * 4;
+        const uint32_t voff = rrow * (uint32_t)ldc * 4u + rchunk * 16u;
+        auto write_chunk = [&](int i, int j) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                v4f o = v4f{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+                if (BIAS) o += bias4(j, q);
+                *reinterpret_cast<lds_v4f*>(wr + 8 * q * 4) = o;
+            }
+        };
+        v4i v[4];
+        write_chunk(0, 0);
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            const int i = c >> 2, j = c & 3;
+#pragma unroll
+            for (int it = 0; it < 4; ++it) v[it] = *reinterpret_cast<const lds_v4i*>(rd + it * 8 * P_EP_PITCH);
+            if (c + 1 < 8) write_chunk((c + 1) >> 2, (c + 1) & 3);
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {
+                uint8_t* dst = tile + ((size_t)(i * 32 + it * 8) * ldc + j * 32) * 4;             // uniform
+                store16<STREAM>(dst + voff, v[it]);
+            }
+        }
+    }
+}
+
 // bias: LDS address of the bias value of column nbase (FP32, 128 values), or null.
 template <bool STREAM>
 __device__ __forceinline__ void gemm_epilogue_chunked(const GemmArgs& g, uint8_t* ep, v16f (&acc)[2][4],
@@ -814,8 +916,6 @@ __device__ __forceinline__ void barrier_after_mfma(v16f (&acc)[2][4])
                  : "memory");
 }
 
-typedef __attribute__((address_space(3))) uint8_t lds_u8;
-
 // DMA load, 16 bytes per lane: lane i's bytes [base + voff, +16) land at LDS byte address
 // lds_addr + 16 * i.  Written as an assembly statement for two reasons.  The compiler then keeps no
 // record of outstanding loads into LDS: with the builtin it waits for all of them (vmcnt(0)) before
@@ -844,6 +944,7 @@ __device__ __forceinline__ void pingpong_wave(const GemmArgs& g, lds_u8* lds, co
     const uint32_t first = xcd * per + min(xcd, rem) + blockIdx.x / 8;
     if (first >= range_end) return;
 
+    MX_PROBE_INIT
     const uint32_t kbytes = g.k >> 1, kgroups = g.k >> 5;
     const int lane = threadIdx.x & 63;
     const int wm = wave & 3;
@@ -920,14 +1021,17 @@ __device__ __forceinline__ void pingpong_wave(const GemmArgs& g, lds_u8* lds, co
             dma_load16_at(i_dst + 1024, a_ptr, a_off[1]);
             dma_load16_at(i_dst + Q_BM * 64, b_ptr, b_off[0]);
             dma_load16_at(i_dst + Q_BM * 64 + 1024, b_ptr, b_off[1]);
+            MX_PROBE(1);
             asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
         } else {
             dma_load16_at(i_dst, a_ptr, a_off[0]);
             dma_load16_at(i_dst + 1024, a_ptr, a_off[1]);
             dma_load16_at(i_dst + Q_BM * 64, b_ptr, b_off[0]);
             dma_load16_at(i_dst + Q_BM * 64 + 1024, b_ptr, b_off[1]);
+            MX_PROBE(1);
             asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
         }
+        MX_PROBE(2);
         a_ptr += i_step;
         b_ptr += i_step;
         i_dst = i_buf == 2 ? i_dst - 2 * Q_STAGE_BYTES : i_dst + Q_STAGE_BYTES;
@@ -968,6 +1072,7 @@ __device__ __forceinline__ void pingpong_wave(const GemmArgs& g, lds_u8* lds, co
 
     auto load_phase = [&]() {
         uint32_t va, vb0, vb1;
+        MX_PROBE(0);
         {
             // scale dwords of this K step: one read serves two 32-row blocks (lanes 0-31 the first,
             // lanes 32-63 the second; the 16-byte row pitch makes each read a 4-way bank conflict
@@ -1012,9 +1117,15 @@ __device__ __forceinline__ void pingpong_wave(const GemmArgs& g, lds_u8* lds, co
         sca[0] = pa[0] >> 8 * lhalf; sca[1] = pa[1] >> 8 * lhalf;
         scb[0] = pb0[0] >> 8 * lhalf; scb[1] = pb0[1] >> 8 * lhalf;
         scb[2] = pb1[0] >> 8 * lhalf; scb[3] = pb1[1] >> 8 * lhalf;
+        MX_PROBE(3);
     };
-    auto mma_phase = [&]() {
+    // FIRST: the first K step of a tile; its first 64-K slice starts the accumulators from zero (the
+    // matrix instruction takes a constant 0 as its addend), so they are never cleared by separate moves.
+    auto mma_phase = [&](auto first_c) {
+        constexpr bool FIRST = decltype(first_c)::value;
+        MX_PROBE(4);
         MX_SCHED_FENCE();
+        const v16f zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
@@ -1024,29 +1135,20 @@ __device__ __forceinline__ void pingpong_wave(const GemmArgs& g, lds_u8* lds, co
                 for (int j = 0; j < 4; ++j) {
                     v8i xb = v8i{f[kk].b[j].x, f[kk].b[j].y, f[kk].b[j].z, f[kk].b[j].w, 0, 0, 0, 0};
                     if (kk == 0)
-                        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(xb, xa, acc[i][j], 4, 4, 0, (int)scb[j], 0, (int)sca[i]);
+                        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(xb, xa, FIRST ? zero : acc[i][j], 4, 4, 0, (int)scb[j], 0, (int)sca[i]);
                     else
                         acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(xb, xa, acc[i][j], 4, 4, 2, (int)scb[j], 2, (int)sca[i]);
                 }
             }
         MX_SCHED_FENCE();
+        MX_PROBE(5);
     };
-    auto zero_acc = [&]() {
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-    };
-
     // ---- prologue: stages 0 and 1 (scale block 0 travels with stage 0) ----
     set_issue_tile(first);
     issue_and_wait();
     issue_and_wait();                                                 // (ends with vmcnt(4): all but stage 1)
     asm volatile("s_barrier" ::: "memory");                           // stage 0 and scale block 0 are in
     if (GRP == 0) load_phase();                                       // operands of step 0
-    zero_acc();
 
     // ---- per K step one barrier: group 0 runs  M(k) | barrier | L(k+1),  group 1 runs
     //      L(k) | barrier | M(k).  At the barrier every read of stage k has returned (group 0's were
@@ -1057,25 +1159,48 @@ __device__ __forceinline__ void pingpong_wave(const GemmArgs& g, lds_u8* lds, co
     uint32_t c_bias = Q_BIAS_OFF;                                 // bias slot of the tile being multiplied
     for (uint32_t c_tile = first; c_tile < range_end; c_tile += stride) {
         const int nk = tile_steps(c_tile);
-        for (int k = 0; k < nk; ++k) {
+        // step 0 starts the accumulators, the others add to them (nk >= 4)
+        if (GRP == 0) {
+            mma_phase(std::true_type{});
+            barrier_after_mfma(acc);
+            load_phase();
+        } else {
+            load_phase();
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            mma_phase(std::true_type{});
+        }
+        for (int k = 1; k < nk; ++k) {
             if (GRP == 0) {
-                mma_phase();
+                mma_phase(std::false_type{});
                 barrier_after_mfma(acc);
                 load_phase();
             } else {
                 load_phase();
                 asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-                mma_phase();
+                mma_phase(std::false_type{});
             }
         }
         const uint32_t z = c_tile / tiles, r = c_tile - z * tiles, tm = r / g.tiles_n;
         const uint32_t m0 = tm * Q_BM + wm * 64, n0 = (r - tm * g.tiles_n) * Q_BN + GRP * 128;
         uint8_t* ep = (uint8_t*)(lds + Q_EP_OFF + wave * P_EP_BYTES);
         const lds_u8* bias = BIAS ? lds + c_bias + GRP * 512 : nullptr;
+        const uint32_t c_bias_now = c_bias;
         if (BIAS) c_bias = c_bias == (uint32_t)Q_BIAS_OFF ? c_bias + 1024u : c_bias - 1024u;
-        if (g.split_k == 1) gemm_epilogue_chunked<true>(g, ep, acc, m0, n0, lane, z, bias);
-        else                gemm_epilogue_chunked<false>(g, ep, acc, m0, n0, lane, z, nullptr);
-        zero_acc();
+        MX_PROBE(6);
+        // wave tile wholly inside the matrix, rows storable 16 bytes at a time, lane offsets within 32 bits
+        const bool final_out = g.split_k == 1;
+        const int64_t ldc = final_out ? g.ldc : (int64_t)g.n;
+        const uint32_t ebytes = (final_out && g.c_bf16) ? 2u : 4u;
+        const bool interior = m0 + 64 <= g.m && n0 + 128 <= g.n && ldc < (1 << 27) &&
+                              ((reinterpret_cast<uintptr_t>(g.c) | (uintptr_t)(ldc * ebytes)) & 15) == 0;
+        if (interior) {
+            if (final_out) gemm_epilogue_interior<true, BIAS>(g, lds + Q_EP_OFF + wave * P_EP_BYTES, acc, m0, n0, z, ldc, BIAS ? lds + c_bias_now + GRP * 512 : nullptr);
+            else           gemm_epilogue_interior<false, false>(g, lds + Q_EP_OFF + wave * P_EP_BYTES, acc, m0, n0, z, ldc, nullptr);
+        } else {
+            if (final_out) gemm_epilogue_chunked<true>(g, ep, acc, m0, n0, lane, z, bias);
+            else           gemm_epilogue_chunked<false>(g, ep, acc, m0, n0, lane, z, nullptr);
+        }
+        MX_PROBE(7);
     }
     // the cursor's trailing loads target this workgroup's LDS: they must land before it is released
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -1098,9 +1223,70 @@ __global__ __launch_bounds__(Q_NT, 2) void mx_gemm_pingpong_kernel(GemmArgs g)
     else          pingpong_wave<1, BIAS>(g, (lds_u8*)lds, wave);
 }
 
+// ---------------------------------------------------------------------------
+// Calibration: the products' MFMA in a register-resident loop.  8 waves per workgroup (two per
+// SIMD, as in the main kernel), each with the main kernel's 8 independent accumulator tiles; every lane
+// loads its 12 operand registers (two 64-K slices of 2 m-side and 4 n-side fragments) once from the
+// caller's buffer and then issues 16 MFMAs per iteration with no memory or LDS access in between.
+// What it measures is the rate the matrix pipe sustains for these operand bytes; that rate depends
+// on the bytes (switching activity against the power limit), which is why the caller supplies them.
+// ---------------------------------------------------------------------------
+constexpr int CAL_WAVES = 8, CAL_FRAGS = 12;
+constexpr size_t CAL_OPERAND_BYTES = (size_t)CAL_WAVES * CAL_FRAGS * 64 * 16;      // 98304
+
+__global__ __launch_bounds__(CAL_WAVES * 64, 1) void calibration_mfma_kernel(const v4i* __restrict__ operands, int iterations,
+                                                                            float* sink)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    v4i f[CAL_FRAGS];
+#pragma unroll
+    for (int q = 0; q < CAL_FRAGS; ++q) f[q] = operands[(wave * CAL_FRAGS + q) * 64 + lane];
+    v16f acc[2][4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    for (int it = 0; it < iterations; ++it) {
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const v4i a = f[kk * 6 + i];
+                const v8i xa = v8i{a.x, a.y, a.z, a.w, 0, 0, 0, 0};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const v4i b = f[kk * 6 + 2 + j];
+                    const v8i xb = v8i{b.x, b.y, b.z, b.w, 0, 0, 0, 0};
+                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(xb, xa, acc[i][j], 4, 4, 0, 0x7F7F7F7F, 0, 0x7F7F7F7F);
+                }
+            }
+        MX_SCHED_FENCE();
+    }
+    // keep the accumulators alive; one value per lane leaves the kernel
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) t += acc[i][j][r];
+    sink[(size_t)blockIdx.x * (CAL_WAVES * 64) + threadIdx.x] = t;
+}
+
 }  // namespace
 
 namespace mxl {
+
+size_t calibration_mfma_operand_bytes() { return CAL_OPERAND_BYTES; }
+
+hipError_t launch_calibration_mfma(const uint8_t* operands, int workgroups, int iterations, float* sink, hipStream_t st)
+{
+    hipLaunchKernelGGL(calibration_mfma_kernel, dim3((unsigned)workgroups), dim3(CAL_WAVES * 64), 0, st,
+                       reinterpret_cast<const v4i*>(operands), iterations, sink);
+    return hipGetLastError();
+}
 
 int gemm_split_k(int64_t m, int64_t n, int64_t k)
 {

@@ -125,6 +125,10 @@ hipError_t launch_ramping_adamw(const RampingAdamwParams& p, hipStream_t st);
 
 hipError_t launch_calibration_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
 
+// Register-resident MFMA loop (calibration of the matrix pipe's sustained rate on given operand bytes).
+size_t calibration_mfma_operand_bytes();
+hipError_t launch_calibration_mfma(const uint8_t* operands, int workgroups, int iterations, float* sink, hipStream_t st);
+
 // Number of K-splits the product will use for these sizes (1 = none).
 int gemm_split_k(int64_t m, int64_t n, int64_t k);
 hipError_t launch_gemm(const GemmParams& p, hipStream_t st);

@@ -891,3 +891,19 @@ def test_transposed_wide_tiles_with_ragged_columns(mx, orc, rows, cols):
     got = mx.mx_quantize_transposed(dev(X, "bf16"), mx.ROUND_SR, 5, 0, True, mx.ROUND_SR, 3, seed=9)
     for g, w, nm in zip(got, want, ("codes_t", "scales_t", "codes_row", "scales_row")):
         assert_same_bytes(g, w, nm + " (both stochastic)")
+
+
+# ------------------------------------------------- calibration helper ----
+
+def test_calibration_mfma_counts_what_it_says(mx):
+    """mx_calibration_mfma on the constant byte 0x22 (two codes of value 1): every MFMA adds 64 products
+    of 1 x 1 to each accumulator entry, so after `it` iterations of two 64-K slices an entry holds
+    128 it, and a lane's sink value (the sum of its 128 accumulator registers) is 128 * 128 * it,
+    exactly (all integers below 2^24).  Pins the loop count behind the flop figure bench.py reports."""
+    ops = torch.full((mx.CALIBRATION_MFMA_OPERAND_BYTES,), 0x22, dtype=torch.uint8, device="cuda")
+    for it, wgs in ((1, 3), (7, 2)):
+        sink = torch.zeros(wgs * 512, device="cuda")
+        flops = mx.mx_calibration_mfma(ops, wgs, it, sink)
+        torch.cuda.synchronize()
+        assert flops == wgs * 8 * it * 16 * 2.0 * 32 * 32 * 64
+        assert torch.all(sink == 128.0 * 128.0 * it)
