@@ -235,6 +235,30 @@ int mx_ema_weight_quant(const void* w, int dtype, float* w_ema, float beta, int 
                   int64_t rows, int64_t cols, int64_t ld,
                   uint8_t* codes, uint8_t* scales, int scale_mode, void* stream);
 
+/* ---- format variant of the ablations: E3M0 elements ---- */
+
+/*
+ * mx_quantize with E3M0 elements, the other 4-bit element format of the paper's format ablation
+ * (Table 7 and its paragraph, which name the format and no more).  Reading, built the way Sec. 3.1's
+ * E2M1 is: code = sign << 3 | exponent field E, three exponent bits, no mantissa bit, bias 3, no
+ * Inf/NaN codes; magnitude 0 for E = 0 and 2^(E-3) for E = 1..7, i.e. 0, 0.25, 0.5, 1, 2, 4, 8, 16;
+ * Q_p = -Q_n = 16, E_max = 4.  Everything else is Sec. 3.2 with these constants: truncation-free scale
+ * s = ceil(log2(2M / (Q_p - Q_n))) = ceil(log2(M / 16)) (8 < M/S <= 16), Eq. 2's scale s = floor(log2 M) - 4
+ * with truncation to +-16 (the group maximum then always lands on +-16), epsilon = 1e-8 for an all-zero
+ * group (s = -30 resp. -31), |s| <= 127; round_D / round_S between the two neighbouring E3M0 values with
+ * the tie rule, the 16-bit draw and the Philox indexing of mx_quantize.  Packed layout as for E2M1.
+ * Only this 1x32 quantizer and the test aid below exist for E3M0: the matrix cores have no such operand
+ * type, so no product takes these codes.  Arguments and errors as mx_quantize.
+ */
+int mx_quantize_e3m0(const void* src, int dtype, int64_t rows, int64_t cols, int64_t ld,
+                uint8_t* codes, uint8_t* scales,
+                int round, int scale_mode,
+                uint64_t seed, uint32_t tensor_id, uint64_t index_base,
+                void* stream);
+/* out[rows x cols] (FP32, dense) = P * 2^s for E3M0 codes.  Test aid. */
+int mx_dequantize_e3m0(const uint8_t* codes, const uint8_t* scales, int64_t rows, int64_t cols,
+                  float* out, void* stream);
+
 /* ---- next step beyond the layer: Q-Ramping's oscillation detection ---- */
 
 /*

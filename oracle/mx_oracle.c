@@ -237,6 +237,132 @@ void orc_quantize(const float* src, int64_t rows, int64_t cols, int64_t ld,
     }
 }
 
+/* ----------------------------------------- E3M0 elements (Table 7's ablation) -- */
+
+/* The format ablation (Table 7 and its paragraph) names E3M0 as the other possible FP4 format and
+ * says no more.  Reading, built the way Sec. 3.1's E2M1 is: sign bit, 3 exponent bits, no mantissa
+ * bit, exponent bias 2^(3-1) - 1 = 3, no Inf/NaN codes.  Exponent field 0 is the subnormal range,
+ * which without a mantissa bit holds only 0; field E >= 1 is 2^(E-3).  Q_p = -Q_n = 16, and the
+ * E_max of Eq. 2 (the exponent of the largest value) is 4. */
+static const double E3M0_MAG[8] = {0.0, 0.25, 0.5, 1.0, 2.0, 4.0, 8.0, 16.0};
+
+double orc_e3m0_value(int code)
+{
+    double m = E3M0_MAG[code & 7];
+    return (code & 8) ? -m : m;
+}
+
+/* Sec. 3.2 with Q_p - Q_n = 32 and E_max = 4. */
+int orc_shared_exponent_e3m0(float M, int scale_mode)
+{
+    double Mt = (M > 0.0f) ? (double)M : 1e-8;
+    int guess, s;
+    (void)frexp(Mt, &guess);
+    if (scale_mode == ORC_SCALE_TRUNCFREE) {
+        /* s = ceil(log2(2*Mt/32)): the smallest integer s with Mt <= 16 * 2^s */
+        s = guess;
+        while (ldexp(16.0, s) < Mt) ++s;
+        while (ldexp(16.0, s - 1) >= Mt) --s;
+    } else {
+        /* s = floor(log2 Mt) - E_max */
+        int e = guess;
+        while (ldexp(1.0, e) > Mt) --e;
+        while (ldexp(1.0, e + 1) <= Mt) ++e;
+        s = e - 4;
+    }
+    if (s > 127) s = 127;
+    if (s < -127) s = -127;
+    return s;
+}
+
+/* two consecutive E3M0 magnitudes with m1 <= a <= m2; m1 = m2 = 16 at or beyond the largest */
+static void bracket_e3m0(double a, double* m1, double* m2)
+{
+    int i = 0;
+    for (int t = 0; t < 8; ++t)
+        if (E3M0_MAG[t] <= a) i = t;
+    *m1 = E3M0_MAG[i];
+    *m2 = (i < 7) ? E3M0_MAG[i + 1] : E3M0_MAG[7];
+}
+
+static int mag_index_e3m0(double m)
+{
+    for (int t = 0; t < 8; ++t)
+        if (E3M0_MAG[t] == m) return t;
+    return 7;
+}
+
+/* round_D of Sec. 3.2 on the E3M0 grid: q1 iff strictly nearer, else q2 */
+static int round_rtn_e3m0_d(double y)
+{
+    int sign = signbit(y) ? 8 : 0;
+    double m1, m2, q1, q2;
+    bracket_e3m0(fabs(y), &m1, &m2);
+    if (!sign) { q1 = m1;  q2 = m2;  }
+    else       { q1 = -m2; q2 = -m1; }
+    double pick = (fabs(y - q1) < fabs(y - q2)) ? q1 : q2;
+    return sign | mag_index_e3m0(fabs(pick));
+}
+
+/* round_S of Sec. 3.2 on the E3M0 grid, with the same use of the 16 random bits as for E2M1 */
+static int round_sr_e3m0_d(double y, uint32_t r16)
+{
+    int sign = signbit(y) ? 8 : 0;
+    double a = fabs(y), m1, m2;
+    bracket_e3m0(a, &m1, &m2);
+    double p = (m2 > m1) ? (a - m1) / (m2 - m1) : 0.0;
+    int up = ((double)r16 < 65536.0 * p);
+    return sign | mag_index_e3m0(up ? m2 : m1);
+}
+
+int orc_round_rtn_e3m0(float y) { return round_rtn_e3m0_d((double)y); }
+int orc_round_sr_e3m0(float y, uint32_t r16) { return round_sr_e3m0_d((double)y, r16); }
+
+void orc_quantize_e3m0(const float* src, int64_t rows, int64_t cols, int64_t ld,
+                  uint8_t* codes, uint8_t* scales,
+                  int round, int scale_mode,
+                  uint64_t seed, uint32_t tensor_id, uint64_t index_base)
+{
+    int64_t groups = cols / 32;
+    #pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        for (int64_t g = 0; g < groups; ++g) {
+            const float* x = src + r * ld + 32 * g;
+            float M = group_amax(x, 1);
+            int s = orc_shared_exponent_e3m0(M, scale_mode);
+            scales[r * groups + g] = (uint8_t)(s + 127);
+            for (int i = 0; i < 32; ++i) {
+                int64_t c = 32 * g + i;
+                double y = ldexp((double)x[i], -s);                 /* exact */
+                if (scale_mode == ORC_SCALE_FLOOR) {                /* Eq. 2's scale leaves |y| up to 32: truncated to Q_p */
+                    if (y > 16.0) y = 16.0;
+                    if (y < -16.0) y = -16.0;
+                }
+                int code;
+                if (round == ORC_ROUND_SR) {
+                    uint64_t e = index_base + (uint64_t)r * (uint64_t)cols + (uint64_t)c;
+                    code = round_sr_e3m0_d(y, orc_sr_bits(seed, tensor_id, e));
+                } else {
+                    code = round_rtn_e3m0_d(y);
+                }
+                put_code(codes + r * (cols / 2), c, code);
+            }
+        }
+    }
+}
+
+void orc_dequantize_e3m0(const uint8_t* codes, const uint8_t* scales,
+                    int64_t rows, int64_t cols, double* out)
+{
+    int64_t groups = cols / 32;
+    #pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t c = 0; c < cols; ++c) {
+            int s = (int)scales[r * groups + c / 32] - 127;
+            out[r * cols + c] = ldexp(orc_e3m0_value(get_code(codes + r * (cols / 2), c)), s);
+        }
+}
+
 void orc_dequantize(const uint8_t* codes, const uint8_t* scales,
                     int64_t rows, int64_t cols, double* out)
 {

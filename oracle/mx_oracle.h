@@ -74,6 +74,21 @@ int orc_round_sr(float y, uint32_t r16);
  * itself an E2M1 value the result is y. */
 int orc_round_ema(float y, float z);
 
+/* E3M0 elements, the other FP4 format of the format ablation (Table 7): sign, 3 exponent bits, no
+ * mantissa bit, bias 3; magnitudes 0, 0.25, 0.5, 1, 2, 4, 8, 16 (Q_p = 16, E_max = 4).  The functions
+ * below are the E3M0 counterparts of orc_e2m1_value, orc_shared_exponent, orc_round_rtn,
+ * orc_round_sr, orc_quantize and orc_dequantize: Sec. 3.2 with these constants. */
+double orc_e3m0_value(int code);
+int orc_shared_exponent_e3m0(float M, int scale_mode);
+int orc_round_rtn_e3m0(float y);
+int orc_round_sr_e3m0(float y, uint32_t r16);
+void orc_quantize_e3m0(const float* src, int64_t rows, int64_t cols, int64_t ld,
+                  uint8_t* codes, uint8_t* scales,
+                  int round, int scale_mode,
+                  uint64_t seed, uint32_t tensor_id, uint64_t index_base);
+void orc_dequantize_e3m0(const uint8_t* codes, const uint8_t* scales,
+                    int64_t rows, int64_t cols, double* out);
+
 /* Quantize src[rows x cols] (row stride ld elements) in 1x32 groups along the
  * columns.  Element (r, c) has global index index_base + r*cols + c. */
 void orc_quantize(const float* src, int64_t rows, int64_t cols, int64_t ld,

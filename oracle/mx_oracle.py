@@ -59,6 +59,18 @@ def lib():
         L.orc_round_sr.argtypes = [ctypes.c_float, _u32]
         L.orc_round_ema.restype = _int
         L.orc_round_ema.argtypes = [ctypes.c_float, ctypes.c_float]
+        L.orc_e3m0_value.restype = ctypes.c_double
+        L.orc_e3m0_value.argtypes = [_int]
+        L.orc_shared_exponent_e3m0.restype = _int
+        L.orc_shared_exponent_e3m0.argtypes = [ctypes.c_float, _int]
+        L.orc_round_rtn_e3m0.restype = _int
+        L.orc_round_rtn_e3m0.argtypes = [ctypes.c_float]
+        L.orc_round_sr_e3m0.restype = _int
+        L.orc_round_sr_e3m0.argtypes = [ctypes.c_float, _u32]
+        L.orc_quantize_e3m0.restype = None
+        L.orc_quantize_e3m0.argtypes = [_f32p, _i64, _i64, _i64, _u8p, _u8p, _int, _int, _u64, _u32, _u64]
+        L.orc_dequantize_e3m0.restype = None
+        L.orc_dequantize_e3m0.argtypes = [_u8p, _u8p, _i64, _i64, _f64p]
         L.orc_quantize.restype = None
         L.orc_quantize.argtypes = [_f32p, _i64, _i64, _i64, _u8p, _u8p, _int, _int, _u64, _u32, _u64]
         L.orc_quantize_transposed.restype = None
@@ -203,6 +215,45 @@ def dequantize(codes, scales):
     rows, cols = codes.shape[0], codes.shape[1] * 2
     out = np.zeros((rows, cols), np.float64)
     lib().orc_dequantize(_p(codes, _u8p), _p(scales, _u8p), rows, cols, _p(out, _f64p))
+    return out
+
+
+# ---- E3M0 elements (Table 7's format ablation) ----
+
+def e3m0_value(code):
+    return lib().orc_e3m0_value(int(code))
+
+
+def shared_exponent_e3m0(M, scale_mode=SCALE_TRUNCFREE):
+    return int(lib().orc_shared_exponent_e3m0(float(M), int(scale_mode)))
+
+
+def round_rtn_e3m0(y):
+    return int(lib().orc_round_rtn_e3m0(float(y)))
+
+
+def round_sr_e3m0(y, r16):
+    return int(lib().orc_round_sr_e3m0(float(y), int(r16)))
+
+
+def quantize_e3m0(src, round=ROUND_RTN, scale_mode=SCALE_TRUNCFREE, seed=0, tensor_id=0, index_base=0):
+    """1x32 groups along the columns, E3M0 elements -> (codes[rows, cols/2], scales[rows, cols/32])."""
+    src = _f32(src)
+    rows, cols = src.shape
+    assert cols % 32 == 0
+    ld = src.strides[0] // 4
+    codes = np.zeros((rows, cols // 2), np.uint8)
+    scales = np.zeros((rows, cols // 32), np.uint8)
+    lib().orc_quantize_e3m0(_p(src, _f32p), rows, cols, ld, _p(codes, _u8p), _p(scales, _u8p),
+                            int(round), int(scale_mode), int(seed), int(tensor_id), int(index_base))
+    return codes, scales
+
+
+def dequantize_e3m0(codes, scales):
+    codes, scales = _u8(codes), _u8(scales)
+    rows, cols = codes.shape[0], codes.shape[1] * 2
+    out = np.zeros((rows, cols), np.float64)
+    lib().orc_dequantize_e3m0(_p(codes, _u8p), _p(scales, _u8p), rows, cols, _p(out, _f64p))
     return out
 
 

@@ -24,7 +24,7 @@ ROUND_RTN, ROUND_SR = 0, 1
 SCALE_TRUNCFREE, SCALE_FLOOR = 0, 1
 GEMM_FWD, GEMM_BWD_DX, GEMM_BWD_DW = 0, 1, 2
 
-EXPORTS = ["mx_quantize", "mx_quantize_transposed", "mx_quantize_transposed_batch", "mx_column_sum_workspace_bytes", "mx_linear_fwd", "mx_linear_fwd_bias", "mx_linear_bwd_dx",
+EXPORTS = ["mx_quantize", "mx_quantize_e3m0", "mx_dequantize_e3m0", "mx_quantize_transposed", "mx_quantize_transposed_batch", "mx_column_sum_workspace_bytes", "mx_linear_fwd", "mx_linear_fwd_bias", "mx_linear_bwd_dx",
            "mx_linear_bwd_dw", "mx_linear_bwd_dw_noalloc", "mx_ema_weight_quant", "mx_linear_workspace_bytes",
            "mx_oscillation_accumulate", "mx_ramping_factor",
            "mx_ramping_adamw_step", "mx_quant_confidence", "mx_rate_of_change_workspace_bytes", "mx_rate_of_change_step",
@@ -67,6 +67,10 @@ def lib():
                                       ctypes.c_int, ctypes.c_size_t, ctypes.c_float)
     L.mx_quantize.restype = ci
     L.mx_quantize.argtypes = [vp, ci, i64, i64, i64, vp, vp, ci, ci, u64, u32, u64, vp]
+    L.mx_quantize_e3m0.restype = ci
+    L.mx_quantize_e3m0.argtypes = [vp, ci, i64, i64, i64, vp, vp, ci, ci, u64, u32, u64, vp]
+    L.mx_dequantize_e3m0.restype = ci
+    L.mx_dequantize_e3m0.argtypes = [vp, vp, i64, i64, vp, vp]
     L.mx_quantize_transposed.restype = ci
     L.mx_quantize_transposed.argtypes = [vp, ci, i64, i64, i64, vp, vp, ci, u32, ci, vp, vp, ci, u32,
                                          vp, vp, ci, u64, u64, vp]
@@ -156,6 +160,25 @@ def mx_quantize(src, round=ROUND_RTN, scale_mode=SCALE_TRUNCFREE, seed=0, tensor
                            round, scale_mode, seed, tensor_id, index_base, _stream(stream))
     _check("mx_quantize", rc)
     return codes, scales
+
+
+def mx_quantize_e3m0(src, round=ROUND_RTN, scale_mode=SCALE_TRUNCFREE, seed=0, tensor_id=0, index_base=0,
+                     out=None, stream=None):
+    """mx_quantize with E3M0 elements (the format ablation's other 4-bit format); same packed layout."""
+    rows, cols, ld = _matrix(src)
+    codes, scales = out if out is not None else (_u8((rows, cols // 2), src.device), _u8((rows, cols // 32), src.device))
+    rc = lib().mx_quantize_e3m0(_ptr(src), _src_dtype(src), rows, cols, ld, _ptr(codes), _ptr(scales),
+                                round, scale_mode, seed, tensor_id, index_base, _stream(stream))
+    _check("mx_quantize_e3m0", rc)
+    return codes, scales
+
+
+def mx_dequantize_e3m0(codes, scales, stream=None):
+    rows, cols = codes.shape[0], codes.shape[1] * 2
+    out = torch.empty((rows, cols), dtype=torch.float32, device=codes.device)
+    rc = lib().mx_dequantize_e3m0(_ptr(codes), _ptr(scales), rows, cols, _ptr(out), _stream(stream))
+    _check("mx_dequantize_e3m0", rc)
+    return out
 
 
 def mx_quantize_transposed(src, round_t=ROUND_SR, tensor_id_t=0, pre_quant=1, want_row=True,

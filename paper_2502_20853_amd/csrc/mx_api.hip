@@ -119,6 +119,31 @@ int mx_quantize(const void* src, int dtype, int64_t rows, int64_t cols, int64_t 
     return hip_status(mxl::launch_quantize_rows(p, static_cast<hipStream_t>(stream)));
 }
 
+int mx_quantize_e3m0(const void* src, int dtype, int64_t rows, int64_t cols, int64_t ld,
+                uint8_t* codes, uint8_t* scales, int round, int scale_mode,
+                uint64_t seed, uint32_t tensor_id, uint64_t index_base, void* stream)
+{
+    int rc = check_rows_call(src, dtype, rows, cols, ld, codes, scales, scale_mode);
+    if (rc != MX_OK) return rc;
+    if (round != MX_ROUND_RTN && round != MX_ROUND_SR) return MX_ERR_MODE;
+    if (round == MX_ROUND_SR && (index_base & 7u) != 0) return MX_ERR_ALIGN;
+    mxl::QuantRowsParams p{};
+    p.src = src; p.bf16 = dtype == MX_DTYPE_BF16; p.rows = rows; p.cols = cols; p.ld = ld;
+    p.codes = codes; p.scales = scales; p.sr = round == MX_ROUND_SR;
+    p.floor_mode = scale_mode == MX_SCALE_FLOOR;
+    p.seed = seed; p.tensor_id = tensor_id; p.index_base = index_base;
+    return hip_status(mxl::launch_quantize_rows_e3m0(p, static_cast<hipStream_t>(stream)));
+}
+
+int mx_dequantize_e3m0(const uint8_t* codes, const uint8_t* scales, int64_t rows, int64_t cols,
+                  float* out, void* stream)
+{
+    if (!codes || !scales || !out) return MX_ERR_NULL;
+    if (rows <= 0 || cols <= 0 || (cols % 32) != 0) return MX_ERR_SHAPE;
+    if (rows > MAX_ELEMS / cols) return MX_ERR_SHAPE;
+    return hip_status(mxl::launch_dequantize_e3m0(codes, scales, rows, cols, out, static_cast<hipStream_t>(stream)));
+}
+
 // Checks one transposed-quantizer request and fills the launcher's parameters.
 static int make_transposed_job(const void* src, int dtype, int64_t rows, int64_t cols, int64_t ld,
                 uint8_t* codes_t, uint8_t* scales_t, int round_t, uint32_t tensor_id_t,

@@ -236,6 +236,66 @@ __device__ __forceinline__ U8 sr_addends(uint64_t blk, uint32_t tensor_id, uint3
     return a;
 }
 
+// ---- E3M0 elements (the other 4-bit format of the paper's format ablation, Table 7) -------------
+// Code = sign << 3 | exponent field E (3 bits, no mantissa bit); magnitude 0 for E = 0 and 2^(E-3)
+// otherwise: 0, 0.25, 0.5, 1, 2, 4, 8, 16 (bias 3, no Inf/NaN codes), Q_p = 16, E_max = 4.
+// The same construction as for E2M1 works one bit higher: v = x * 2^(-s-124) puts |y| in [0, 16] onto
+// FP32 patterns whose exponent field IS the code of the lower neighbour (|y| < 0.25 lands in the
+// subnormals, the bracket [0, 0.25]) and whose 23 mantissa bits are p * 2^23.
+//   truncation-free scale: s = ceil(log2(M / 16)) = e - 4 for M = 2^e exactly, e - 3 otherwise;
+//   Eq. 2's scale:         s = floor(log2 M) - 4.
+// epsilon = 1e-8 = 1.34 * 2^-27 for an all-zero group gives s = -30 resp. -31.
+__device__ __forceinline__ uint32_t scale_byte_e3m0(uint32_t amax_bits, bool floor_mode)
+{
+    uint32_t field = (amax_bits + (floor_mode ? 0u : 0x7FFFFFu)) >> 23;   // carries iff the mantissa is not zero
+    uint32_t b;
+    asm("v_sub_u32_e64 %0, %1, 4 clamp" : "=v"(b) : "v"(field));
+    return amax_bits == 0u ? (floor_mode ? 96u : 97u) : b;
+}
+
+constexpr uint32_t GRID_MAX_BITS_E3M0 = 7u << 23;     // 16 * 2^-124
+
+__device__ __forceinline__ int grid_exponent_e3m0(uint32_t byte) { return 3 - (int)byte; }
+
+// round_D; rounding mode toward minus infinity (see rtn_code).
+template <bool FLOOR>
+__device__ __forceinline__ uint32_t rtn_code_e3m0(float x, int e)
+{
+    uint32_t vb = __float_as_uint(__builtin_ldexpf(x, e));
+    uint32_t mag = vb & 0x7FFFFFFFu;
+    if (FLOOR) mag = mag > GRID_MAX_BITS_E3M0 ? GRID_MAX_BITS_E3M0 : mag;
+    uint32_t t = mag + 0x400000u + (uint32_t)((int32_t)vb >> 31);
+    return (t >> 23) | ((vb >> 28) & 8u);
+}
+
+// round_S; rounding mode toward plus infinity; rinv = ((65535 - r16) << 7) | 127.
+template <bool FLOOR>
+__device__ __forceinline__ uint32_t sr_code_e3m0(float x, int e, uint32_t rinv)
+{
+    uint32_t mag = __float_as_uint(__builtin_ldexpf(__builtin_fabsf(x), e));
+    if (FLOOR) mag = mag > GRID_MAX_BITS_E3M0 ? GRID_MAX_BITS_E3M0 : mag;
+    return ((mag + rinv) >> 23) | ((__float_as_uint(x) >> 28) & 8u);
+}
+
+__device__ __forceinline__ U8 sr_addends_e3m0(uint64_t blk, uint32_t tensor_id, uint32_t k0, uint32_t k1)
+{
+    U4 r = sr_block(blk, tensor_id, k0, k1);
+    U8 a;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        a.w[2 * i] = ((65535u - (r.w[i] & 0xFFFFu)) << 7) | 127u;
+        a.w[2 * i + 1] = ((65535u - (r.w[i] >> 16)) << 7) | 127u;
+    }
+    return a;
+}
+
+// signed value of an E3M0 code times 2^s: (E << 23) is 2^(E-127) as an FP32 pattern (0 for E = 0)
+__device__ __forceinline__ float dequant_e3m0(uint32_t code, uint32_t byte)
+{
+    float mag = __builtin_ldexpf(__uint_as_float((code & 7u) << 23), (int)byte - 3);
+    return __uint_as_float(__float_as_uint(mag) | ((code & 8u) << 28));
+}
+
 // ---- cross-lane max over aligned groups of 4 lanes (one 32-element group) ---
 __device__ __forceinline__ uint32_t quad_max(uint32_t v)
 {

@@ -59,6 +59,9 @@ struct GemmParams {
 };
 
 hipError_t launch_quantize_rows(const QuantRowsParams& p, hipStream_t st);
+hipError_t launch_quantize_rows_e3m0(const QuantRowsParams& p, hipStream_t st);      // E3M0 elements (Table 7)
+hipError_t launch_dequantize_e3m0(const uint8_t* codes, const uint8_t* scales, int64_t rows, int64_t cols,
+                                  float* out, hipStream_t st);
 hipError_t launch_ema_quantize(const QuantRowsParams& p, float* ema, float beta, int update_ema, hipStream_t st);
 hipError_t launch_quantize_tile(const QuantTileParams& p, hipStream_t st);
 size_t column_sum_workspace_bytes(int64_t rows, int64_t cols);

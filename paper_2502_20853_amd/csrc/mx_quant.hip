@@ -65,6 +65,38 @@ __device__ __forceinline__ void set_round_mode_for()
     else    f32_round_toward_minus_inf();
 }
 
+// The 1x32 quantizer with E3M0 elements (format ablation, Table 7): same work split as
+// quantize_rows_kernel, the element codec one bit higher in the FP32 layout.
+template <typename SrcT, bool SR, bool FLOOR>
+__global__ __launch_bounds__(ROWS_THREADS) void quantize_rows_e3m0_kernel(RowsArgs a)
+{
+    set_round_mode_for<SR>();
+    const SrcT* src = static_cast<const SrcT*>(a.src);
+    for (uint32_t q = blockIdx.x * ROWS_THREADS + threadIdx.x; q < a.total; q += gridDim.x * ROWS_THREADS) {
+        // a.total is a multiple of 4 and a quad starts at a multiple of 4: the four lanes of a group stay together
+        int64_t off;
+        if (a.contiguous) {
+            off = (int64_t)q * 8;
+        } else {
+            uint32_t r = q / a.cpr;
+            off = (int64_t)r * a.ld + (int64_t)(q - r * a.cpr) * 8;
+        }
+        const F8 x = load8(src + off);
+        const uint32_t byte = scale_byte_e3m0(quad_max(amax_bits8(x)), FLOOR);
+        const int e = grid_exponent_e3m0(byte);
+        U8 rnd;
+        if (SR) rnd = sr_addends_e3m0(a.base_blk + q, a.tensor_id, a.k0, a.k1);
+        uint32_t packed = 0;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            uint32_t c = SR ? sr_code_e3m0<FLOOR>(x.v[t], e, rnd.w[t]) : rtn_code_e3m0<FLOOR>(x.v[t], e);
+            packed |= c << (4 * t);
+        }
+        reinterpret_cast<uint32_t*>(a.codes)[q] = packed;
+        if ((threadIdx.x & 3) == 0) a.scales[q >> 2] = (uint8_t)byte;
+    }
+}
+
 template <typename SrcT, bool SR, bool FLOOR>
 __global__ __launch_bounds__(ROWS_THREADS) void quantize_rows_kernel(RowsArgs a)
 {
@@ -766,6 +798,18 @@ __global__ void dequantize_kernel(const uint8_t* codes, const uint8_t* scales, i
     out[2 * i + 1] = dequant(b >> 4, byte);
 }
 
+__global__ void dequantize_e3m0_kernel(const uint8_t* codes, const uint8_t* scales, int64_t total, int64_t cols, float* out)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;       // index of a code byte
+    if (i >= total) return;
+    int64_t half = cols >> 1;
+    int64_t r = i / half, j = i - r * half;
+    uint32_t byte = scales[r * (cols >> 5) + (j >> 4)];
+    uint32_t b = codes[i];
+    out[2 * i] = dequant_e3m0(b & 15u, byte);
+    out[2 * i + 1] = dequant_e3m0(b >> 4, byte);
+}
+
 __global__ __launch_bounds__(256) void calibration_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n)
 {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -802,6 +846,41 @@ hipError_t launch_quantize_rows(const QuantRowsParams& p, hipStream_t st)
         default: MX_ROWS_LAUNCH(uint16_t, true, true); break;
     }
 #undef MX_ROWS_LAUNCH
+    return hipGetLastError();
+}
+
+hipError_t launch_quantize_rows_e3m0(const QuantRowsParams& p, hipStream_t st)
+{
+    RowsArgs a{};
+    a.src = p.src; a.codes = p.codes; a.scales = p.scales; a.ema = nullptr;
+    a.ld = p.ld; a.cpr = (uint32_t)(p.cols / 8); a.total = (uint32_t)(p.rows * (p.cols / 8));
+    a.contiguous = p.ld == p.cols; a.floor_mode = p.floor_mode;
+    a.k0 = (uint32_t)p.seed; a.k1 = (uint32_t)(p.seed >> 32); a.tensor_id = p.tensor_id;
+    a.base_blk = p.index_base >> 3;
+    uint32_t blocks = (a.total + ROWS_THREADS - 1) / ROWS_THREADS;
+    dim3 grid(blocks < 8192u ? blocks : 8192u), block(ROWS_THREADS);
+#define MX_ROWS_LAUNCH(T, SR, FL) hipLaunchKernelGGL((quantize_rows_e3m0_kernel<T, SR, FL>), grid, block, 0, st, a)
+    const int variant = (p.bf16 ? 4 : 0) | (p.sr ? 2 : 0) | (p.floor_mode ? 1 : 0);
+    switch (variant) {
+        case 0: MX_ROWS_LAUNCH(float, false, false); break;
+        case 1: MX_ROWS_LAUNCH(float, false, true); break;
+        case 2: MX_ROWS_LAUNCH(float, true, false); break;
+        case 3: MX_ROWS_LAUNCH(float, true, true); break;
+        case 4: MX_ROWS_LAUNCH(uint16_t, false, false); break;
+        case 5: MX_ROWS_LAUNCH(uint16_t, false, true); break;
+        case 6: MX_ROWS_LAUNCH(uint16_t, true, false); break;
+        default: MX_ROWS_LAUNCH(uint16_t, true, true); break;
+    }
+#undef MX_ROWS_LAUNCH
+    return hipGetLastError();
+}
+
+hipError_t launch_dequantize_e3m0(const uint8_t* codes, const uint8_t* scales, int64_t rows, int64_t cols,
+                                  float* out, hipStream_t st)
+{
+    int64_t total = rows * (cols / 2);
+    dim3 grid((unsigned)((total + 255) / 256)), block(256);
+    hipLaunchKernelGGL(dequantize_e3m0_kernel, grid, block, 0, st, codes, scales, total, cols, out);
     return hipGetLastError();
 }
 

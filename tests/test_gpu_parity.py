@@ -907,3 +907,60 @@ def test_calibration_mfma_counts_what_it_says(mx):
         torch.cuda.synchronize()
         assert flops == wgs * 8 * it * 16 * 2.0 * 32 * 32 * 64
         assert torch.all(sink == 128.0 * 128.0 * it)
+
+
+# ------------------------------------------------- E3M0 elements (format ablation, Table 7) ----
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("rnd", [0, 1])
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("shape", [(256, 192), (37, 1056), (1, 32), (4100, 2080)])
+def test_quantize_e3m0_rows(mx, orc, dtype, rnd, mode, shape):
+    """The E3M0 quantizer against the oracle, bit for bit: both source types, both roundings, both scale
+    rules; sizes from one group to more elements than one pass of the launch covers; midpoints of the
+    E3M0 grid, all-zero groups and signed zeros planted; dequantized values too."""
+    x = mixed_matrix(*shape, seed=30 + shape[0], dtype=dtype)
+    if shape[1] >= 64:
+        x[0, 32:40] = x[0, 40] * np.array([0.75, -0.75, 0.375, -0.375, 0.1875, -0.1875, 0.09375, 1.0], np.float32)
+    want = orc.quantize_e3m0(x, round=rnd, scale_mode=mode, seed=78, tensor_id=5, index_base=8192)
+    got = mx.mx_quantize_e3m0(dev(x, dtype), rnd, mode, seed=78, tensor_id=5, index_base=8192)
+    assert_same_bytes(got[1], want[1], "scales")
+    assert_same_bytes(got[0], want[0], "codes")
+    deq = host(mx.mx_dequantize_e3m0(*got)).astype(np.float64)
+    assert np.array_equal(deq, orc.dequantize_e3m0(*want))
+
+
+def test_quantize_e3m0_extreme_values_and_strides(mx, orc):
+    """Subnormals, the clamp at s = -127, the largest finite inputs, exact powers of two and their
+    neighbours, quotients far below FP32's range; a strided view with a 64-bit seed and index base."""
+    rows = 64
+    x = np.zeros((rows, 64), np.float32)
+    bits = np.array([0x00000001, 0x00000100, 0x007FFFFF, 0x00800000, 0x00800001, 0x00FFFFFF, 0x01000000,
+                     0x3F800000, 0x3F800001, 0x3F7FFFFF, 0x7F7FFFFF, 0x7F000000, 0x7E800000, 0x41800000,
+                     0x41800001, 0x417FFFFF], np.uint32)
+    for i, b in enumerate(bits):
+        x[i, 0] = np.array([b], np.uint32).view(np.float32)[0]
+        x[i, 1:32] = x[i, 0] * np.linspace(-1, 1, 31, dtype=np.float32)
+        x[i, 32] = -x[i, 0]
+        x[i, 33:64] = x[i, 0] * np.float32(2.0) ** -np.arange(1, 32, dtype=np.float32) * 1.7
+    rng = np.random.default_rng(1)
+    x[16:48] = rng.standard_normal((32, 64)).astype(np.float32) * np.float32(2.0) ** rng.integers(-140, 120, (32, 1)).astype(np.float32)
+    x[48:, ::32] = np.float32(2.0) ** rng.integers(0, 60, (16, 2)).astype(np.float32)
+    tiny = np.float32(2.0) ** rng.integers(-149, -100, (16, 64)).astype(np.float32) * rng.choice(np.array([-1.0, 1.0], np.float32), (16, 64))
+    mask = np.ones((16, 64), bool)
+    mask[:, ::32] = False
+    x[48:][mask] = tiny[mask]
+    x = np.nan_to_num(x, posinf=3e38, neginf=-3e38)
+    for rnd in (0, 1):
+        for mode in (0, 1):
+            for seed in (5, 6):
+                want = orc.quantize_e3m0(x, round=rnd, scale_mode=mode, seed=seed, tensor_id=1)
+                got = mx.mx_quantize_e3m0(dev(x), rnd, mode, seed=seed, tensor_id=1)
+                assert_same_bytes(got[1], want[1], "scales r%d m%d" % (rnd, mode))
+                assert_same_bytes(got[0], want[0], "codes r%d m%d" % (rnd, mode))
+    big = mixed_matrix(64, 256, seed=4, dtype="bf16")
+    seed = 0xDEADBEEF12345678
+    want = orc.quantize_e3m0(big[:, 64:192], round=1, seed=seed, tensor_id=0xFFFFFFFF, index_base=(1 << 36) + 8)
+    got = mx.mx_quantize_e3m0(dev(big, "bf16")[:, 64:192], 1, 0, seed=seed, tensor_id=0xFFFFFFFF, index_base=(1 << 36) + 8)
+    assert_same_bytes(got[0], want[0], "strided codes")
+    assert_same_bytes(got[1], want[1], "strided scales")

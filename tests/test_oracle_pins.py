@@ -885,3 +885,121 @@ def test_column_sums_f32_ordered_pins(orc):
     x[0, 0], x[1 * 256, 0], x[2 * 256, 0] = 2.0 ** 24, 1.0, 1.0
     assert orc.column_sums_f32_ordered(x)[0] == np.float32(2.0 ** 24)
     assert orc.column_sums(x)[0] == 2.0 ** 24 + 2
+
+
+# ------------------------------------------------- E3M0 elements (Table 7's format ablation) ----
+
+E3M0_GRID = [0.0, 0.25, 0.5, 1.0, 2.0, 4.0, 8.0, 16.0]
+
+
+def test_e3m0_table_from_bit_fields(orc):
+    """sign | 3 exponent bits | no mantissa bit, bias 3: exponent field 0 is the (empty) subnormal range,
+    i.e. 0; field E >= 1 is 2^(E - 3).  Largest value 16 = 2^4: Q_p = 16, E_max = 4."""
+    for code in range(16):
+        E, sign = code & 7, code >> 3
+        mag = 0.0 if E == 0 else 2.0 ** (E - 3)
+        v = orc.e3m0_value(code)
+        assert abs(v) == mag and (math.copysign(1.0, v) < 0) == bool(sign)
+    assert max(orc.e3m0_value(c) for c in range(16)) == 16.0
+    assert sorted(abs(orc.e3m0_value(c)) for c in range(8)) == E3M0_GRID
+
+
+def test_e3m0_shared_exponent_vs_exact_rational(orc):
+    """Sec. 3.2's two rules with Q_p - Q_n = 32 and E_max = 4 against exact rational arithmetic, incl.
+    exact powers of two (the only values where the ceiling does not round up) and their neighbours."""
+    rng = np.random.default_rng(21)
+    bits = rng.integers(0x00800000, 0x7F000000, size=3000, dtype=np.uint32)
+    special = [((e + 127) << 23) | m for e in range(-120, 120, 7) for m in (0, 1, 0x400000, 0x7FFFFF)]
+    bits = np.concatenate([bits, np.array(special, np.uint32)])
+    for u, v in zip(bits.tolist(), bits.view(np.float32).tolist()):
+        fr = Fraction(v)
+        tf = _exact_ceil_log2(2 * fr / 32)
+        fl = _exact_floor_log2(fr) - 4
+        assert orc.shared_exponent_e3m0(v, orc.SCALE_TRUNCFREE) == max(-127, min(127, tf))
+        assert orc.shared_exponent_e3m0(v, orc.SCALE_FLOOR) == max(-127, min(127, fl))
+        e, m = (u >> 23) - 127, u & 0x7FFFFF
+        assert tf == e - 4 + (1 if m > 0 else 0) and fl == e - 4
+    # the worked magnitude of Sec. 3.2, M = 31: truncation-free S = 2 (15.5 fits), Eq. 2's S = 1 (31 is cut to 16)
+    assert orc.shared_exponent_e3m0(31.0, orc.SCALE_TRUNCFREE) == 1
+    assert orc.shared_exponent_e3m0(31.0, orc.SCALE_FLOOR) == 0
+    # all-zero group: epsilon = 1e-8
+    eps = PAPER["zero_group_epsilon"]["epsilon"]
+    assert orc.shared_exponent_e3m0(0.0, orc.SCALE_TRUNCFREE) == math.ceil(math.log2(eps / 16)) == -30
+    assert orc.shared_exponent_e3m0(0.0, orc.SCALE_FLOOR) == math.floor(math.log2(eps)) - 4 == -31
+    assert orc.shared_exponent_e3m0(float(np.float32(1e-45)), orc.SCALE_TRUNCFREE) == -127
+
+
+def test_e3m0_rtn_brute_force_and_ties(orc):
+    """Every bf16 value in [-16, 16]: the nearest of the 15 values, a midpoint to the larger value."""
+    signed = sorted(set([-g for g in E3M0_GRID] + E3M0_GRID))
+    grid = np.array(signed)
+    u = np.arange(65536, dtype=np.uint32) << 16
+    y = u.view(np.float32)
+    y = y[np.isfinite(y) & (np.abs(y) <= 16.0)]
+    for v in y.tolist():
+        d = np.abs(grid - v)
+        best = grid[np.flatnonzero(d == d.min()).max()]
+        code = orc.round_rtn_e3m0(v)
+        assert orc.e3m0_value(code) == best, v
+        assert (code >> 3) == (1 if math.copysign(1.0, v) < 0 else 0)
+    ties = {0.125: 0.25, 0.375: 0.5, 0.75: 1.0, 1.5: 2.0, 3.0: 4.0, 6.0: 8.0, 12.0: 16.0,
+            -0.125: 0.0, -0.375: -0.25, -0.75: -0.5, -1.5: -1.0, -3.0: -2.0, -6.0: -4.0, -12.0: -8.0}
+    for yv, want in ties.items():
+        assert orc.e3m0_value(orc.round_rtn_e3m0(yv)) == want
+
+
+def test_e3m0_sr_exhaustive_counts(orc):
+    for y in (0.1, 0.125, 0.3, 1.2, 1.999, 2.75, 5.0, 11.0, 15.999, -0.3, -2.2, -9.0, 1e-6, 4.0, -16.0, 0.0):
+        y = f32(y)
+        a = abs(y)
+        m1 = max(g for g in E3M0_GRID if g <= a)
+        m2 = min([g for g in E3M0_GRID if g > m1] or [m1])
+        p = (Fraction(a) - Fraction(m1)) / Fraction(m2 - m1) if m2 > m1 else Fraction(0)
+        ups = 0
+        for r in range(0, 65536):
+            v = orc.e3m0_value(orc.round_sr_e3m0(y, r))
+            assert abs(v) in (m1, m2) and (v == 0 or (v < 0) == (y < 0))
+            ups += abs(v) == m2 and m2 > m1
+        assert ups == math.ceil(65536 * p), y
+
+
+def test_e3m0_quantize_invariants(orc):
+    """Range invariants of the two scale rules, the error bound of round_D (half the gap of the cell the
+    scaled value lies in), 2^k equivariance, Eq. 2's rule always putting the group maximum on +-16, the
+    all-zero group, the pack layout, and stochastic decisions recomposed from (sr_bits, round_sr)."""
+    rng = np.random.default_rng(22)
+    x = (rng.standard_normal((48, 160)) * np.exp(rng.uniform(-15, 15, (48, 1)))).astype(np.float32)
+    x[5, 32:64] = 0.0
+    M = np.abs(x.reshape(48, 5, 32)).max(-1).astype(np.float64)
+    nz = M > 0
+    c, s = orc.quantize_e3m0(x, scale_mode=orc.SCALE_TRUNCFREE)
+    S = 2.0 ** (s.astype(np.int64) - 127)
+    r = M / S
+    assert np.all(r[nz] <= 16.0) and np.all(r[nz] > 8.0)
+    assert s[5, 1] == 127 - 30 and np.all(c[5, 16:32] == 0)
+    d = orc.dequantize_e3m0(c, s)
+    y = np.abs(x.astype(np.float64)) / np.repeat(S, 32, axis=1)
+    lo = np.where(y >= 0.25, 2.0 ** np.floor(np.log2(np.maximum(y, 1e-300))), 0.0)
+    gap = np.where(y >= 0.25, lo, 0.25)
+    assert np.all(np.abs(np.abs(d) - np.abs(x.astype(np.float64))) <= 0.5 * gap * np.repeat(S, 32, axis=1) + 1e-300)
+    c8, s8 = orc.quantize_e3m0(x * np.float32(8.0), scale_mode=orc.SCALE_TRUNCFREE)
+    assert np.array_equal(c8, c) and np.array_equal(s8.astype(np.int64)[nz], s.astype(np.int64)[nz] + 3)
+    cf, sf = orc.quantize_e3m0(x, scale_mode=orc.SCALE_FLOOR)
+    rf = M / 2.0 ** (sf.astype(np.int64) - 127)
+    assert np.all(rf[nz] >= 16.0) and np.all(rf[nz] < 32.0)
+    df = np.abs(orc.dequantize_e3m0(cf, sf)).reshape(48, 5, 32).max(-1)
+    assert np.all(df[nz] == 16.0 * 2.0 ** (sf.astype(np.int64) - 127)[nz])
+    assert sf[5, 1] == 127 - 31
+    # pack layout: low nibble = even column
+    codes = [orc.round_rtn_e3m0(float(np.float32(v)) / float(S[0, 0])) for v in x[0, :4]]
+    assert c[0, 0] == codes[0] | (codes[1] << 4) and c[0, 1] == codes[2] | (codes[3] << 4)
+    # stochastic rounding follows the element index of the source
+    cs, ss = orc.quantize_e3m0(x, round=orc.ROUND_SR, seed=77, tensor_id=3, index_base=1 << 33)
+    assert np.array_equal(ss, s)
+    for (rr, cc) in ((0, 0), (7, 33), (47, 159), (20, 100)):
+        e = (1 << 33) + rr * 160 + cc
+        yv = float(np.float32(x[rr, cc])) / float(S[rr, cc // 32])
+        want = orc.round_sr_e3m0(np.float32(yv), orc.sr_bits(77, 3, e)) if abs(yv) >= 2.0 ** -100 else None
+        got = (cs[rr, cc // 2] >> (4 * (cc & 1))) & 15
+        if want is not None:
+            assert got == want
