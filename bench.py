@@ -285,6 +285,53 @@ def main():
     mfma_cal.update({"unit": "TFLOP/s", "kernel": "calibration_mfma_kernel", "workgroups": n_cu, "waves_per_simd": 2,
                      "note": "register-resident V_MFMA_SCALE_F32_32X32X64_F8F6F4 loop; calibration only, not the roofline peak"})
 
+    # fc1 -> GELU -> fc2's quantizers, outside the timed region: the fused forward product (GELU and fc2's Q1
+    # in fc1's output stage, fc2's Q6 from the packed codes) against the separate calls (forward product with
+    # bias, an element-wise GELU kernel, the fused Q1/Q6 quantizer reading the activation)
+    mlp_fusion = None
+    if not args.no_other_schedule and [n for (n, _, _, _) in layers[2:4]] == ["fc1", "fc2"]:
+        (_, N1, D1, C1), st1, st2 = layers[2], steps_obj[2], steps_obj[3]
+        bias1 = torch.randn(C1, device="cuda") * 0.1
+        gelu = torch.nn.functional.gelu
+        act = gelu(st1.y)
+
+        def sep_product():
+            B.mx_linear_fwd_bias(st1.xq, st1.xs, st1.wq, st1.ws, bias1, out=st1.y, workspace=st1.workspace)
+
+        def sep_quant():
+            B.mx_quantize_transposed(act, B.ROUND_SR, 6, 1, True, B.ROUND_RTN, 1, seed=1, out=(st2.xtq, st2.xts, st2.xq, st2.xs))
+
+        def separate():
+            sep_product()
+            a = gelu(st1.y)                                # (torch's allocator hands back the same block each time)
+            B.mx_quantize_transposed(a, B.ROUND_SR, 6, 1, True, B.ROUND_RTN, 1, seed=1, out=(st2.xtq, st2.xts, st2.xq, st2.xs))
+
+        def fused_product():
+            B.mx_linear_fwd_gelu_quant(st1.xq, st1.xs, st1.wq, st1.ws, bias1, out=st1.y, quant_out=(st2.xq, st2.xs))
+
+        def q6_from_codes():
+            B.mx_quantize_transposed(None, B.ROUND_SR, 6, 1, False, row_in=(st2.xq, st2.xs), seed=1, shape=(N1, C1),
+                                     out=(st2.xtq, st2.xts, None, None))
+
+        def fused():
+            fused_product()
+            q6_from_codes()
+
+        mlp_fusion = {"layer": "fc1 -> GELU -> fc2 quantizers", "shape": [N1, C1, D1]}
+        for key, fn in (("separate_us", separate), ("fused_us", fused), ("separate_product_us", sep_product),
+                        ("separate_gelu_us", lambda: gelu(st1.y)), ("separate_quantizer_us", sep_quant),
+                        ("fused_product_us", fused_product), ("fused_q6_from_codes_us", q6_from_codes)):
+            for _ in range(3):
+                fn()
+            e0, e1 = ev(), ev()
+            e0.record()
+            for _ in range(10):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            mlp_fusion[key] = round(e0.elapsed_time(e1) / 10 * 1e3, 1)
+        del act
+
     # Q-EMA weight quantizer (Sec. 5), outside the timed region: the four weights of the block, one
     # update + quantization each, as a training step with Q-EMA would issue them
     qema = []
@@ -455,6 +502,7 @@ def main():
         "mfma_sustained": mfma_cal,
         "launches": launches,
         "forward_with_bias": fwd_bias,
+        "mlp_fusion": mlp_fusion,
         "qema_weight_quant": qema,
         "oscillation_detection": osc,
         "other_schedule": None if other_ms is None else {

@@ -185,6 +185,30 @@ int mx_linear_fwd_bias(const uint8_t* xq, const uint8_t* xs, const uint8_t* wq, 
                   int64_t N, int64_t C, int64_t D, const float* bias,
                   void* y, int y_dtype, int64_t ldy,
                   void* workspace, size_t workspace_bytes, void* stream);
+/* The forward product of the first layer of a transformer MLP with the element-wise neighbour and the NEXT
+ * layer's forward quantizer in its output stage (Sec. 7.1 quantizes all linear layers of the MLP module; fc1
+ * feeds fc2 through GELU only).  One launch gives
+ *     P      = Q1(X) . Q2(W)^T + 1 . bias^T                 (Eq. 3 of this layer), stored to y as y_dtype: the
+ *              pre-activation, which the backward pass of the activation needs;
+ *     aq, as = Q(1) of the next layer (Eq. 3 there: 1x32 groups along the C columns, round_D, scale_mode)
+ *              applied to A = GELU(P), GELU(x) = x * Phi(x) with the exact normal distribution function,
+ *              evaluated in FP32 on the FP32 value of P (before its rounding to y_dtype).
+ * aq [N x C/2], as [N x C/32] are what mx_linear_fwd of the next layer takes as xq, xs; its Q(6) comes from
+ * mx_quantize_transposed with row_codes_in = aq, row_scales_in = as (double quantization, Sec. 3.3).  This
+ * removes the activation kernel's pass over P and the read of A by the next layer's quantizer.
+ * Accuracy: P as mx_linear_fwd_bias; the value that is quantized differs from the exact GELU of the exact
+ * product by at most 1.13 |P - P_exact| + 2^-18 |A| + 2^-120 (FP32 erfc, which underflows for |A| near 1e-38),
+ * so a code or scale byte may differ from those of the exact A only where A lies within that distance of a
+ * rounding threshold or a scale boundary.
+ *   bias    device, FP32, C values, 16-byte aligned; required (pass zeros for a layer without bias)
+ *   aq, as  device out; aq 16-byte aligned
+ *   C % 32 == 0; D % 128 == 0 and D >= 512 and no K split (the sizes the main kernel takes without a K split;
+ *   every MLP of the ViT configurations), else MX_ERR_SHAPE.  No workspace.  Everything else as
+ *   mx_linear_fwd_bias. */
+int mx_linear_fwd_gelu_quant(const uint8_t* xq, const uint8_t* xs, const uint8_t* wq, const uint8_t* ws,
+                  int64_t N, int64_t C, int64_t D, const float* bias,
+                  void* y, int y_dtype, int64_t ldy,
+                  uint8_t* aq, uint8_t* as, int scale_mode, void* stream);
 int mx_linear_bwd_dx(const uint8_t* dyq, const uint8_t* dys, const uint8_t* wtq, const uint8_t* wts,
                   int64_t N, int64_t C, int64_t D,
                   void* dx, int dx_dtype, int64_t lddx,

@@ -237,6 +237,18 @@ void orc_quantize(const float* src, int64_t rows, int64_t cols, int64_t ld,
     }
 }
 
+/* ------------------------------------------------------------------ GELU -- */
+
+/* The activation between the two linear layers of a transformer MLP (Sec. 7.1 quantizes all linear
+ * layers of the MLP module): GELU(x) = x * Phi(x), Phi the standard normal distribution function,
+ * Phi(x) = erfc(-x / sqrt(2)) / 2.  FP64. */
+void orc_gelu(const double* x, int64_t n, double* out)
+{
+    #pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i)
+        out[i] = x[i] * (0.5 * erfc(-x[i] / sqrt(2.0)));
+}
+
 /* ----------------------------------------- E3M0 elements (Table 7's ablation) -- */
 
 /* The format ablation (Table 7 and its paragraph) names E3M0 as the other possible FP4 format and

@@ -74,6 +74,10 @@ int orc_round_sr(float y, uint32_t r16);
  * itself an E2M1 value the result is y. */
 int orc_round_ema(float y, float z);
 
+/* GELU(x) = x * Phi(x) (exact form), FP64, element-wise: the activation between the two linear layers of
+ * the MLP module, used by the check of the product with the fused activation and next-layer quantizer. */
+void orc_gelu(const double* x, int64_t n, double* out);
+
 /* E3M0 elements, the other FP4 format of the format ablation (Table 7): sign, 3 exponent bits, no
  * mantissa bit, bias 3; magnitudes 0, 0.25, 0.5, 1, 2, 4, 8, 16 (Q_p = 16, E_max = 4).  The functions
  * below are the E3M0 counterparts of orc_e2m1_value, orc_shared_exponent, orc_round_rtn,

@@ -59,6 +59,8 @@ def lib():
         L.orc_round_sr.argtypes = [ctypes.c_float, _u32]
         L.orc_round_ema.restype = _int
         L.orc_round_ema.argtypes = [ctypes.c_float, ctypes.c_float]
+        L.orc_gelu.restype = None
+        L.orc_gelu.argtypes = [_f64p, _i64, _f64p]
         L.orc_e3m0_value.restype = ctypes.c_double
         L.orc_e3m0_value.argtypes = [_int]
         L.orc_shared_exponent_e3m0.restype = _int
@@ -216,6 +218,24 @@ def dequantize(codes, scales):
     out = np.zeros((rows, cols), np.float64)
     lib().orc_dequantize(_p(codes, _u8p), _p(scales, _u8p), rows, cols, _p(out, _f64p))
     return out
+
+
+def gelu(x):
+    """GELU(x) = x * Phi(x), FP64, element-wise."""
+    x = np.ascontiguousarray(x, np.float64)
+    out = np.empty_like(x)
+    lib().orc_gelu(_p(x.reshape(-1), _f64p), x.size, _p(out.reshape(-1), _f64p))
+    return out
+
+
+def linear_fwd_gelu_quant(xq, xs, wq, ws, bias, scale_mode=SCALE_TRUNCFREE):
+    """The first MLP layer followed by GELU and the next layer's forward quantizer, step by step:
+    P = Q1(X) . Q2(W)^T + bias (FP64), A = GELU(P) (FP64), then the 1x32 round_D quantizer on A rounded
+    to FP32.  Returns (P, A, codes, scales)."""
+    P = gemm_f64(xq, xs, wq, ws) + np.asarray(bias, np.float64)[None, :]
+    A = gelu(P)
+    codes, scales = quantize(A.astype(np.float32), round=ROUND_RTN, scale_mode=scale_mode)
+    return P, A, codes, scales
 
 
 # ---- E3M0 elements (Table 7's format ablation) ----

@@ -10,7 +10,7 @@ from .binding import (  # noqa: F401
     RateOfChangeState, mx_quant_confidence, mx_rate_of_change_step,
     RampingAdamwState, mx_ramping_adamw_step,
     CALIBRATION_MFMA_OPERAND_BYTES, NOALLOC_MAX_WORKSPACE_BYTES, mx_calibration_copy, mx_calibration_mfma,
-    mx_linear_bwd_dw_noalloc, mx_quantize_e3m0, mx_dequantize_e3m0,
+    mx_linear_bwd_dw_noalloc, mx_quantize_e3m0, mx_dequantize_e3m0, mx_linear_fwd_gelu_quant,
 )
 from .layer import MxLinearStep  # noqa: F401
 from .module import MxLinear  # noqa: F401

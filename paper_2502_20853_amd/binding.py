@@ -24,7 +24,7 @@ ROUND_RTN, ROUND_SR = 0, 1
 SCALE_TRUNCFREE, SCALE_FLOOR = 0, 1
 GEMM_FWD, GEMM_BWD_DX, GEMM_BWD_DW = 0, 1, 2
 
-EXPORTS = ["mx_quantize", "mx_quantize_e3m0", "mx_dequantize_e3m0", "mx_quantize_transposed", "mx_quantize_transposed_batch", "mx_column_sum_workspace_bytes", "mx_linear_fwd", "mx_linear_fwd_bias", "mx_linear_bwd_dx",
+EXPORTS = ["mx_quantize", "mx_quantize_e3m0", "mx_dequantize_e3m0", "mx_quantize_transposed", "mx_quantize_transposed_batch", "mx_column_sum_workspace_bytes", "mx_linear_fwd", "mx_linear_fwd_bias", "mx_linear_fwd_gelu_quant", "mx_linear_bwd_dx",
            "mx_linear_bwd_dw", "mx_linear_bwd_dw_noalloc", "mx_ema_weight_quant", "mx_linear_workspace_bytes",
            "mx_oscillation_accumulate", "mx_ramping_factor",
            "mx_ramping_adamw_step", "mx_quant_confidence", "mx_rate_of_change_workspace_bytes", "mx_rate_of_change_step",
@@ -84,6 +84,8 @@ def lib():
     L.mx_column_sum_workspace_bytes.argtypes = [i64, i64]
     L.mx_linear_fwd_bias.restype = ci
     L.mx_linear_fwd_bias.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, vp, ci, i64, vp, sz, vp]
+    L.mx_linear_fwd_gelu_quant.restype = ci
+    L.mx_linear_fwd_gelu_quant.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, vp, ci, i64, vp, vp, ci, vp]
     L.mx_ema_weight_quant.restype = ci
     L.mx_ema_weight_quant.argtypes = [vp, ci, vp, f32, ci, i64, i64, i64, vp, vp, ci, vp]
     L.mx_linear_workspace_bytes.restype = sz
@@ -309,6 +311,23 @@ def mx_linear_fwd_bias(xq, xs, wq, ws, bias, out=None, out_dtype=torch.float32, 
                                   _ptr(out), _src_dtype(out), out.stride(0), _ptr(workspace), wbytes, _stream(stream))
     _check("mx_linear_fwd_bias", rc)
     return out
+
+
+def mx_linear_fwd_gelu_quant(xq, xs, wq, ws, bias, out=None, out_dtype=torch.bfloat16, scale_mode=SCALE_TRUNCFREE,
+                             quant_out=None, stream=None):
+    """fc1 of an MLP with GELU and the next layer's forward quantizer in the product's output stage.
+    Returns (P[N, C] pre-activation with bias, aq[N, C/2], as[N, C/32])."""
+    N, D, C = xq.shape[0], xq.shape[1] * 2, wq.shape[0]
+    if bias.dtype != torch.float32 or not bias.is_contiguous() or bias.numel() != C:
+        raise ValueError("bias must be a contiguous float32 tensor of C values")
+    if out is None:
+        out = torch.empty((N, C), dtype=out_dtype, device=xq.device)
+    aq, as_ = quant_out if quant_out is not None else (_u8((N, C // 2), xq.device), _u8((N, C // 32), xq.device))
+    rc = lib().mx_linear_fwd_gelu_quant(_ptr(xq), _ptr(xs), _ptr(wq), _ptr(ws), N, C, D, _ptr(bias),
+                                        _ptr(out), _src_dtype(out), out.stride(0), _ptr(aq), _ptr(as_), scale_mode,
+                                        _stream(stream))
+    _check("mx_linear_fwd_gelu_quant", rc)
+    return out, aq, as_
 
 
 def mx_linear_bwd_dx(dyq, dys, wtq, wts, out=None, out_dtype=torch.float32, workspace=None, stream=None):

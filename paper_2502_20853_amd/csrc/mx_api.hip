@@ -250,6 +250,26 @@ int mx_linear_fwd_bias(const uint8_t* xq, const uint8_t* xs, const uint8_t* wq, 
     return run_gemm(xq, xs, wq, ws, N, C, D, y, y_dtype, ldy, workspace, workspace_bytes, stream, bias);
 }
 
+int mx_linear_fwd_gelu_quant(const uint8_t* xq, const uint8_t* xs, const uint8_t* wq, const uint8_t* ws,
+                  int64_t N, int64_t C, int64_t D, const float* bias, void* y, int y_dtype, int64_t ldy,
+                  uint8_t* aq, uint8_t* as, int scale_mode, void* stream)
+{
+    if (!bias || !aq || !as) return MX_ERR_NULL;
+    if (N <= 0 || C <= 0 || D <= 0) return (!xq || !xs || !wq || !ws || !y) ? MX_ERR_NULL : MX_ERR_SHAPE;
+    int rc = check_gemm_call(xq, xs, wq, ws, N, C, D, y, y_dtype, ldy);
+    if (rc != MX_OK) return rc;
+    if (scale_mode != MX_SCALE_TRUNCFREE && scale_mode != MX_SCALE_FLOOR) return MX_ERR_MODE;
+    if ((C % 32) != 0 || !mxl::gemm_takes_fused_quantizer(N, C, D)) return MX_ERR_SHAPE;
+    if (!aligned(bias, 16) || !aligned(aq, 16)) return MX_ERR_ALIGN;
+    mxl::GemmParams p{};
+    p.a_codes = xq; p.a_scales = xs; p.b_codes = wq; p.b_scales = ws;
+    p.m = N; p.n = C; p.k = D;
+    p.c = y; p.c_bf16 = y_dtype == MX_DTYPE_BF16; p.ldc = ldy;
+    p.workspace = nullptr; p.split_k = 1; p.bias = bias;
+    p.q_codes = aq; p.q_scales = as; p.q_floor = scale_mode == MX_SCALE_FLOOR;
+    return hip_status(mxl::launch_gemm(p, static_cast<hipStream_t>(stream)));
+}
+
 int mx_linear_bwd_dx(const uint8_t* dyq, const uint8_t* dys, const uint8_t* wtq, const uint8_t* wts,
                   int64_t N, int64_t C, int64_t D, void* dx, int dx_dtype, int64_t lddx,
                   void* workspace, size_t workspace_bytes, void* stream)

@@ -25,6 +25,7 @@
 //     16 or 32 rows) are bank-conflict free;
 //   - the MFMA's first operand is the B (n) side, so that a lane ends up with runs of four
 //     consecutive n of one m and stores 8 or 16 contiguous bytes.
+#include "mx_device.hpp"
 #include "mx_launch.hpp"
 
 #include <type_traits>
@@ -66,6 +67,9 @@ struct GemmArgs {
     uint32_t tiles_m, tiles_n;
     int stagger;             // start delay of every other workgroup of an XCD, in s_sleep(32) units
     const float* bias;       // n values added to every row of a final output (n % 4 == 0), or null
+    uint8_t* q_codes;        // fused GELU + 1x32 quantizer of the output rows (main kernel only): packed codes
+    uint8_t* q_scales;       //   [m x n/2] and scale bytes [m x n/32] of Q(GELU(product + bias)), or null
+    int q_floor;             //   its scale rule: 0 truncation-free, 1 Eq. 2
 };
 
 constexpr int KSTEP_BYTES = 64;     // 128 FP4 elements
@@ -778,6 +782,91 @@ __device__ __forceinline__ void gemm_epilogue_interior(const GemmArgs& g, lds_u8
     }
 }
 
+// GELU(x) = x * Phi(x) with Phi(x) = erfc(-x / sqrt(2)) / 2 (the exact form, not the tanh approximation),
+// FP32.  erfc keeps its relative accuracy in the negative tail, where 1 + erf(x / sqrt(2)) would cancel.
+__device__ __forceinline__ float gelu_f32(float x)
+{
+    return __fmul_rn(__fmul_rn(0.5f, x), erfcf(__fmul_rn(-0.70710678118654752440f, x)));
+}
+
+// Second output stage of the fused forward product of an MLP's first layer: the next layer's forward
+// quantizer Q(1) (Eq. 3; 1x32 groups along the output columns, which are the next layer's contraction
+// dimension, round_D) applied to GELU(product + bias), from the FP32 accumulators.  Runs after the stage
+// that stores the pre-activation and reuses the wave's LDS strip.
+// A lane holds, of each 32 x 32 MFMA tile (i, j), 16 of the 32 columns of one row: the four runs
+// 8q + 4 * lhalf + (0..3); the other 16 are in the lane 32 away.  Group maximum: the lane's 16 values, then one
+// exchange with that lane.  The 16 codes of a lane are four 2-byte pieces of the group's 16 bytes; they go to
+// the strip ([64 rows][64 B] codes, then [64 rows][4] scale bytes) and leave as 16-byte pieces, 64 contiguous
+// bytes per row.  Rows beyond m and column groups beyond n (n % 32 == 0) are not stored.
+template <bool FLOOR>
+__device__ __forceinline__ void gemm_epilogue_gelu_quant(const GemmArgs& g, lds_u8* ep, v16f (&acc)[2][4],
+                                                         uint32_t mrow0, uint32_t nbase, const lds_u8* bias)
+{
+    typedef __attribute__((address_space(3))) v4f lds_v4f;
+    typedef __attribute__((address_space(3))) v4i lds_v4i;
+    typedef __attribute__((address_space(3))) uint16_t lds_u16;
+    typedef __attribute__((address_space(3))) uint32_t lds_u32;
+    const uint32_t lane = fresh_lane_id();
+    const uint32_t lrow = lane & 31, lhalf = lane >> 5;
+    lds_u8* scale_strip = ep + 4096;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float v[16];
+            uint32_t m = 0;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const v4f bv = *reinterpret_cast<const lds_v4f*>(bias + (32 * j + 8 * q + 4 * lhalf) * 4);
+                v[4 * q] = gelu_f32(acc[i][j][4 * q] + bv.x);
+                v[4 * q + 1] = gelu_f32(acc[i][j][4 * q + 1] + bv.y);
+                v[4 * q + 2] = gelu_f32(acc[i][j][4 * q + 2] + bv.z);
+                v[4 * q + 3] = gelu_f32(acc[i][j][4 * q + 3] + bv.w);
+                m = mxd::absmax3_bits(v[4 * q], v[4 * q + 1], m);
+                m = mxd::absmax3_bits(v[4 * q + 2], v[4 * q + 3], m);
+            }
+            const auto sw = __builtin_amdgcn_permlane32_swap(m, m, false, false);
+            m = sw[0] > sw[1] ? sw[0] : sw[1];
+            const uint32_t byte = mxd::scale_byte(m, FLOOR);
+            const int e = mxd::grid_exponent(byte);
+            mxd::f32_round_toward_minus_inf();              // round_D's mode for inexact subnormal scalings
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                uint32_t pk = 0;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) pk |= mxd::rtn_code<FLOOR>(v[4 * q + r], e) << (4 * r);
+                *reinterpret_cast<lds_u16*>(ep + (i * 32 + lrow) * 64 + 16 * j + 4 * q + 2 * lhalf) = (uint16_t)pk;
+            }
+            mxd::f32_round_to_nearest_even();
+            if (lhalf == 0) scale_strip[(i * 32 + lrow) * 4 + j] = (uint8_t)byte;
+        }
+    asm volatile("" ::: "memory");          // the strip is read back below through other lanes' addresses
+    // codes: 4 lanes per row (one column group each), 16 rows per instruction
+    const uint32_t half_n = g.n >> 1, grp_n = g.n >> 5;
+    const uint32_t piece = lane & 3, prow = lane >> 2;
+    const bool group_ok = nbase + 32 * piece < g.n;
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const uint32_t row = it * 16 + prow;
+        const v4i c = *reinterpret_cast<const lds_v4i*>(ep + row * 64 + piece * 16);
+        if (group_ok && mrow0 + row < g.m)
+            *reinterpret_cast<v4i*>(g.q_codes + (size_t)(mrow0 + row) * half_n + (nbase >> 1) + piece * 16) = c;
+    }
+    // scale bytes: one row per lane
+    {
+        const uint32_t sc = *reinterpret_cast<const lds_u32*>(scale_strip + lane * 4);
+        if (mrow0 + lane < g.m) {
+            uint8_t* dst = g.q_scales + (size_t)(mrow0 + lane) * grp_n + (nbase >> 5);
+            if (nbase + 128 <= g.n && (grp_n & 3u) == 0u && (reinterpret_cast<uintptr_t>(g.q_scales) & 3u) == 0u) {
+                *reinterpret_cast<uint32_t*>(dst) = sc;
+            } else {
+                for (uint32_t b = 0; b < 4; ++b)
+                    if (nbase + 32 * b < g.n) dst[b] = (uint8_t)(sc >> (8 * b));
+            }
+        }
+    }
+}
+
 // bias: LDS address of the bias value of column nbase (FP32, 128 values), or null.
 template <bool STREAM>
 __device__ __forceinline__ void gemm_epilogue_chunked(const GemmArgs& g, uint8_t* ep, v16f (&acc)[2][4],
@@ -934,7 +1023,7 @@ __device__ __forceinline__ void dma_load16_at(uint32_t lds_addr, const uint8_t* 
 // The whole tile walk of one wave; GRP (0: columns 0-127, M phase first; 1: columns 128-255, L phase
 // first) is a template parameter so that each group's loop is straight-line code.  All cursor
 // state is wave-uniform (scalar registers) and advanced with compares and adds only.
-template <int GRP, bool BIAS>
+template <int GRP, bool BIAS, bool GELUQ>
 __device__ __forceinline__ void pingpong_wave(const GemmArgs& g, lds_u8* lds, const int wave)
 {
     const uint32_t tiles = g.tiles_m * g.tiles_n, total = tiles * (uint32_t)g.split_k;
@@ -1200,6 +1289,11 @@ __device__ __forceinline__ void pingpong_wave(const GemmArgs& g, lds_u8* lds, co
             if (final_out) gemm_epilogue_chunked<true>(g, ep, acc, m0, n0, lane, z, bias);
             else           gemm_epilogue_chunked<false>(g, ep, acc, m0, n0, lane, z, nullptr);
         }
+        if (GELUQ) {
+            // BIAS is set with GELUQ: the bias slot of this tile is still valid (it is reused two tiles later)
+            if (g.q_floor) gemm_epilogue_gelu_quant<true>(g, lds + Q_EP_OFF + wave * P_EP_BYTES, acc, m0, n0, lds + c_bias_now + GRP * 512);
+            else           gemm_epilogue_gelu_quant<false>(g, lds + Q_EP_OFF + wave * P_EP_BYTES, acc, m0, n0, lds + c_bias_now + GRP * 512);
+        }
         MX_PROBE(7);
     }
     // the cursor's trailing loads target this workgroup's LDS: they must land before it is released
@@ -1208,7 +1302,8 @@ __device__ __forceinline__ void pingpong_wave(const GemmArgs& g, lds_u8* lds, co
 
 // BIAS: a bias row is added in the output stage (a separate instance: the plain product's code is
 // the same with and without this feature in the source).
-template <bool BIAS>
+// GELUQ (only with BIAS): a second output stage quantizes GELU(product + bias) for the next layer.
+template <bool BIAS, bool GELUQ = false>
 __global__ __launch_bounds__(Q_NT, 2) void mx_gemm_pingpong_kernel(GemmArgs g)
 {
     __shared__ __attribute__((aligned(1024))) uint8_t lds[BIAS ? Q_LDS_BYTES : Q_BIAS_OFF];
@@ -1219,8 +1314,8 @@ __global__ __launch_bounds__(Q_NT, 2) void mx_gemm_pingpong_kernel(GemmArgs g)
     // of the workgroups start half a K loop later, so that one half stores while the other multiplies.
     if ((blockIdx.x >> 3) & 1)
         for (int i = 0; i < g.stagger; ++i) __builtin_amdgcn_s_sleep(32);
-    if (wave < 4) pingpong_wave<0, BIAS>(g, (lds_u8*)lds, wave);
-    else          pingpong_wave<1, BIAS>(g, (lds_u8*)lds, wave);
+    if (wave < 4) pingpong_wave<0, BIAS, GELUQ>(g, (lds_u8*)lds, wave);
+    else          pingpong_wave<1, BIAS, GELUQ>(g, (lds_u8*)lds, wave);
 }
 
 // ---------------------------------------------------------------------------
@@ -1305,6 +1400,12 @@ int gemm_split_k(int64_t m, int64_t n, int64_t k)
     return (int)s;
 }
 
+bool gemm_takes_fused_quantizer(int64_t m, int64_t n, int64_t k)
+{
+    // the main kernel: K a multiple of 128 with at least four K steps, and no K split
+    return (k & 127) == 0 && k >= 512 && (n & 31) == 0 && gemm_split_k(m, n, k) == 1;
+}
+
 hipError_t launch_gemm(const GemmParams& p, hipStream_t st)
 {
     GemmArgs g{};
@@ -1331,12 +1432,21 @@ hipError_t launch_gemm(const GemmParams& p, hipStream_t st)
             // 3-5 % at K = 2304, nothing at K = 3072; pointless below two rounds of tiles
             g.stagger = (g.split_k == 1 && nblk >= 2 * Q_SLOTS && p.k <= 2304) ? 3 : 0;
             const dim3 pgrid(nblk < Q_SLOTS ? nblk : Q_SLOTS);
-            if (g.bias) hipLaunchKernelGGL(mx_gemm_pingpong_kernel<true>, pgrid, dim3(Q_NT), 0, st, g);
-            else        hipLaunchKernelGGL(mx_gemm_pingpong_kernel<false>, pgrid, dim3(Q_NT), 0, st, g);
+            if (p.q_codes) {
+                if (!g.bias || g.split_k != 1) return hipErrorInvalidValue;
+                g.q_codes = p.q_codes; g.q_scales = p.q_scales; g.q_floor = p.q_floor ? 1 : 0;
+                hipLaunchKernelGGL((mx_gemm_pingpong_kernel<true, true>), pgrid, dim3(Q_NT), 0, st, g);
+            } else if (g.bias) {
+                hipLaunchKernelGGL(mx_gemm_pingpong_kernel<true>, pgrid, dim3(Q_NT), 0, st, g);
+            } else {
+                hipLaunchKernelGGL(mx_gemm_pingpong_kernel<false>, pgrid, dim3(Q_NT), 0, st, g);
+            }
         } else {
+            if (p.q_codes) return hipErrorInvalidValue;          // the fused quantizer lives in the main kernel only
             hipLaunchKernelGGL(mx_gemm_dma_kernel, grid, dim3(D_NT), 0, st, g);
         }
     } else {
+        if (p.q_codes) return hipErrorInvalidValue;
         g.tiles_m = (uint32_t)((p.m + G_BM - 1) / G_BM);
         g.tiles_n = (uint32_t)((p.n + G_BN - 1) / G_BN);
         dim3 grid(g.tiles_m * g.tiles_n, 1, g.split_k);

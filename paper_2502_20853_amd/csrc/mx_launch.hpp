@@ -56,7 +56,14 @@ struct GemmParams {
     void* workspace;
     int split_k;     // >= 1; > 1 needs workspace of split_k * m * n floats
     const float* bias = nullptr;   // n values added to every output row (needs n % 4 == 0), or null
+    // fused GELU + 1x32 round_D quantizer of the output (needs bias, k % 128 == 0, k >= 512, no K split,
+    // n % 32 == 0): codes [m x n/2], scale bytes [m x n/32]; gemm_takes_fused_quantizer() tells
+    uint8_t* q_codes = nullptr;
+    uint8_t* q_scales = nullptr;
+    bool q_floor = false;
 };
+// Whether launch_gemm runs these sizes on the kernel that carries the fused output quantizer.
+bool gemm_takes_fused_quantizer(int64_t m, int64_t n, int64_t k);
 
 hipError_t launch_quantize_rows(const QuantRowsParams& p, hipStream_t st);
 hipError_t launch_quantize_rows_e3m0(const QuantRowsParams& p, hipStream_t st);      // E3M0 elements (Table 7)

@@ -964,3 +964,99 @@ def test_quantize_e3m0_extreme_values_and_strides(mx, orc):
     got = mx.mx_quantize_e3m0(dev(big, "bf16")[:, 64:192], 1, 0, seed=seed, tensor_id=0xFFFFFFFF, index_base=(1 << 36) + 8)
     assert_same_bytes(got[0], want[0], "strided codes")
     assert_same_bytes(got[1], want[1], "strided scales")
+
+
+# ------------------------------------------------- fc1 with GELU and the next layer's quantizer fused ----
+
+def _check_fused_quantizer(orc, P64, absref, P_gpu, got_c, got_s, scale_mode, tag):
+    """The kernel quantizes A' = gelu_f32(P_gpu).  |A' - GELU(P64)| <= 1.13 |P_gpu - P64| + 2^-18 |A| + 2^-120
+    (GELU's Lipschitz constant; FP32 erfc and its underflow), so: the product is within the product tolerance; every scale byte is one
+    that a group maximum within that distance gives; and, under the kernel's scale, every dequantized value
+    lies between round_D(A - tol) and round_D(A + tol) (round_D is monotone).  Where nothing is near a
+    threshold this is bit equality with the oracle, and the check counts how often that is."""
+    err = np.abs(P_gpu.astype(np.float64) - P64)
+    assert np.all(err <= 1e-5 * absref), (tag, "product", np.max(err / (absref + 1e-300)))
+    A = orc.gelu(P64)
+    tol = 1.13 * err + 2.0 ** -18 * np.abs(A) + 2.0 ** -120          # the last term: FP32 erfc underflows near 1e-38
+    want_c, want_s = orc.quantize(A.astype(np.float32), scale_mode=scale_mode)
+    rows, cols = A.shape
+    same_scale = got_s == want_s
+    for r, gidx in zip(*np.nonzero(~same_scale)):
+        seg = slice(32 * gidx, 32 * gidx + 32)
+        lo = max(float(np.max(np.abs(A[r, seg]) - tol[r, seg])), 0.0)
+        hi = float(np.max(np.abs(A[r, seg]) + tol[r, seg]))
+        # a maximum of exactly 0 takes the epsilon rule (s = -29); any positive maximum up to hi takes its own
+        s_ok = set(range(orc.shared_exponent(np.float32(lo), scale_mode) if lo > 0 else -127,
+                         orc.shared_exponent(np.float32(hi), scale_mode) + 1))
+        if lo == 0.0:
+            s_ok.add(orc.shared_exponent(0.0, scale_mode))
+        assert int(got_s[r, gidx]) - 127 in s_ok, (tag, "scale", r, gidx)
+    got_v = orc.dequantize(got_c, got_s)
+    exact = np.repeat(same_scale, 32, axis=1) & (got_v == orc.dequantize(want_c, want_s))
+    S = np.repeat(2.0 ** (got_s.astype(np.float64) - 127), 32, axis=1)
+    clamp = (lambda y: min(max(y, -6.0), 6.0)) if scale_mode == 1 else (lambda y: y)
+    for r, c in zip(*np.nonzero(~exact)):
+        lo = orc.e2m1_value(orc.round_rtn(np.float32(clamp((A[r, c] - tol[r, c]) / S[r, c])))) * S[r, c]
+        hi = orc.e2m1_value(orc.round_rtn(np.float32(clamp((A[r, c] + tol[r, c]) / S[r, c])))) * S[r, c]
+        assert lo <= got_v[r, c] <= hi, (tag, "code", r, c, A[r, c], tol[r, c], got_v[r, c], lo, hi)
+    return float(exact.mean())
+
+
+@pytest.mark.parametrize("scale_mode", [0, 1])
+@pytest.mark.parametrize("N,C,D", [(320, 384, 512), (544, 416, 768), (256, 256, 1024)])
+def test_linear_fwd_gelu_quant(mx, orc, N, C, D, scale_mode):
+    """mx_linear_fwd_gelu_quant against the oracle's product -> GELU -> quantizer: edge rows and columns of
+    the 256 x 256 tiles, a column count whose scale rows are not word-aligned, FP32 and bf16 pre-activation
+    outputs; nearly all codes must equal the oracle's outright."""
+    import mx_workloads as wl
+    X, W, _ = wl.linear_layer(N, D, C, seed=50 + N, dtype="bf16", outliers=3)
+    W = (W * 4).astype(np.float32)                           # pre-activations of order 1: both GELU branches
+    rng = np.random.default_rng(N)
+    bias = rng.standard_normal(C).astype(np.float32)
+    bias[:32] = -30.0                                        # a whole group deep in GELU's negative tail
+    xq, xs = orc.quantize(X)
+    wq, ws = orc.quantize(W)
+    P64, A64, _, _ = orc.linear_fwd_gelu_quant(xq, xs, wq, ws, bias, scale_mode)
+    absref = np.abs(orc.dequantize(xq, xs)) @ np.abs(orc.dequantize(wq, ws)).T + np.abs(bias.astype(np.float64))[None, :]
+    args = (dev(xq, "u8"), dev(xs, "u8"), dev(wq, "u8"), dev(ws, "u8"), dev(bias))
+    y, aq, as_ = mx.mx_linear_fwd_gelu_quant(*args, out_dtype=torch.float32, scale_mode=scale_mode)
+    frac = _check_fused_quantizer(orc, P64, absref, host(y), host(aq), host(as_), scale_mode, "fused %dx%dx%d" % (N, C, D))
+    assert frac > 0.999, frac
+    # the same codes with a bf16 pre-activation output (the quantizer sees the FP32 value either way), and the
+    # pre-activation is what mx_linear_fwd_bias stores
+    y16, aq16, as16 = mx.mx_linear_fwd_gelu_quant(*args, out_dtype=torch.bfloat16, scale_mode=scale_mode)
+    assert torch.equal(aq16, aq) and torch.equal(as16, as_)
+    assert torch.equal(y16, mx.mx_linear_fwd_bias(*args, out_dtype=torch.bfloat16))
+    assert torch.equal(y, mx.mx_linear_fwd_bias(*args, out_dtype=torch.float32))
+    # the next layer: its forward product takes (aq, as) as they are, its Q(6) re-quantizes them
+    W2 = wl.weights(96, C, seed=3, dtype="bf16")
+    w2q, w2s = orc.quantize(W2)
+    y2 = mx.mx_linear_fwd(aq, as_, dev(w2q, "u8"), dev(w2s, "u8"), out_dtype=torch.float32)
+    check_product(orc, y2, host(aq), host(as_), w2q, w2s, "next layer on fused codes")
+    if N % 32 == 0:
+        t = mx.mx_quantize_transposed(None, 1, 6, 1, False, row_in=(aq, as_), seed=4, shape=(N, C))
+        Adq = orc.dequantize(host(aq), host(as_)).astype(np.float32)
+        want_t = orc.quantize_transposed(Adq, round_t=1, tensor_id_t=6, pre_quant=0, want_row=False, seed=4)
+        assert_same_bytes(t[0], want_t[0], "Q6 of the fused codes")
+        assert_same_bytes(t[1], want_t[1], "S6 of the fused codes")
+
+
+def test_linear_fwd_gelu_quant_full_size_fc1(mx, orc):
+    """ViT-B/16 batch 256 fc1 (50432 x 768 -> 3072) through the fused entry point: 384 sampled rows (first,
+    last, random) checked in full against the oracle."""
+    import mx_workloads as wl
+    N, D, C = 50432, 768, 3072
+    X, W, _ = wl.linear_layer(N, D, C, seed=2, dtype="bf16")
+    W = (W * 2).astype(np.float32)
+    bias = np.random.default_rng(5).standard_normal(C).astype(np.float32) * 0.5
+    xq, xs = orc.quantize(X)
+    wq, ws = orc.quantize(W)
+    del X
+    y, aq, as_ = mx.mx_linear_fwd_gelu_quant(dev(xq, "u8"), dev(xs, "u8"), dev(wq, "u8"), dev(ws, "u8"), dev(bias),
+                                             out_dtype=torch.float32)
+    rows = np.unique(np.concatenate([[0, 1, 255, 256, N - 257, N - 256, N - 1], np.random.default_rng(6).integers(0, N, 380)]))
+    P64, A64, _, _ = orc.linear_fwd_gelu_quant(xq[rows], xs[rows], wq, ws, bias)
+    absref = np.abs(orc.dequantize(xq[rows], xs[rows])) @ np.abs(orc.dequantize(wq, ws)).T + np.abs(bias.astype(np.float64))[None, :]
+    idx = torch.from_numpy(rows).cuda()
+    frac = _check_fused_quantizer(orc, P64, absref, host(y[idx]), host(aq[idx]), host(as_[idx]), 0, "fused fc1")
+    assert frac > 0.999, frac

@@ -1003,3 +1003,49 @@ def test_e3m0_quantize_invariants(orc):
         got = (cs[rr, cc // 2] >> (4 * (cc & 1))) & 15
         if want is not None:
             assert got == want
+
+
+# ------------------------------------------------- GELU (between the MLP's two linear layers) ----
+
+def test_gelu_against_library_routines_and_identities(orc):
+    """x * Phi(x): against scipy's normal distribution function and torch's FP64 GELU, the textbook
+    values at 0 and +-1, the identity GELU(x) - GELU(-x) = x (Phi(x) + Phi(-x) = 1), GELU(x) -> x for
+    large x, a correctly signed and relatively accurate negative tail (x Phi(x) with Phi from its
+    asymptotic series), and |GELU'| <= 1.13 (the Lipschitz constant the fused kernel's tolerance uses)."""
+    import torch
+    from scipy.special import ndtr
+    x = np.concatenate([np.linspace(-12, 12, 4001), np.array([0.0, -0.0, 1e-300, -1e-300, 1.0, -1.0, 37.0, -37.0])])
+    g = orc.gelu(x)
+    assert np.allclose(g, x * ndtr(x), rtol=1e-12, atol=0)       # two libm implementations of erfc
+    # torch forms 1 + erf(x / sqrt 2), which cancels in the negative tail: compared where that is harmless
+    mid = np.abs(x) <= 5
+    assert np.allclose(g[mid], torch.nn.functional.gelu(torch.from_numpy(x[mid])).numpy(), rtol=1e-9, atol=1e-15)
+    assert orc.gelu([0.0])[0] == 0.0
+    assert abs(orc.gelu([1.0])[0] - 0.8413447460685429) < 1e-15
+    assert abs(orc.gelu([-1.0])[0] + 0.15865525393145707) < 1e-15
+    assert np.allclose(orc.gelu(x) - orc.gelu(-x), x, rtol=0, atol=1e-14)
+    assert orc.gelu([40.0])[0] == 40.0
+    t = -9.0                                            # Phi(t) ~ phi(t)/|t| * (1 - 1/t^2 + 3/t^4 - 15/t^6)
+    phi = math.exp(-t * t / 2) / math.sqrt(2 * math.pi)
+    series = phi / abs(t) * (1 - 1 / t ** 2 + 3 / t ** 4 - 15 / t ** 6)
+    assert abs(orc.gelu([t])[0] / (t * series) - 1) < 1e-5 and orc.gelu([t])[0] < 0
+    xs = np.linspace(-8, 8, 200001)
+    slope = np.diff(orc.gelu(xs)) / np.diff(xs)
+    assert slope.max() < 1.13 and slope.min() > -0.13
+
+
+def test_fused_reference_is_the_composition(orc):
+    """linear_fwd_gelu_quant = product + bias, GELU, row quantizer, on a tiny layer by hand."""
+    rng = np.random.default_rng(31)
+    X = rng.standard_normal((4, 64)).astype(np.float32)
+    W = (rng.standard_normal((32, 64)) * 0.3).astype(np.float32)
+    bias = rng.standard_normal(32).astype(np.float32)
+    xq, xs = orc.quantize(X)
+    wq, ws = orc.quantize(W)
+    P, A, c, s = orc.linear_fwd_gelu_quant(xq, xs, wq, ws, bias)
+    Pn = orc.dequantize(xq, xs) @ orc.dequantize(wq, ws).T + bias.astype(np.float64)
+    assert np.allclose(P, Pn, rtol=1e-14, atol=1e-14)
+    from scipy.special import ndtr
+    assert np.allclose(A, Pn * ndtr(Pn), rtol=1e-12, atol=1e-300)
+    c2, s2 = orc.quantize(A.astype(np.float32))
+    assert np.array_equal(c, c2) and np.array_equal(s, s2)
