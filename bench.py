@@ -37,7 +37,13 @@ def parse():
                     help="skip the comparison pass under the other stream schedule (for profiler runs: its "
                          "overlapped kernels would mix into the per-kernel statistics)")
     ap.add_argument("--streams", type=int, default=1, choices=(1, 2),
-                    help="2: issue the weight / gradient quantizers and the dW product on a second HIP stream")
+                    help="2: the timed steps without per-kernel events issue the weight / gradient quantizers and the dW "
+                         "product on a second HIP stream (MxLinearStep.step_two_streams); once the chip is warm this "
+                         "measures the same as one stream, which stays the default")
+    ap.add_argument("--settle-ms", type=float, default=250.0,
+                    help="untimed steps are run for this long before the W warm-up steps: after the idle time of input "
+                         "generation the chip needs about 100 ms of load before its clocks settle (the first steps "
+                         "run 5 %% slower), which W = 3..5 steps (7 ms) do not provide")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference dispatch for scaling rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters)")
@@ -112,10 +118,10 @@ def main():
     dw_ws = [torch.empty_like(st.workspace) for st in steps_obj]     # the dW product's own K-split workspace
 
     def run_step(seed, record, side=None):
-        """One step.  With one stream every launch follows the previous one.  With two, the main
-        stream carries quant X -> fwd -> dX and the second one quant W -> quant dY -> dW of the same
-        layer; events express the data dependencies (fwd needs the weight codes, dX the gradient
-        codes, dW the transposed activation codes), so the tail of one kernel overlaps the next."""
+        """One step.  With one stream (side is None) every launch follows the previous one, and per-kernel
+        events may be recorded.  With two, MxLinearStep.step_two_streams spreads a layer's launches over
+        the current stream and `side`, so that the tail of one kernel overlaps the next."""
+        assert not (record and side is not None)
         B = mx.binding
         main = torch.cuda.current_stream()
         for li, (st, (X, W, dY)) in enumerate(zip(steps_obj, inputs)):
@@ -134,45 +140,12 @@ def main():
                 if record: e[6].record()
                 spans = {"quant X+W": (0, 2), "fwd": (2, 3), "quant dY": (3, 4), "dX": (4, 5), "dW": (5, 6)}
             else:
-                fork, w_done, dy_done, x_done = torch.cuda.Event(), torch.cuda.Event(), torch.cuda.Event(), torch.cuda.Event()
-                fork.record(main)
-                side.wait_event(fork)                  # the layer's inputs are ready on the main stream
-                with torch.cuda.stream(side):
-                    if record: e[0].record()
-                    st.quantize_weight(W, seed)
-                    if record: e[1].record()
-                    w_done.record()
-                    if record: e[2].record()
-                    B.mx_quantize_transposed(dY, B.ROUND_SR, 5, 0, True, B.ROUND_SR, 3, seed=seed, out=(st.dytq, st.dyts, st.dyq, st.dys))
-                    if record: e[3].record()
-                    dy_done.record()
-                if record: e[4].record()
-                B.mx_quantize_transposed(X, B.ROUND_SR, 6, 1, True, B.ROUND_RTN, 1, seed=seed, out=(st.xtq, st.xts, st.xq, st.xs))
-                if record: e[5].record()
-                x_done.record(main)
-                main.wait_event(w_done)
-                if record: e[6].record()
-                B.mx_linear_fwd(st.xq, st.xs, st.wq, st.ws, out=st.y, workspace=st.workspace)
-                if record: e[7].record()
-                main.wait_event(dy_done)
-                if record: e[8].record()
-                B.mx_linear_bwd_dx(st.dyq, st.dys, st.wtq, st.wts, out=st.dx, workspace=st.workspace)
-                if record: e[9].record()
-                with torch.cuda.stream(side):
-                    side.wait_event(x_done)
-                    if record: e[10].record()
-                    B.mx_linear_bwd_dw(st.dytq, st.dyts, st.xtq, st.xts, out=st.dw, workspace=dw_ws[li])
-                    if record: e[11].record()
-                spans = {"quant W": (0, 1), "quant dY": (2, 3), "quant X": (4, 5), "fwd": (6, 7), "dX": (8, 9), "dW": (10, 11)}
+                st.step_two_streams(X, W, dY, seed, side, dw_ws[li])      # no events: see layer.py for the schedule
             if record:
                 quant_events.extend([(e[a], e[b]) for k, (a, b) in spans.items() if k.startswith("quant")])
                 gemm_events.extend([(e[a], e[b]) for k, (a, b) in spans.items() if not k.startswith("quant")])
                 for op, (a, b) in spans.items():
                     per_launch.setdefault((li, op), []).append((e[a], e[b]))
-        if side is not None:
-            join = torch.cuda.Event()
-            join.record(side)
-            main.wait_event(join)                      # the step ends when both streams have ended
 
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")      # 1 GiB read, 1 GiB written
@@ -183,6 +156,11 @@ def main():
         del src, dst
 
     timed_side = side_stream if args.streams == 2 else None
+    t_settle = time.perf_counter()
+    while (time.perf_counter() - t_settle) * 1e3 < args.settle_ms:
+        for w in range(5):
+            run_step(w, False, None)
+        torch.cuda.synchronize()
     for w in range(args.warmup):
         run_step(w, False, timed_side)
     torch.cuda.synchronize()
@@ -191,7 +169,9 @@ def main():
     for s in range(args.steps):
         rec = s % max(1, args.event_every) == 0
         n_recorded += rec
-        run_step(1000 + s, rec, timed_side)    # events are recorded on the stream each kernel is launched on
+        # events are recorded on the stream each kernel is launched on; a step that carries them runs on one
+        # stream, so that the interval between a kernel's two events holds no other kernel's work
+        run_step(1000 + s, rec, None if rec else timed_side)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt * 1e3 / args.steps
@@ -489,7 +469,10 @@ def main():
             args.workload, layers[0][1], ",".join("%s %d->%d" % (n, d, c) for (n, _, d, c) in layers)),
             "quantizers": "Q1,Q2 RTN; Q3..Q6 stochastic (Philox4x32-10); truncation-free scale; double quantization",
             "arithmetic": "E2M1 elements x E8M0 group scales in the products, FP32 accumulation; %s sources" % cfg["dtype"],
-            "streams": args.streams, "steps_with_kernel_events": n_recorded},
+            "streams": args.streams, "steps_with_kernel_events": n_recorded,
+            "settle_ms_before_warmup": args.settle_ms,
+            "schedule": ("steps without kernel events: two streams (quant W, quant dY, dW beside quant X, fwd, dX); "
+                         "steps with kernel events: one stream") if args.streams == 2 else "one stream"},
         "roofline": {"bound": "mfma", "kernel": "mx_gemm_pingpong_kernel<false> (12 launches per step)",
                      "achieved": achieved, "peak": PEAK_FP4_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_FP4_TFLOPS,

@@ -73,3 +73,39 @@ class MxLinearStep:
         B.mx_linear_bwd_dx(self.dyq, self.dys, self.wtq, self.wts, out=self.dx, workspace=self.workspace)
         B.mx_linear_bwd_dw(self.dytq, self.dyts, self.xtq, self.xts, out=self.dw, workspace=self.workspace)
         return self.dx, self.dw
+
+    def step_two_streams(self, X, W, dY, seed, side, dw_workspace=None):
+        """forward() + backward() with the launches spread over two streams: the current stream carries
+        quant X -> forward product -> dX product, `side` carries quant W -> quant dY -> dW product; events
+        express the data dependencies (the forward product needs the weight codes, dX the gradient codes,
+        dW the transposed activation codes).  The sparsely filled last round of one kernel then overlaps the
+        next kernel.  Same calls, same results as forward() and backward() (the library holds no state).
+        dw_workspace: the dW product's own K-split workspace (it may run while dX uses self.workspace).
+        When it returns, the current stream waits for `side`."""
+        main = torch.cuda.current_stream()
+        if dw_workspace is None:
+            if getattr(self, "_dw_workspace", None) is None:
+                self._dw_workspace = torch.empty_like(self.workspace)
+            dw_workspace = self._dw_workspace
+        fork, w_done, dy_done, x_done, join = (torch.cuda.Event() for _ in range(5))
+        fork.record(main)
+        side.wait_event(fork)                          # the layer's inputs are ready on the current stream
+        with torch.cuda.stream(side):
+            self.quantize_weight(W, seed)
+            w_done.record()
+            B.mx_quantize_transposed(dY, B.ROUND_SR, Q5, 0, True, B.ROUND_SR, Q3, scale_mode=self.scale_mode,
+                                     seed=seed, out=(self.dytq, self.dyts, self.dyq, self.dys))
+            dy_done.record()
+        B.mx_quantize_transposed(X, B.ROUND_SR, Q6, 1, True, B.ROUND_RTN, Q1, scale_mode=self.scale_mode,
+                                 seed=seed, out=(self.xtq, self.xts, self.xq, self.xs))
+        x_done.record(main)
+        main.wait_event(w_done)
+        B.mx_linear_fwd(self.xq, self.xs, self.wq, self.ws, out=self.y, workspace=self.workspace)
+        main.wait_event(dy_done)
+        B.mx_linear_bwd_dx(self.dyq, self.dys, self.wtq, self.wts, out=self.dx, workspace=self.workspace)
+        with torch.cuda.stream(side):
+            side.wait_event(x_done)
+            B.mx_linear_bwd_dw(self.dytq, self.dyts, self.xtq, self.xts, out=self.dw, workspace=dw_workspace)
+            join.record()
+        main.wait_event(join)
+        return self.y, self.dx, self.dw

@@ -650,6 +650,44 @@ def test_two_streams_give_the_single_stream_results(mx, orc):
     assert_same_bytes(both[0][1], xt[0], "Q6 under two streams")
 
 
+@pytest.mark.parametrize("qema", [False, True])
+def test_two_stream_schedule_of_a_layer_equals_forward_backward(mx, orc, qema):
+    """MxLinearStep.step_two_streams (the schedule bench.py times: quant W, quant dY and dW on a second
+    stream beside quant X, forward and dX) leaves every packed operand and every product exactly as
+    forward() + backward() on one stream do, also when several layers follow one another without a
+    synchronization in between; and they are the oracle's."""
+    import mx_workloads as wl
+    shapes = [(2048 + 32, 512, 768), (1024 + 96, 768, 256), (4096, 256, 512)]
+    data = [wl.linear_layer(N, D, C, seed=60 + i, dtype="bf16", outliers=2) for i, (N, D, C) in enumerate(shapes)]
+    dev_data = [tuple(dev(t, "bf16") for t in d) for d in data]
+    names = ("xq", "xs", "xtq", "xts", "wq", "ws", "wtq", "wts", "dyq", "dys", "dytq", "dyts", "y", "dx", "dw")
+
+    def run(two):
+        steps = [mx.MxLinearStep(N, D, C, out_dtype=torch.bfloat16, qema=qema, beta=0.9) for (N, D, C) in shapes]
+        side = torch.cuda.Stream()
+        torch.cuda.synchronize()
+        for rep in range(2):                                 # the second round also exercises the EMA update
+            for st, (X, W, dY) in zip(steps, dev_data):
+                if two:
+                    st.step_two_streams(X, W, dY, 33 + rep, side)
+                else:
+                    st.forward(X, W, 33 + rep)
+                    st.backward(dY, 33 + rep)
+        torch.cuda.synchronize()
+        return [[getattr(st, n).clone() for n in names] for st in steps]
+
+    one, two = run(False), run(True)
+    for a_layer, b_layer in zip(one, two):
+        for n, u, v in zip(names, a_layer, b_layer):
+            assert torch.equal(u, v), n
+    if not qema:
+        xt, wt, dy = oracle_layer(orc, *data[0], seed=34)
+        got = dict(zip(names, two[0]))
+        assert_same_bytes(got["xtq"], xt[0], "Q6 under the two-stream schedule")
+        assert_same_bytes(got["dytq"], dy[0], "Q5 under the two-stream schedule")
+        assert_same_bytes(got["wtq"], wt[0], "Q4 under the two-stream schedule")
+
+
 # ------------------------------------------------- full size, bench launch configuration ----
 
 @pytest.mark.parametrize("layer", ["qkv", "proj", "fc1", "fc2"])
