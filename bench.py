@@ -19,6 +19,69 @@ PEAK_FP4_TFLOPS = 10100.0      # MI355X dense FP4/FP6 matrix peak
 PEAK_HBM_GBS = 8000.0
 
 
+class BoardPower:
+    """Board power of GPU 0 from the amdgpu hwmon files (microwatts), sampled by a thread every 10 ms.
+    Reading the files touches neither the HIP runtime nor the streams; where they are absent every
+    figure is None."""
+
+    def __init__(self):
+        import glob
+        self.path = self.cap_w = None
+        for h in sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*")):
+            for name in ("power1_input", "power1_average"):
+                if self.path is None and os.path.exists(os.path.join(h, name)):
+                    self.path = os.path.join(h, name)
+            cap = os.path.join(h, "power1_cap")
+            if self.cap_w is None and os.path.exists(cap):
+                try:
+                    self.cap_w = int(open(cap).read()) / 1e6
+                except (OSError, ValueError):
+                    pass
+        self.samples, self._stop, self._thread = [], False, None
+
+    def _read(self):
+        try:
+            return int(open(self.path).read()) / 1e6
+        except (OSError, ValueError, TypeError):
+            return None
+
+    def start(self):
+        import threading
+        self.samples, self._stop = [], False
+
+        def loop():
+            while not self._stop:
+                w = self._read()
+                if w is not None:
+                    self.samples.append((time.perf_counter(), w))
+                time.sleep(0.01)
+        if self.path is not None:
+            self._thread = threading.Thread(target=loop, daemon=True)
+            self._thread.start()
+
+    def stop(self, since=None):
+        """Mean watts of the samples taken after `since` (a perf_counter value), or None."""
+        self._stop = True
+        if self._thread is not None:
+            self._thread.join()
+            self._thread = None
+        w = [x for (t, x) in self.samples if since is None or t >= since]
+        return round(sum(w) / len(w), 1) if w else None
+
+    def watts_of(self, fn, sync, seconds=0.4):
+        """Mean board power while fn() is issued back to back for `seconds` (the first third is left out)."""
+        if self.path is None:
+            return None
+        sync()
+        self.start()
+        t0 = time.perf_counter()
+        while time.perf_counter() - t0 < seconds:
+            for _ in range(4):
+                fn()
+            sync()
+        return self.stop(since=t0 + seconds / 3)
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -44,6 +107,9 @@ def parse():
                     help="untimed steps are run for this long before the W warm-up steps: after the idle time of input "
                          "generation the chip needs about 100 ms of load before its clocks settle (the first steps "
                          "run 5 %% slower), which W = 3..5 steps (7 ms) do not provide")
+    ap.add_argument("--no-power", action="store_true",
+                    help="skip the board-power loops after the timed region (for profiler runs: 0.4 s of back-to-back "
+                         "launches per kernel family would swamp the per-kernel statistics)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference dispatch for scaling rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters)")
@@ -156,6 +222,8 @@ def main():
         del src, dst
 
     timed_side = side_stream if args.streams == 2 else None
+    board = BoardPower()
+    board.start()                          # sampled through the settle phase, the warm-up and the timed steps
     t_settle = time.perf_counter()
     while (time.perf_counter() - t_settle) * 1e3 < args.settle_ms:
         for w in range(5):
@@ -175,6 +243,7 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt * 1e3 / args.steps
+    step_watts = board.stop(since=t_settle + 0.1)
 
     # the same steps under the other schedule, after the timed region, for comparison: with two
     # streams the tails of the products overlap the next kernels, but a kernel's event-to-event time
@@ -262,6 +331,33 @@ def main():
         e1.record()
         torch.cuda.synchronize()
         mfma_cal[key] = round(fl / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
+    # Board power (amdgpu hwmon) while one kernel family runs back to back for 0.4 s each, against the board's
+    # power cap: the products, the quantizers and the calibration loop each draw close to the cap on their
+    # own, which is what sets the shader clock they run at.
+    def products_only():
+        B = mx.binding
+        for st in steps_obj:
+            B.mx_linear_fwd(st.xq, st.xs, st.wq, st.ws, out=st.y, workspace=st.workspace)
+            B.mx_linear_bwd_dx(st.dyq, st.dys, st.wtq, st.wts, out=st.dx, workspace=st.workspace)
+            B.mx_linear_bwd_dw(st.dytq, st.dyts, st.xtq, st.xts, out=st.dw, workspace=st.workspace)
+
+    def quantizers_only():
+        B = mx.binding
+        for st, (X, W, dY) in zip(steps_obj, inputs):
+            st.quantize_inputs(X, W, 7)
+            B.mx_quantize_transposed(dY, B.ROUND_SR, 5, 0, True, B.ROUND_SR, 3, seed=7, out=(st.dytq, st.dyts, st.dyq, st.dys))
+
+    sync = torch.cuda.synchronize
+    if args.no_power:
+        board.path = None
+    power = {"unit": "W", "source": "amdgpu hwmon power1_input, 10 ms samples", "cap": board.cap_w,
+             "whole_step": step_watts,
+             "products_only": board.watts_of(products_only, sync),
+             "quantizers_only": board.watts_of(quantizers_only, sync),
+             "calibration_mfma_constant_bytes": board.watts_of(
+                 lambda: mx.binding.mx_calibration_mfma(cal_inputs["constant_bytes_0x22"], n_cu, 2000, cal_sink), sync),
+             "calibration_mfma_quantized_codes": board.watts_of(
+                 lambda: mx.binding.mx_calibration_mfma(cal_inputs["quantized_activation_codes"], n_cu, 2000, cal_sink), sync)}
     mfma_cal.update({"unit": "TFLOP/s", "kernel": "calibration_mfma_kernel", "workgroups": n_cu, "waves_per_simd": 2,
                      "note": "register-resident V_MFMA_SCALE_F32_32X32X64_F8F6F4 loop; calibration only, not the roofline peak"})
 
@@ -413,6 +509,18 @@ def main():
     quant_ms = sum(a.elapsed_time(b) for a, b in quant_events) / n_recorded
     n_gemm = 3 * len(layers)
     achieved = total_flops / (gemm_ms * 1e-3) / 1e12
+    # the same kernel without launch gaps and neighbours' tails: its average duration in a rocprofv3
+    # kernel trace of this command (profiles/gemm_kernel_only.json), the figure the committed summary shows
+    kernel_only = None
+    kj = os.path.join(ROOT, "profiles", "gemm_kernel_only.json")
+    if os.path.exists(kj) and args.workload == "vit_base_b256" and args.tokens is None:
+        try:
+            ko = json.load(open(kj))
+            ko_tf = total_flops / n_gemm / (ko["avg_launch_us"] * 1e-6) / 1e12
+            kernel_only = {"avg_launch_us": ko["avg_launch_us"], "achieved": ko_tf, "frac": ko_tf / PEAK_FP4_TFLOPS,
+                           "source": "profiles/gemm_kernel_only.json (rocprofv3 --kernel-trace of this command)"}
+        except Exception:
+            kernel_only = None
     traffic = None
     if os.path.exists(args.traffic_json):
         try:
@@ -476,8 +584,12 @@ def main():
         "roofline": {"bound": "mfma", "kernel": "mx_gemm_pingpong_kernel<false> (12 launches per step)",
                      "achieved": achieved, "peak": PEAK_FP4_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_FP4_TFLOPS,
+                     "timing": "HIP events around each product on its stream, live in this run: event to event, "
+                               "i.e. with the launch gap and, for a K-split product, its reduction kernel",
                      "flops_per_launch": total_flops / n_gemm, "avg_launch_ms": gemm_ms / n_gemm,
+                     "kernel_only": kernel_only,
                      "traffic": traffic},
+        "power": power,
         "quantizers": {"bound": "hbm", "achieved": q_bytes / (quant_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
                        "unit": "GB/s", "frac": q_bytes / (quant_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
                        "ms_per_step": quant_ms, "bytes_per_step": q_bytes, "alu": quant_alu},
