@@ -1385,11 +1385,12 @@ hipError_t launch_calibration_mfma(const uint8_t* operands, int workgroups, int 
 
 int gemm_split_k(int64_t m, int64_t n, int64_t k)
 {
-    // Split K only when the output has too few tiles to fill the machine and K is long.
-    // The fast kernel runs two 256 x 128 workgroups per CU: 512 slots on 256 CUs; the
-    // split is the largest that still fits in one round of slots.
+    // Split K only when the output has too few tiles to fill the machine and K is long.  A split
+    // product runs in the main kernel (at least 8 K steps per split): one 256 x 256 workgroup per
+    // CU, 256 slots; the split is the largest that still fits in one round of slots, so that
+    // every partial tile is written once and the second, emptier round does not exist.
     const bool fast = (k & 127) == 0;
-    const int64_t bm = fast ? D_BM : G_BM, bn = fast ? D_BN : G_BN, slots = fast ? 512 : 256;
+    const int64_t bm = fast ? Q_BM : G_BM, bn = fast ? Q_BN : G_BN, slots = 256;
     int64_t tiles = ((m + bm - 1) / bm) * ((n + bn - 1) / bn);
     if (tiles * 2 > slots || k < 4096) return 1;
     int64_t s = slots / tiles;
