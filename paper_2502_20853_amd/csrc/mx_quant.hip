@@ -327,7 +327,13 @@ __global__ __launch_bounds__(TILE_THREADS, 4) void quantize_tile_kernel(TileBatc
     // macro tile of this workgroup (uniform): a wide one, or one half of a wide one
     const bool wide = block < a.n_wide;
     const uint32_t narrow = wide ? 0u : block - a.n_wide;
-    const uint32_t wide_index = wide ? block : a.n_wide + (narrow >> 1);
+    // Workgroup ids go round the 8 XCDs, each with its own L2.  A macro tile writes 4 scale bytes per row
+    // and 8 per column: a 32-byte sector of a scale array is completed by up to 8 tiles side by side, or 4
+    // on top of each other.  Each XCD therefore takes a contiguous range of the row-major tile order, so
+    // that the tiles which share sectors meet in one L2 and the sectors leave it whole.
+    const uint32_t xcd_class = block & 7u, per_xcd = a.n_wide >> 3, rem_xcd = a.n_wide & 7u;
+    const uint32_t wide_index = wide ? xcd_class * per_xcd + min(xcd_class, rem_xcd) + (block >> 3)
+                                     : a.n_wide + (narrow >> 1);
     const uint32_t row_block = wide_index / a.wide_per_row;
     const int tiles_per_wave = wide ? 2 : 1;
     const uint32_t macro_rows = 256u, macro_cols = 64u * tiles_per_wave;
