@@ -114,6 +114,27 @@ def write_step_kernels(out_dir):
                "reduction_avg_us": (red[0][1] / red[0][0]) if red else None, "reductions_per_step": 4,
                "source": "rocprofv3 --kernel-trace of bench.py (profiles/vit_base_b256_step_kernels.md)"},
               open(os.path.join(PROFILES, "gemm_kernel_only.json"), "w"), indent=1)
+    # fused quantizer launches: counter traffic against the algorithmic bytes (bf16 source read once; codes
+    # 0.5 B and scale 1/32 B per element, in both layouts)
+    known = {1340: ("dY-type 50432x768", 50432 * 768), 3546: ("dY-type 50432x2304", 50432 * 2304),
+             4848: ("dY-type 50432x3072", 50432 * 3072), 1376: ("X-type 50432x768 + weight", 50432 * 768 + 768 * 768),
+             4992: ("X-type 50432x3072 + weight", 50432 * 3072 + 768 * 3072),
+             1448: ("X-type 50432x768 + weight 2304x768", 50432 * 768 + 2304 * 768),
+             1484: ("X-type 50432x768 + weight 3072x768", 50432 * 768 + 3072 * 768)}
+    qrows = collections.OrderedDict()
+    fd, wd = _dispatches(fetch), _dispatches(write)
+    for ef, ew in zip(fd, wd):
+        if "quantize_tile_kernel" not in ef["name"] or ef["grid"] // 512 not in known or ef["grid"] != ew["grid"]:
+            continue
+        label, elements = known[ef["grid"] // 512]
+        q = qrows.setdefault(label, [elements, [], []])
+        q[1].append(ef["FETCH_SIZE"] * 1024 * ff)
+        q[2].append(ew["WRITE_SIZE"] * 1024 * wf)
+    qlines = ["| fused quantizer launch | read MB (counter) | algorithmic | write MB (counter) | algorithmic | write / algorithmic |", "|---|---|---|---|---|---|"]
+    for label, (elements, fr, wr_) in qrows.items():
+        r_, w_ = sum(fr) / len(fr), sum(wr_) / len(wr_)
+        qlines.append("| %s | %.1f | %.1f | %.1f | %.1f | %.3f |" % (label, r_ / 1e6, elements * 2 / 1e6, w_ / 1e6,
+                                                                 elements * 1.0625 / 1e6, w_ / (elements * 1.0625)))
     n_par = 12 * (2304 * 768 + 768 * 768 + 3072 * 768 + 768 * 3072)
     opt = []
     for ok, label in (("ramping_adamw_kernel<float, true>", "with factors (56 B/element algorithmic)"),
@@ -140,6 +161,11 @@ Scaled HBM traffic of the dominant kernel (%s), average per launch over the 12 p
 read %.1f MB + write %.1f MB = %.1f MB (profiles/gemm_traffic.json, read by bench.py).
 Kernel-only average duration of that kernel: %.1f us over %d launches (profiles/gemm_kernel_only.json, read by bench.py).
 
+Scaled HBM traffic of the fused quantizer launches of a step (quantize_tile_kernel; every workgroup stages its codes
+and scale bytes in LDS and each XCD takes a contiguous range of the tile order, so that sectors leave L2 whole):
+
+%s
+
 After its timed region the same command also measures the kernels beyond the layer (Q-EMA, oscillation
 detection, diagnostics, the MLP fusion comparison, the MFMA calibration loop and the optimizer step on the %d
 weight elements of a 12-block model); scaled HBM traffic of the optimizer kernel:
@@ -150,7 +176,7 @@ weight elements of a 12-block model); scaled HBM traffic of the optimizer kernel
 %s
 ```
 """ % (CMD["trace"], CMD["fetch"], CMD["write"], SUMMARISE, gem[0] // 12, cal_f, cal_w, ff, wf, gk, rd / 1e6, wr / 1e6, (rd + wr) / 1e6,
-       gem[1] / gem[0], gem[0], n_par, "\n".join(opt), table)
+       gem[1] / gem[0], gem[0], "\n".join(qlines), n_par, "\n".join(opt), table)
     open(os.path.join(PROFILES, "vit_base_b256_step_kernels.md"), "w").write(md)
     return md
 
