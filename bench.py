@@ -408,6 +408,31 @@ def main():
             mlp_fusion[key] = round(e0.elapsed_time(e1) / 10 * 1e3, 1)
         del act
 
+    # E3M0 element codec of the format ablation (Table 7), outside the timed region: the row quantizer on the
+    # largest activation of the block, both rounding rules, next to the E2M1 row quantizer on the same tensor
+    # (algorithmic bytes: source + 0.5 B codes + 1/32 B scales per element)
+    e3m0 = []
+    Xl = max((X for (X, _, _) in inputs), key=lambda t: t.numel())
+    qb_row = Xl.numel() * (Xl.element_size() + 0.5 + 1.0 / 32)
+    e3_out = (torch.empty((Xl.shape[0], Xl.shape[1] // 2), dtype=torch.uint8, device="cuda"),
+              torch.empty((Xl.shape[0], Xl.shape[1] // 32), dtype=torch.uint8, device="cuda"))
+    for label, fn in (("e3m0 round_D", lambda: mx.binding.mx_quantize_e3m0(Xl, mx.binding.ROUND_RTN, out=e3_out)),
+                      ("e3m0 round_S", lambda: mx.binding.mx_quantize_e3m0(Xl, mx.binding.ROUND_SR, seed=9, tensor_id=6, out=e3_out)),
+                      ("e2m1 round_D", lambda: mx.binding.mx_quantize(Xl, mx.binding.ROUND_RTN, out=e3_out)),
+                      ("e2m1 round_S", lambda: mx.binding.mx_quantize(Xl, mx.binding.ROUND_SR, seed=9, tensor_id=6, out=e3_out))):
+        for _ in range(2):
+            fn()
+        e0, e1 = ev(), ev()
+        e0.record()
+        for _ in range(10):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / 10 * 1e3
+        e3m0.append({"op": label, "shape": list(Xl.shape), "us": round(us, 1), "GB/s": round(qb_row / us / 1e3, 1),
+                     "hbm_frac": round(qb_row / us / 1e3 / PEAK_HBM_GBS, 3)})
+    del e3_out
+
     # Q-EMA weight quantizer (Sec. 5), outside the timed region: the four weights of the block, one
     # update + quantization each, as a training step with Q-EMA would issue them
     qema = []
@@ -598,6 +623,7 @@ def main():
         "launches": launches,
         "forward_with_bias": fwd_bias,
         "mlp_fusion": mlp_fusion,
+        "e3m0_codec": e3m0,
         "qema_weight_quant": qema,
         "oscillation_detection": osc,
         "other_schedule": None if other_ms is None else {
