@@ -365,7 +365,10 @@ def main():
     # in fc1's output stage, fc2's Q6 from the packed codes) against the separate calls (forward product with
     # bias, an element-wise GELU kernel, the fused Q1/Q6 quantizer reading the activation)
     mlp_fusion = None
-    if not args.no_other_schedule and [n for (n, _, _, _) in layers[2:4]] == ["fc1", "fc2"]:
+    # (the fused stage lives in the main product kernel: K a multiple of 128, at least 512, output width % 32)
+    fusable = (len(layers) >= 4 and [n for (n, _, _, _) in layers[2:4]] == ["fc1", "fc2"]
+               and layers[2][2] % 128 == 0 and layers[2][2] >= 512 and layers[2][3] % 32 == 0)
+    if not args.no_other_schedule and fusable:
         (_, N1, D1, C1), st1, st2 = layers[2], steps_obj[2], steps_obj[3]
         bias1 = torch.randn(C1, device="cuda") * 0.1
         gelu = torch.nn.functional.gelu
